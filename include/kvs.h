@@ -1,0 +1,203 @@
+/*
+ * kvs.h -- C ABI of the MI355X (gfx950) library for the DHD KV-reuse hot path of KVShare
+ * (Dual-Stage High Deviation token selection, Alg. 1 / Eq. (3); partial recomputation,
+ * App. A; decode-stage re-check, Sec. 4.2).
+ *
+ * Conventions shared by every call
+ * --------------------------------
+ * Pointers marked [dev] are device (HBM) addresses, pointers marked [host] are ordinary host
+ * memory that is read before the call returns.  The caller owns every buffer; the library
+ * allocates nothing, keeps no state between calls, and never synchronises: each call checks
+ * its arguments on the host, enqueues its kernels on `stream` (a hipStream_t passed as
+ * void*, NULL = the default stream) and returns.  Outputs are valid in stream order.
+ *
+ * Layouts are row-major and contiguous:
+ *   K, V        [rows, n_kv_heads, head_dim]   element type given by kvs_shape.dtype
+ *   Q           [rows, n_q_heads,  head_dim]
+ *   dev_k/dev_v [n_kv_heads, rows] fp32        per-token, per-KV-head L1 deviation
+ *   alpha       [n_kv_heads, rows] fp32        attention column mass, summed over the query
+ *                                              heads that share the KV head
+ *   score       [rows] fp32                    -inf for tokens that are not candidates
+ * Query head h reads KV head h / (n_q_heads / n_kv_heads).  K/V/Q base addresses must be
+ * 16-byte aligned.
+ *
+ * Errors: every function returns a kvs_status.  Argument errors are detected on the host
+ * before anything is enqueued (KVS_EINVAL: NULL required pointer, negative size, k larger
+ * than its row, n_q_heads not a multiple of n_kv_heads, unsorted offsets; KVS_EUNSUPPORTED:
+ * head_dim/dtype combination that has no kernel; KVS_EWORKSPACE: workspace too small;
+ * KVS_EHIP: the HIP runtime refused a launch).  kvs_last_error() returns a thread-local
+ * description of the most recent failure.  Nothing throws or aborts across this boundary.
+ *
+ * Supported shapes: dtype KVS_BF16 or KVS_F32; head_dim 64 or 128; n_kv_heads * head_dim *
+ * sizeof(element) a multiple of 256 bytes.
+ */
+#ifndef KVS_H
+#define KVS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define KVS_API __attribute__((visibility("default")))
+
+typedef enum {
+    KVS_OK = 0,
+    KVS_EINVAL = 1,
+    KVS_EUNSUPPORTED = 2,
+    KVS_EWORKSPACE = 3,
+    KVS_EHIP = 4
+} kvs_status;
+
+typedef enum { KVS_F32 = 0, KVS_BF16 = 1 } kvs_dtype;
+
+/* KVS_SCORE_V is the paper's score (value deviation only, Sec. 4.1 drops the key term);
+ * KVS_SCORE_KV adds the key deviation's L1 norm under the same weight. */
+typedef enum { KVS_SCORE_V = 0, KVS_SCORE_KV = 1 } kvs_score_mode;
+
+typedef struct {
+    int32_t n_q_heads;
+    int32_t n_kv_heads;
+    int32_t head_dim;
+    int32_t dtype; /* kvs_dtype */
+} kvs_shape;
+
+/*
+ * kvs_deviation -- Alg. 1 step 3 / Eq. (3): the deviation impact score of every token.
+ *
+ *   dev_v[g,i] = sum_c | v_fresh[i,g,c] - v_cache[i,g,c] |        (L1 norm of Delta V_i on head g)
+ *   dev_k[g,i] likewise on K (computed when mode == KVS_SCORE_KV or dev_k != NULL)
+ *   score[i]   = sum_g alpha[g,i] * dev_v[g,i]                    mode KVS_SCORE_V
+ *              = sum_g alpha[g,i] * (dev_k[g,i] + dev_v[g,i])     mode KVS_SCORE_KV
+ *   score[i]   = -inf where reused[i] == 0 (the token was computed fresh, nothing to repair)
+ *
+ * n_tokens            rows of every tensor (0 is allowed: nothing is launched)
+ * k_fresh, k_cache    [dev] may be NULL in mode KVS_SCORE_V with dev_k == NULL
+ * v_fresh, v_cache    [dev] required
+ * reused              [dev] uint8[n_tokens], NULL = every token is a candidate
+ * alpha               [dev] fp32[n_kv_heads, n_tokens], NULL = 1 (magnitude-only ranking)
+ * dev_k, dev_v, score [dev] outputs; each may be NULL if not wanted
+ * All arithmetic is fp32 on exactly widened inputs, in a fixed order (bit-reproducible).
+ */
+KVS_API kvs_status kvs_deviation(const kvs_shape *shape, int64_t n_tokens,
+                         const void *k_fresh, const void *v_fresh,
+                         const void *k_cache, const void *v_cache,
+                         const uint8_t *reused, const float *alpha, int32_t mode,
+                         float *dev_k, float *dev_v, float *score, void *stream);
+
+/*
+ * kvs_select_topk -- Alg. 1 step 4: the k highest-scoring entries of each row.
+ *
+ * Row r of the ragged matrix is scores[row_off[r] .. row_off[r+1]).  The k_row[r] entries
+ * that come first in the order (score descending, index ascending) are written as row-local
+ * int32 indices, in ascending index order, at idx_out + sum(k_row[0..r)).  Scores compare as
+ * real numbers (-0 equals +0); -inf entries rank last (still by index); NaN scores are a
+ * caller error with unspecified (but memory-safe) results.  The result is exact and
+ * deterministic.
+ *
+ * scores   [dev] fp32            row_off [host] int64[n_rows+1], non-decreasing
+ * k_row    [host] int32[n_rows], 0 <= k_row[r] <= row length; rows longer than 2^31-1 are
+ *          rejected
+ * idx_out  [dev] int32[sum k_row]
+ * workspace [dev] at least kvs_workspace_size("select_topk", ...) bytes, 256-byte aligned
+ */
+KVS_API kvs_status kvs_select_topk(const float *scores, int32_t n_rows, const int64_t *row_off,
+                           const int32_t *k_row, int32_t *idx_out,
+                           void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * kvs_scatter_kv -- the KV Writer of App. A: recomputed K/V replace the reused entries.
+ *
+ *   k_cache[sel_pos[s]] = k_new[s],  v_cache[sel_pos[s]] = v_new[s]      for s in [0, n_sel)
+ *   reused[sel_pos[s]] = 0           (if reused != NULL)  the token is no longer a candidate
+ *   dev_v[g, sel_pos[s]] = 0         (if dev_v  != NULL)  its stored deviation is repaired
+ *
+ * n_rows     rows of the cache (and row stride of dev_v)
+ * k_new,v_new [dev] [n_sel, n_kv_heads, head_dim]
+ * sel_pos    [dev] int32[n_sel], global cache rows in [0, n_rows), all distinct (duplicates
+ *            race: one of the writers wins per 16-byte piece)
+ */
+KVS_API kvs_status kvs_scatter_kv(const kvs_shape *shape, int64_t n_rows,
+                          const void *k_new, const void *v_new,
+                          const int32_t *sel_pos, int64_t n_sel,
+                          void *k_cache, void *v_cache, uint8_t *reused, float *dev_v,
+                          void *stream);
+
+/*
+ * kvs_partial_attention -- Eq. (1) restricted to the rows of the selected tokens (App. A:
+ * only the selected tokens are computed, the others' KV is reused).
+ *
+ * Request b owns cache rows [ctx_off[b], ctx_off[b] + ctx_len[b]) and the selected tokens
+ * [cu_sel[b], cu_sel[b+1]).  Selected token s sits at request-local position p = sel_pos[s]
+ * and its query head h attends causally, by that original position, over the cache as it
+ * stands (recomputed rows already scattered in):
+ *
+ *   out[s,h,:] = sum_{i <= p} softmax_i( scale * q_sel[s,h,:] . K[ctx_off[b]+i, g(h), :] )
+ *                             * V[ctx_off[b]+i, g(h), :]
+ *   lse[s,h]   = log sum_{i <= p} exp( scale * q . K_i )          (natural log; optional)
+ *
+ * ctx_off, ctx_len [host] int64[batch];  cu_sel [host] int64[batch+1], non-decreasing
+ * q_sel   [dev] [n_sel, n_q_heads, head_dim]         sel_pos [dev] int32[n_sel], ascending
+ *         within each request, each in [0, ctx_len[b])
+ * out     [dev] [n_sel, n_q_heads, head_dim] in the shape's dtype
+ * lse_out [dev] fp32[n_sel, n_q_heads] or NULL
+ * bf16 inputs are contracted on the matrix cores with fp32 accumulation and an fp32 online
+ * softmax; fp32 inputs take an fp32 vector path.
+ */
+KVS_API kvs_status kvs_partial_attention(const kvs_shape *shape, int32_t batch,
+                                 const int64_t *ctx_off, const int64_t *ctx_len,
+                                 const int64_t *cu_sel,
+                                 const void *q_sel, const int32_t *sel_pos,
+                                 const void *k_cache, const void *v_cache, float scale,
+                                 void *out, float *lse_out,
+                                 void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * kvs_decode_check -- Sec. 4.2: Alg. 1 re-run in the decode stage with alpha replaced by the
+ * decoding token's current attention over the cache.
+ *
+ * For request b (its new token's K/V already appended, context ctx_len[b] rows):
+ *   a[h,i]   = softmax_{i in [0, ctx_len[b])}( scale * q_new[b,h,:] . K[ctx_off[b]+i, g(h), :] )
+ *   score[i] = sum_g ( sum_{h in group g} a[h,i] ) * dev_v[g, ctx_off[b]+i]   if reused, else -inf
+ * and the k_req[b] best candidates (same order and tie rule as kvs_select_topk) are written
+ * as ascending request-local indices at idx_out + sum(k_req[0..b)).
+ *
+ * n_rows    rows of the packed cache (row stride of dev_v, length of reused / score_out)
+ * q_new     [dev] [batch, n_q_heads, head_dim]
+ * v_cache   [dev] only read when attn_out != NULL
+ * dev_v     [dev] fp32[n_kv_heads, n_rows] as left by kvs_deviation / kvs_scatter_kv
+ * reused    [dev] uint8[n_rows] or NULL (all candidates)
+ * k_req     [host] int32[batch], 0 <= k_req[b] <= ctx_len[b]
+ * score_out [dev] fp32[n_rows] or NULL; rows outside the contexts are not written
+ * attn_out  [dev] [batch, n_q_heads, head_dim] (shape dtype) or NULL: sum_i a[h,i] * V_i
+ */
+KVS_API kvs_status kvs_decode_check(const kvs_shape *shape, int32_t batch, int64_t n_rows,
+                            const int64_t *ctx_off, const int64_t *ctx_len,
+                            const void *q_new, const void *k_cache, const void *v_cache,
+                            const float *dev_v, const uint8_t *reused, float scale,
+                            const int32_t *k_req, int32_t *idx_out, float *score_out,
+                            void *attn_out,
+                            void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Workspace a call needs, in bytes, for the given problem.  `call` is "select_topk",
+ * "partial_attention" or "decode_check" (anything else returns 0).  n_rows_total is the total
+ * number of score / cache rows the call will see, n_sel_total the total number of selected
+ * tokens (partial_attention only).  The answer is an upper bound valid for any split of the
+ * totals over `batch` requests.
+ */
+KVS_API size_t kvs_workspace_size(const char *call, const kvs_shape *shape, int32_t batch,
+                          int64_t n_rows_total, int64_t n_sel_total);
+
+KVS_API const char *kvs_strerror(kvs_status status);
+KVS_API const char *kvs_last_error(void);
+
+/* Library build identification: "kvshare-hip gfx950 <n>" */
+KVS_API const char *kvs_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KVS_H */

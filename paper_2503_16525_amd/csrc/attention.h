@@ -1,0 +1,32 @@
+// Internal declarations shared by the attention translation units (not part of the ABI).
+#pragma once
+
+#include "kvs_internal.h"
+
+namespace kvs {
+
+constexpr int kAttnMaxReq = 64; // requests described per launch (passed by value as a kernel argument)
+
+// Host-side request table, copied into the kernel's argument block: no device allocation, no
+// asynchronous host-to-device copy whose source would have to outlive the call.
+struct AttnBatch {
+    int64_t ctx_off[kAttnMaxReq];     // first cache row of request b
+    int64_t ctx_len[kAttnMaxReq];     // context rows of request b
+    int64_t cu_sel[kAttnMaxReq + 1];  // selected tokens of request b: [cu_sel[b], cu_sel[b+1]) (global numbering)
+    int64_t sel_begin;                // first selected token covered by this launch (= cu_sel[0])
+    int32_t n_req;
+};
+
+kvs_status launch_attention_valu(const kvs_shape *shape, const AttnBatch &bd, int64_t n_sel,
+                                 const void *q_sel, const int32_t *sel_pos, const void *k_cache,
+                                 const void *v_cache, float scale, void *out, float *lse_out,
+                                 hipStream_t st);
+
+// bf16, head_dim 128 matrix-core path; returns KVS_EUNSUPPORTED for shapes it does not cover
+kvs_status launch_attention_mfma(const kvs_shape *shape, const AttnBatch &bd, int64_t n_sel,
+                                 const void *q_sel, const int32_t *sel_pos, const void *k_cache,
+                                 const void *v_cache, float scale, void *out, float *lse_out,
+                                 hipStream_t st);
+bool attention_mfma_supports(const kvs_shape *shape);
+
+} // namespace kvs

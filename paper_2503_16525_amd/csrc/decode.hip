@@ -1,0 +1,325 @@
+// kvs_decode_check: decode-stage re-scoring of the reuse candidates (Sec. 4.2).  The new
+// token's attention row over its whole context replaces the prefill column mass of Alg. 1:
+//     score_i = sum_g ( sum_{h in g} softmax_i(scale * q_h . K_i) ) * dev_v[g,i]
+//
+// Kernels, all on the caller's stream:
+//   1. logits     streams K once (16-byte pieces, LPH lanes per (token, kv head) cell, DPP
+//                 reduction as in the deviation kernel) and writes scale*q.K for every query head
+//                 to the workspace as fp32 [n_q_heads][n_rows];
+//   2. stats      per (request, head): softmax max and normaliser over the context;
+//   3. score      per token: normalised weights summed per group, times the stored deviation,
+//                 masked to the candidates;
+//   4. select     the same exact top-k kernel as kvs_select_topk, one row per request;
+//   5. attn_out   (optional) sum_i a[h,i] * V_i.
+#include "kvs_internal.h"
+#include "attention.h"
+
+#include <math.h>
+
+namespace kvs {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kTok = 32;          // tokens per workgroup in the logits kernel
+constexpr int kMaxReq = kAttnMaxReq;
+
+struct DecodeBatch {
+    int64_t ctx_off[kMaxReq];
+    int32_t ctx_len[kMaxReq];
+    int32_t tile_begin[kMaxReq + 1];  // first token tile (of kTok) of request b in this launch's grid
+    int32_t req0;                     // global index of the first request of this launch
+    int32_t n_req;
+};
+
+// ---- 1. logits --------------------------------------------------------------------------------
+// LPH lanes per cell (head_dim * elem / 16 bytes); EPL = elements per 16-byte piece.
+template <int DTYPE, int LPH>
+__global__ __launch_bounds__(kThreads) void decode_logits_kernel(
+    const DecodeBatch bd, int n_q_heads, int n_kv_heads, int64_t n_rows,
+    const void *__restrict__ q_new, const uint4 *__restrict__ k_cache, float scale,
+    float *__restrict__ logits)
+{
+    constexpr int EPL = DTYPE == KVS_BF16 ? 8 : 4;
+    constexpr int D = LPH * EPL;
+    extern __shared__ float lds[];
+    float *q_s = lds;                              // [n_q_heads][D], pre-multiplied by scale
+    float *lg_s = lds + n_q_heads * D;             // [n_q_heads][kTok]
+
+    int b = 0;
+    while (b + 1 < bd.n_req && (int)blockIdx.x >= bd.tile_begin[b + 1]) ++b;
+    const int tile = blockIdx.x - bd.tile_begin[b];
+    const int len = bd.ctx_len[b];
+    const int tok0 = tile * kTok;
+    const int tile_tok = min(kTok, len - tok0);
+    const int64_t row0 = bd.ctx_off[b] + tok0;
+    const int grp = n_q_heads / n_kv_heads;
+    const int tid = threadIdx.x;
+
+    for (int e = tid; e < n_q_heads * D; e += kThreads) {
+        const int64_t gi = (int64_t)(bd.req0 + b) * n_q_heads * D + e;
+        float v;
+        if (DTYPE == KVS_F32) v = ((const float *)q_new)[gi];
+        else v = __uint_as_float((uint32_t)((const uint16_t *)q_new)[gi] << 16);
+        q_s[e] = v * scale;
+    }
+    __syncthreads();
+
+    constexpr int CPB = kThreads / LPH;             // cells per step
+    const int sub = tid % LPH, cell_in_step = tid / LPH;
+    const int tile_cells = tile_tok * n_kv_heads;
+    for (int base = 0; base < tile_cells; base += CPB) {
+        const int c = base + cell_in_step;
+        const bool live = c < tile_cells;
+        const int t = live ? c / n_kv_heads : 0;
+        const int g = live ? c - t * n_kv_heads : 0;
+        float kx[EPL];
+        if (live) {
+            const uint4 w = stream_load16(k_cache + ((row0 + t) * n_kv_heads + g) * LPH + sub);
+            if constexpr (DTYPE == KVS_BF16) {
+                kx[0] = bf16_lo(w.x); kx[1] = bf16_hi(w.x); kx[2] = bf16_lo(w.y); kx[3] = bf16_hi(w.y);
+                kx[4] = bf16_lo(w.z); kx[5] = bf16_hi(w.z); kx[6] = bf16_lo(w.w); kx[7] = bf16_hi(w.w);
+            } else {
+                kx[0] = __uint_as_float(w.x); kx[1] = __uint_as_float(w.y);
+                kx[2] = __uint_as_float(w.z); kx[3] = __uint_as_float(w.w);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < EPL; ++i) kx[i] = 0.f;
+        }
+        for (int hh = 0; hh < grp; ++hh) {
+            const float *qh = q_s + (g * grp + hh) * D + sub * EPL;
+            float acc = 0.f;
+#pragma unroll
+            for (int i = 0; i < EPL; ++i) acc += qh[i] * kx[i];
+            // reduce over the LPH lanes of the cell (every lane of the wave takes part)
+            if (LPH == 16) acc = row16_sum(acc);
+            else if (LPH == 32) { acc = row16_sum(acc); acc += __shfl_xor(acc, 16); }
+            else { acc += __shfl_xor(acc, 4); acc += __shfl_xor(acc, 2); acc += __shfl_xor(acc, 1); }
+            if (live && sub == 0) lg_s[(g * grp + hh) * kTok + t] = acc;
+        }
+    }
+    __syncthreads();
+    for (int e = tid; e < n_q_heads * kTok; e += kThreads) {
+        const int h = e / kTok, t = e % kTok;
+        if (t < tile_tok) logits[(int64_t)h * n_rows + row0 + t] = lg_s[e];
+    }
+}
+
+// ---- 2. softmax statistics per (request, head) ---------------------------------------------------
+__global__ __launch_bounds__(kThreads) void decode_stats_kernel(
+    const DecodeBatch bd, int n_q_heads, int64_t n_rows, const float *__restrict__ logits,
+    float2 *__restrict__ stats /* [batch][n_q_heads] (max, sum) */)
+{
+    __shared__ float red[kThreads / 64];
+    __shared__ float bc;
+    const int b = blockIdx.x / n_q_heads, h = blockIdx.x % n_q_heads;
+    const int len = bd.ctx_len[b];
+    const float *row = logits + (int64_t)h * n_rows + bd.ctx_off[b];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    float m = -INFINITY;
+    for (int i = tid; i < len; i += kThreads) m = fmaxf(m, row[i]);
+    m = wave_max(m);
+    if (lane == 0) red[wave] = m;
+    __syncthreads();
+    if (tid == 0) { float x = red[0]; for (int w = 1; w < kThreads / 64; ++w) x = fmaxf(x, red[w]); bc = x; }
+    __syncthreads();
+    m = bc;
+    float z = 0.f;
+    for (int i = tid; i < len; i += kThreads) z += expf(row[i] - m);
+    z = wave_sum(z);
+    __syncthreads();
+    if (lane == 0) red[wave] = z;
+    __syncthreads();
+    if (tid == 0) {
+        float x = 0.f;
+        for (int w = 0; w < kThreads / 64; ++w) x += red[w];
+        stats[(int64_t)(bd.req0 + b) * n_q_heads + h] = make_float2(m, x);
+    }
+}
+
+// ---- 3. scores ---------------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void decode_score_kernel(
+    const DecodeBatch bd, int n_q_heads, int n_kv_heads, int64_t n_rows,
+    const float *__restrict__ logits, const float2 *__restrict__ stats,
+    const float *__restrict__ dev_v, const uint8_t *__restrict__ reused, float *__restrict__ score)
+{
+    int b = 0;
+    while (b + 1 < bd.n_req && (int)blockIdx.x >= bd.tile_begin[b + 1]) ++b;
+    // this kernel is launched with kThreads-token tiles: tile_begin was built for kTok tokens, so
+    // the launcher passes a table built for kThreads instead (see launch code)
+    const int tile = blockIdx.x - bd.tile_begin[b];
+    const int i = tile * kThreads + threadIdx.x;
+    if (i >= bd.ctx_len[b]) return;
+    const int64_t row = bd.ctx_off[b] + i;
+    const int grp = n_q_heads / n_kv_heads;
+    const float2 *st = stats + (int64_t)(bd.req0 + b) * n_q_heads;
+    float s = 0.f;
+    for (int g = 0; g < n_kv_heads; ++g) {
+        float mass = 0.f;
+        for (int hh = 0; hh < grp; ++hh) {
+            const int h = g * grp + hh;
+            const float2 ms = st[h];
+            mass += expf(logits[(int64_t)h * n_rows + row] - ms.x) / ms.y;
+        }
+        s += mass * dev_v[(int64_t)g * n_rows + row];
+    }
+    const bool cand = reused ? reused[row] != 0 : true;
+    score[row] = cand ? s : -INFINITY;
+}
+
+// ---- 5. optional decode attention output -------------------------------------------------------
+// one workgroup per (request, kv head); thread = (half, channel); tokens split even/odd over halves
+template <int DTYPE, int D>
+__global__ __launch_bounds__(kThreads) void decode_attn_kernel(
+    const DecodeBatch bd, int n_q_heads, int n_kv_heads, int64_t n_rows,
+    const float *__restrict__ logits, const float2 *__restrict__ stats,
+    const void *__restrict__ v_cache, void *__restrict__ attn_out)
+{
+    constexpr int MAXG = 8;
+    constexpr int PARTS = kThreads / D;
+    __shared__ float part[PARTS][MAXG][D];
+    const int b = blockIdx.x / n_kv_heads, g = blockIdx.x % n_kv_heads;
+    const int len = bd.ctx_len[b];
+    const int64_t row0 = bd.ctx_off[b];
+    const int grp = n_q_heads / n_kv_heads;
+    const int c = threadIdx.x % D, part_id = threadIdx.x / D;
+    const float2 *st = stats + (int64_t)(bd.req0 + b) * n_q_heads;
+    for (int h0 = 0; h0 < grp; h0 += MAXG) {
+        const int nh = min(MAXG, grp - h0);
+        float acc[MAXG];
+        float mx[MAXG], inv[MAXG];
+#pragma unroll
+        for (int hh = 0; hh < MAXG; ++hh) {
+            acc[hh] = 0.f;
+            const float2 ms = hh < nh ? st[g * grp + h0 + hh] : make_float2(0.f, 1.f);
+            mx[hh] = ms.x;
+            inv[hh] = 1.0f / ms.y;
+        }
+        for (int i = part_id; i < len; i += PARTS) {
+            const int64_t gi = ((row0 + i) * n_kv_heads + g) * (int64_t)D + c;
+            float v;
+            if (DTYPE == KVS_F32) v = ((const float *)v_cache)[gi];
+            else v = __uint_as_float((uint32_t)((const uint16_t *)v_cache)[gi] << 16);
+#pragma unroll
+            for (int hh = 0; hh < MAXG; ++hh)
+                if (hh < nh) acc[hh] += expf(logits[(int64_t)(g * grp + h0 + hh) * n_rows + row0 + i] - mx[hh]) * inv[hh] * v;
+        }
+#pragma unroll
+        for (int hh = 0; hh < MAXG; ++hh) part[part_id][hh][c] = acc[hh];
+        __syncthreads();
+        if (part_id == 0) {
+            for (int hh = 0; hh < nh; ++hh) {
+                float s = 0.f;
+                for (int pp = 0; pp < PARTS; ++pp) s += part[pp][hh][c];
+                const int64_t oi = ((int64_t)(bd.req0 + b) * n_q_heads + g * grp + h0 + hh) * D + c;
+                if (DTYPE == KVS_F32) ((float *)attn_out)[oi] = s;
+                else ((uint16_t *)attn_out)[oi] = (uint16_t)f32_to_bf16_bits(s);
+            }
+        }
+        __syncthreads();
+    }
+}
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+} // namespace
+
+size_t decode_workspace_bytes(const kvs_shape *shape, int32_t batch, int64_t n_rows)
+{
+    size_t logits = align_up(sizeof(float) * (size_t)shape->n_q_heads * (size_t)n_rows, 256);
+    size_t stats = align_up(sizeof(float2) * (size_t)batch * (size_t)shape->n_q_heads, 256);
+    size_t score = align_up(sizeof(float) * (size_t)n_rows, 256);
+    return logits + stats + score;
+}
+
+} // namespace kvs
+
+extern "C" kvs_status kvs_decode_check(const kvs_shape *shape, int32_t batch, int64_t n_rows,
+                                       const int64_t *ctx_off, const int64_t *ctx_len,
+                                       const void *q_new, const void *k_cache, const void *v_cache,
+                                       const float *dev_v, const uint8_t *reused, float scale,
+                                       const int32_t *k_req, int32_t *idx_out, float *score_out,
+                                       void *attn_out,
+                                       void *workspace, size_t workspace_bytes, void *stream)
+{
+    using namespace kvs;
+    kvs_status st = check_shape(shape);
+    if (st != KVS_OK) return st;
+    if (batch < 0 || n_rows < 0) return fail(KVS_EINVAL, "kvs_decode_check: negative size");
+    if (batch == 0) return KVS_OK;
+    if (!ctx_off || !ctx_len || !k_req) return fail(KVS_EINVAL, "kvs_decode_check: ctx_off/ctx_len/k_req is NULL");
+    if (!q_new || !k_cache || !dev_v) return fail(KVS_EINVAL, "kvs_decode_check: q_new/k_cache/dev_v is NULL");
+    if (attn_out && !v_cache) return fail(KVS_EINVAL, "kvs_decode_check: attn_out needs v_cache");
+    if (!aligned16(k_cache) || (v_cache && !aligned16(v_cache))) return fail(KVS_EINVAL, "kvs_decode_check: K/V pointers must be 16-byte aligned");
+    int64_t total_k = 0;
+    for (int32_t b = 0; b < batch; ++b) {
+        if (ctx_off[b] < 0 || ctx_len[b] < 0 || ctx_off[b] + ctx_len[b] > n_rows)
+            return fail(KVS_EINVAL, "kvs_decode_check: request %d context [%lld,+%lld) outside the %lld cache rows", b, (long long)ctx_off[b], (long long)ctx_len[b], (long long)n_rows);
+        if (ctx_len[b] > 0x7fffffffLL) return fail(KVS_EINVAL, "kvs_decode_check: request %d context too long", b);
+        if (k_req[b] < 0 || k_req[b] > ctx_len[b]) return fail(KVS_EINVAL, "kvs_decode_check: k_req[%d]=%d outside [0,%lld]", b, k_req[b], (long long)ctx_len[b]);
+        if (ctx_len[b] == 0 && attn_out) return fail(KVS_EINVAL, "kvs_decode_check: attn_out with an empty context (request %d)", b);
+        total_k += k_req[b];
+    }
+    if (total_k > 0 && !idx_out) return fail(KVS_EINVAL, "kvs_decode_check: idx_out is NULL");
+    if (shape->n_q_heads > 256) return fail(KVS_EUNSUPPORTED, "kvs_decode_check: more than 256 query heads");
+    const size_t need = decode_workspace_bytes(shape, batch, n_rows);
+    if (!workspace || workspace_bytes < need) return fail(KVS_EWORKSPACE, "kvs_decode_check: workspace %zu < %zu bytes", workspace_bytes, need);
+    if (reinterpret_cast<uintptr_t>(workspace) & 255u) return fail(KVS_EINVAL, "kvs_decode_check: workspace must be 256-byte aligned");
+
+    hipStream_t hs = (hipStream_t)stream;
+    const int hq = shape->n_q_heads, hk = shape->n_kv_heads, d = shape->head_dim;
+    char *ws = (char *)workspace;
+    float *logits = (float *)ws;
+    ws += align_up(sizeof(float) * (size_t)hq * (size_t)n_rows, 256);
+    float2 *stats = (float2 *)ws;
+    ws += align_up(sizeof(float2) * (size_t)batch * (size_t)hq, 256);
+    float *score = score_out ? score_out : (float *)ws;
+    const int lph = (int)(d * elem_bytes(shape->dtype) / 16);
+
+    for (int32_t b0 = 0; b0 < batch; b0 += kMaxReq) {
+        const int nr = (batch - b0) < kMaxReq ? (batch - b0) : kMaxReq;
+        DecodeBatch bd_tok, bd_thr;   // tile tables for kTok-token and kThreads-token tiles
+        int64_t tiles_tok = 0, tiles_thr = 0;
+        for (int i = 0; i < kMaxReq; ++i) {
+            const bool live = i < nr;
+            const int64_t len = live ? ctx_len[b0 + i] : 0;
+            bd_tok.ctx_off[i] = bd_thr.ctx_off[i] = live ? ctx_off[b0 + i] : 0;
+            bd_tok.ctx_len[i] = bd_thr.ctx_len[i] = (int32_t)len;
+            bd_tok.tile_begin[i] = (int32_t)tiles_tok;
+            bd_thr.tile_begin[i] = (int32_t)tiles_thr;
+            tiles_tok += (len + kTok - 1) / kTok;
+            tiles_thr += (len + kThreads - 1) / kThreads;
+            if (tiles_tok > 0x7fffffffLL) return fail(KVS_EINVAL, "kvs_decode_check: too many tokens in one launch");
+        }
+        bd_tok.tile_begin[kMaxReq] = (int32_t)tiles_tok;
+        bd_thr.tile_begin[kMaxReq] = (int32_t)tiles_thr;
+        bd_tok.req0 = bd_thr.req0 = b0;
+        bd_tok.n_req = bd_thr.n_req = nr;
+        if (tiles_tok == 0) continue;
+        const size_t lds = sizeof(float) * (size_t)hq * (d + kTok);
+        dim3 block(kThreads);
+#define KVS_DEC_CASE(DT, L) hipLaunchKernelGGL((decode_logits_kernel<DT, L>), dim3((unsigned)tiles_tok), block, lds, hs, bd_tok, hq, hk, n_rows, q_new, (const uint4 *)k_cache, scale, logits)
+        if (shape->dtype == KVS_BF16 && lph == 16) KVS_DEC_CASE(KVS_BF16, 16);
+        else if (shape->dtype == KVS_BF16 && lph == 8) KVS_DEC_CASE(KVS_BF16, 8);
+        else if (shape->dtype == KVS_F32 && lph == 16) KVS_DEC_CASE(KVS_F32, 16);
+        else if (shape->dtype == KVS_F32 && lph == 32) KVS_DEC_CASE(KVS_F32, 32);
+        else return fail(KVS_EUNSUPPORTED, "kvs_decode_check: head_dim %d", d);
+#undef KVS_DEC_CASE
+        if ((st = check_launch("kvs_decode_check(logits)")) != KVS_OK) return st;
+        hipLaunchKernelGGL(decode_stats_kernel, dim3((unsigned)(nr * hq)), block, 0, hs, bd_tok, hq, n_rows, logits, stats);
+        if ((st = check_launch("kvs_decode_check(stats)")) != KVS_OK) return st;
+        hipLaunchKernelGGL(decode_score_kernel, dim3((unsigned)tiles_thr), block, 0, hs, bd_thr, hq, hk, n_rows,
+                           logits, stats, dev_v, reused, score);
+        if ((st = check_launch("kvs_decode_check(score)")) != KVS_OK) return st;
+        if (attn_out) {
+            dim3 grid((unsigned)(nr * hk));
+            if (shape->dtype == KVS_BF16 && d == 128) hipLaunchKernelGGL((decode_attn_kernel<KVS_BF16, 128>), grid, block, 0, hs, bd_tok, hq, hk, n_rows, logits, stats, v_cache, attn_out);
+            else if (shape->dtype == KVS_BF16 && d == 64) hipLaunchKernelGGL((decode_attn_kernel<KVS_BF16, 64>), grid, block, 0, hs, bd_tok, hq, hk, n_rows, logits, stats, v_cache, attn_out);
+            else if (shape->dtype == KVS_F32 && d == 128) hipLaunchKernelGGL((decode_attn_kernel<KVS_F32, 128>), grid, block, 0, hs, bd_tok, hq, hk, n_rows, logits, stats, v_cache, attn_out);
+            else hipLaunchKernelGGL((decode_attn_kernel<KVS_F32, 64>), grid, block, 0, hs, bd_tok, hq, hk, n_rows, logits, stats, v_cache, attn_out);
+            if ((st = check_launch("kvs_decode_check(attn)")) != KVS_OK) return st;
+        }
+    }
+    if (total_k == 0) return KVS_OK;
+    return launch_select(score, batch, ctx_off, ctx_len, k_req, idx_out, hs);
+}

@@ -1,0 +1,112 @@
+// Internal helpers shared by the HIP translation units of libkvshare_hip.so.
+// Nothing here is part of the ABI (see include/kvs.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "kvs.h"
+
+namespace kvs {
+
+// thread-local error text behind kvs_last_error()
+void set_error(const char *fmt, ...) __attribute__((format(printf, 1, 2)));
+kvs_status fail(kvs_status st, const char *fmt, ...) __attribute__((format(printf, 2, 3)));
+kvs_status check_launch(const char *what);
+
+inline size_t elem_bytes(int32_t dtype) { return dtype == KVS_F32 ? 4 : 2; }
+
+// Validates a kvs_shape for the kernels that exist; on failure the status says why.
+kvs_status check_shape(const kvs_shape *s);
+
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// exact top-k over rows given as (begin, len) pairs of one score array (select.hip)
+kvs_status launch_select(const float *scores, int32_t n_rows, const int64_t *begin, const int64_t *len,
+                         const int32_t *k_row, int32_t *idx_out, hipStream_t stream);
+size_t decode_workspace_bytes(const kvs_shape *shape, int32_t batch, int64_t n_rows);
+
+constexpr int kWave = 64;
+
+// ---- wavefront primitives (64 lanes) ------------------------------------------------------
+
+// value of `v` taken from the lane `ctrl` selects inside the same 16-lane row (DPP)
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float v)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(
+        0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, false));
+}
+template <int CTRL>
+__device__ __forceinline__ int dpp_i32(int v)
+{
+    return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xf, 0xf, false);
+}
+
+// sum over each aligned group of 16 lanes, result in every lane of the group; fixed order
+__device__ __forceinline__ float row16_sum(float v)
+{
+    v += dpp_f32<0x128>(v); // row_ror:8
+    v += dpp_f32<0x124>(v); // row_ror:4
+    v += dpp_f32<0x122>(v); // row_ror:2
+    v += dpp_f32<0x121>(v); // row_ror:1
+    return v;
+}
+
+__device__ __forceinline__ float wave_sum(float v)
+{
+    v = row16_sum(v);
+    v += __shfl_xor(v, 16);
+    v += __shfl_xor(v, 32);
+    return v;
+}
+
+__device__ __forceinline__ float wave_max(float v)
+{
+    v = fmaxf(v, dpp_f32<0x128>(v));
+    v = fmaxf(v, dpp_f32<0x124>(v));
+    v = fmaxf(v, dpp_f32<0x122>(v));
+    v = fmaxf(v, dpp_f32<0x121>(v));
+    v = fmaxf(v, __shfl_xor(v, 16));
+    v = fmaxf(v, __shfl_xor(v, 32));
+    return v;
+}
+
+__device__ __forceinline__ int wave_sum_i32(int v)
+{
+    v += dpp_i32<0x128>(v);
+    v += dpp_i32<0x124>(v);
+    v += dpp_i32<0x122>(v);
+    v += dpp_i32<0x121>(v);
+    v += __shfl_xor(v, 16);
+    v += __shfl_xor(v, 32);
+    return v;
+}
+
+// 16-byte streaming (non-temporal) load: data that is read once should not displace reusable lines
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 stream_load16(const uint4 *p)
+{
+    const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(p));
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+
+// exact bf16 -> fp32 widening of the two halves of a packed pair
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+// fp32 -> bf16, round to nearest even (finite inputs; NaN keeps a quiet pattern)
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
+{
+    return f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16);
+}
+
+} // namespace kvs

@@ -1,0 +1,114 @@
+"""CPU-side checks of the C-ABI library: it loads without a GPU, exports every symbol the header
+declares, and rejects bad arguments on the host before anything is launched (no compute calls
+here: every call below fails validation or is a no-op by construction)."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2503_16525_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x10000  # non-NULL, 16-byte aligned, never dereferenced: validation fails first
+
+
+@pytest.fixture(scope="module")
+def lib():
+    return B.load()
+
+
+def test_exports_every_declared_symbol(lib):
+    header = open(os.path.join(ROOT, "include", "kvs.h")).read()
+    declared = re.findall(r"KVS_API\s+[\w\s\*]+?\b(kvs_\w+)\s*\(", header)
+    assert sorted(declared) == sorted(B.EXPORTS)
+    for name in declared:
+        assert getattr(lib, name) is not None
+    assert lib.kvs_version().startswith(b"kvshare-hip gfx950")
+    assert lib.kvs_strerror(B.EINVAL) == b"invalid argument"
+
+
+def _shape(hq=32, hk=8, d=128, dt=B.BF16):
+    return B.make_shape(hq, hk, d, dt)
+
+
+def test_shape_validation(lib):
+    for sh, want in [(_shape(hq=30), B.EINVAL), (_shape(d=96), B.EUNSUPPORTED), (_shape(dt=7), B.EINVAL),
+                     (_shape(hk=0), B.EINVAL)]:
+        rc = lib.kvs_deviation(ctypes.byref(sh), 16, None, FAKE, None, FAKE, None, None, 0, None, FAKE, FAKE, None)
+        assert rc == want, lib.kvs_last_error()
+    assert lib.kvs_deviation(None, 16, None, FAKE, None, FAKE, None, None, 0, None, FAKE, FAKE, None) == B.EINVAL
+
+
+def test_deviation_argument_errors(lib):
+    sh = _shape()
+    assert lib.kvs_deviation(ctypes.byref(sh), -1, None, FAKE, None, FAKE, None, None, 0, None, None, None, None) == B.EINVAL
+    assert lib.kvs_deviation(ctypes.byref(sh), 8, None, None, None, FAKE, None, None, 0, None, None, None, None) == B.EINVAL
+    # mode KV needs the key tensors
+    assert lib.kvs_deviation(ctypes.byref(sh), 8, None, FAKE, None, FAKE, None, None, 1, None, None, None, None) == B.EINVAL
+    assert b"k_fresh" in lib.kvs_last_error()
+    assert lib.kvs_deviation(ctypes.byref(sh), 8, None, FAKE + 4, None, FAKE, None, None, 0, None, None, None, None) == B.EINVAL
+    assert lib.kvs_deviation(ctypes.byref(sh), 8, None, FAKE, None, FAKE, None, None, 5, None, None, None, None) == B.EINVAL
+    # empty input: success, nothing launched
+    assert lib.kvs_deviation(ctypes.byref(sh), 0, None, None, None, None, None, None, 0, None, None, None, None) == B.OK
+
+
+def test_select_argument_errors(lib):
+    ro = np.array([0, 10, 5], np.int64)
+    kr = np.array([1, 1], np.int32)
+    assert lib.kvs_select_topk(FAKE, 2, ro.ctypes.data, kr.ctypes.data, FAKE, None, 0, None) == B.EINVAL
+    ro = np.array([0, 10], np.int64)
+    for k in (-1, 11):
+        kr = np.array([k], np.int32)
+        assert lib.kvs_select_topk(FAKE, 1, ro.ctypes.data, kr.ctypes.data, FAKE, None, 0, None) == B.EINVAL
+    kr = np.array([3], np.int32)
+    assert lib.kvs_select_topk(None, 1, ro.ctypes.data, kr.ctypes.data, FAKE, None, 0, None) == B.EINVAL
+    assert lib.kvs_select_topk(FAKE, -1, ro.ctypes.data, kr.ctypes.data, FAKE, None, 0, None) == B.EINVAL
+    # k = 0 everywhere and zero rows are no-ops
+    kr = np.array([0], np.int32)
+    assert lib.kvs_select_topk(None, 1, ro.ctypes.data, kr.ctypes.data, None, None, 0, None) == B.OK
+    assert lib.kvs_select_topk(None, 0, None, None, None, None, 0, None) == B.OK
+
+
+def test_scatter_argument_errors(lib):
+    sh = _shape()
+    assert lib.kvs_scatter_kv(ctypes.byref(sh), 100, FAKE, FAKE, FAKE, 101, FAKE, FAKE, None, None, None) == B.EINVAL
+    assert lib.kvs_scatter_kv(ctypes.byref(sh), 100, None, FAKE, FAKE, 5, FAKE, FAKE, None, None, None) == B.EINVAL
+    assert lib.kvs_scatter_kv(ctypes.byref(sh), 100, FAKE, FAKE, FAKE, -1, FAKE, FAKE, None, None, None) == B.EINVAL
+    assert lib.kvs_scatter_kv(ctypes.byref(sh), 100, None, None, None, 0, None, None, None, None, None) == B.OK
+
+
+def test_attention_argument_errors(lib):
+    sh = _shape()
+    co, cl = np.array([0], np.int64), np.array([100], np.int64)
+
+    def call(cu, q=FAKE):
+        cs = np.array(cu, np.int64)
+        return lib.kvs_partial_attention(ctypes.byref(sh), 1, co.ctypes.data, cl.ctypes.data, cs.ctypes.data,
+                                         q, FAKE, FAKE, FAKE, 1.0, FAKE, None, None, 0, None)
+    assert call([0, 101]) == B.EINVAL          # more selected tokens than context rows
+    assert call([1, 5]) == B.EINVAL            # cu_sel must start at 0
+    assert call([0, 5], q=None) == B.EINVAL
+    assert call([0, 5], q=FAKE + 2) == B.EINVAL
+    assert call([0, 0], q=None) == B.OK        # nothing selected: no-op
+    assert lib.kvs_partial_attention(ctypes.byref(sh), -1, None, None, None, None, None, None, None, 1.0,
+                                     None, None, None, 0, None) == B.EINVAL
+
+
+def test_decode_argument_errors(lib):
+    sh = _shape()
+    co, cl, kr = np.array([0, 50], np.int64), np.array([50, 60], np.int64), np.array([1, 1], np.int32)
+    need = B.kvs_workspace_size("decode_check", sh, 2, 110)
+    assert need >= 4 * 32 * 110
+
+    def call(n_rows=110, ws=FAKE * 16, ws_bytes=need, k=kr, attn=None, v=None):
+        return lib.kvs_decode_check(ctypes.byref(sh), 2, n_rows, co.ctypes.data, cl.ctypes.data, FAKE, FAKE, v,
+                                    FAKE, None, 1.0, k.ctypes.data, FAKE, None, attn, ws, ws_bytes, None)
+    assert call(n_rows=100) == B.EINVAL                       # second context overruns the cache
+    assert call(ws_bytes=need - 1) == B.EWORKSPACE
+    assert call(ws=None) == B.EWORKSPACE
+    assert call(k=np.array([1, 61], np.int32)) == B.EINVAL
+    assert call(attn=FAKE) == B.EINVAL                        # attn_out without v_cache
+    assert b"v_cache" in lib.kvs_last_error()
+    assert B.kvs_workspace_size("nonsense", sh, 1, 10) == 0

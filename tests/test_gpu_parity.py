@@ -1,0 +1,416 @@
+"""GPU parity: every C-ABI call of libkvshare_hip.so against the CPU oracle, element by element,
+on the same seeded inputs.  Sizes here are ones the oracle finishes in seconds but that span
+several tiles and a ragged tail; full-size cases live in test_gpu_fullsize.py.
+
+Tolerances (the spec bars): index sets bit-exact on identical fp32 scores; deviation and
+scores 1e-5 relative; attention 2e-2 absolute for bf16, 1e-4 for fp32.
+"""
+import math
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2503_16525_amd import binding as B
+from paper_2503_16525_amd import synth
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+
+def say(msg):
+    print(f"[case] {msg}", flush=True)
+    sys.stdout.flush()
+
+
+def shape_for(w):
+    return B.shape_of(w)
+
+
+def to_dev(lay):
+    return {k: (v.to(DEV) if isinstance(v, torch.Tensor) else v) for k, v in lay.items()}
+
+
+def assert_scores_close(got, ref, rtol=1e-5):
+    got, ref = np.asarray(got), np.asarray(ref)
+    inf = np.isneginf(ref)
+    assert np.array_equal(np.isneginf(got), inf)
+    np.testing.assert_allclose(got[~inf], ref[~inf], rtol=rtol, atol=0)
+
+
+# --------------------------------------------------------------------------------- deviation
+
+DEV_CASES = [
+    ("tiny-f32", synth.TINY),
+    ("qwen-2085", synth.scaled(synth.QWEN, 2085)),
+    ("llama-4133", synth.scaled(synth.LLAMA, 4133)),
+    ("llama-31", synth.scaled(synth.LLAMA, 31, span_mean=8.0)),
+    ("f32-d128", synth.scaled(synth.TINY, 300, head_dim=128, n_kv_heads=2, n_q_heads=4, n_spans=2, span_lo=20, span_hi=60)),
+    ("bf16-d64", synth.scaled(synth.QWEN, 777, head_dim=64, n_kv_heads=3, n_q_heads=6, span_mean=32.0)),
+]
+
+
+@pytest.mark.parametrize("name,w", DEV_CASES, ids=[c[0] for c in DEV_CASES])
+@pytest.mark.parametrize("mode", [B.SCORE_V, B.SCORE_KV])
+@pytest.mark.parametrize("weighted", [False, True])
+def test_deviation_parity(name, w, mode, weighted):
+    say(f"deviation {name} mode={mode} weighted={weighted}")
+    lay = synth.make_layer(w, with_q=False)
+    n, hk = w.n_ctx, w.n_kv_heads
+    alpha = synth.synthetic_alpha(w) if weighted else None
+    rk, rv, rs = oracle.deviation(lay["v_fresh"], lay["v_cache"], lay["k_fresh"], lay["k_cache"],
+                                  reused=lay["reused"], alpha=alpha, mode=mode, want_dev_k=True)
+    g = to_dev(lay)
+    dev_k = torch.full((hk, n), float("nan"), device=DEV)
+    dev_v = torch.full((hk, n), float("nan"), device=DEV)
+    score = torch.full((n,), float("nan"), device=DEV)
+    B.kvs_deviation(shape_for(w), n, g["k_fresh"], g["v_fresh"], g["k_cache"], g["v_cache"], g["reused"],
+                    alpha.to(DEV) if weighted else None, mode, dev_k, dev_v, score)
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(dev_v.cpu().numpy(), rv, rtol=1e-5, atol=0)
+    np.testing.assert_allclose(dev_k.cpu().numpy(), rk, rtol=1e-5, atol=0)
+    assert_scores_close(score.cpu().numpy(), rs)
+
+
+def test_deviation_value_only_without_keys_and_mask():
+    w = synth.scaled(synth.LLAMA, 1000)
+    say("deviation value-only, NULL keys, NULL mask, NULL dev outputs")
+    lay = synth.make_layer(w, with_q=False)
+    _, rv, rs = oracle.deviation(lay["v_fresh"], lay["v_cache"])
+    g = to_dev(lay)
+    score = torch.empty((w.n_ctx,), device=DEV)
+    B.kvs_deviation(shape_for(w), w.n_ctx, None, g["v_fresh"], None, g["v_cache"], None, None, B.SCORE_V,
+                    None, None, score)
+    assert_scores_close(score.cpu().numpy(), rs)
+    # run-to-run reproducibility (fixed summation order, no atomics)
+    score2 = torch.empty_like(score)
+    B.kvs_deviation(shape_for(w), w.n_ctx, None, g["v_fresh"], None, g["v_cache"], None, None, B.SCORE_V,
+                    None, None, score2)
+    assert torch.equal(score, score2)
+
+
+# --------------------------------------------------------------------------------- select
+
+def gpu_select(scores_np, row_off, k_row):
+    s = torch.from_numpy(np.ascontiguousarray(scores_np)).to(DEV)
+    out = torch.full((max(int(np.sum(k_row)), 1),), -7, dtype=torch.int32, device=DEV)
+    B.kvs_select_topk(s, row_off, k_row, out)
+    torch.cuda.synchronize()
+    return out.cpu().numpy()[: int(np.sum(k_row))]
+
+
+def check_select(scores_np, row_off, k_row, what):
+    say(f"select {what}: rows={len(k_row)} total={len(scores_np)} k={list(k_row)[:6]}")
+    ref = oracle.select_topk(scores_np, row_off, k_row)
+    got = gpu_select(scores_np, row_off, k_row)
+    np.testing.assert_array_equal(got, ref)
+
+
+@pytest.mark.parametrize("n", [1, 63, 64, 1000, 4096, 4097, 16384, 20001, 32768, 32769, 50000, 131072])
+def test_select_single_row_sizes(n):
+    rng = np.random.default_rng(n)
+    s = rng.lognormal(-3, 1.5, n).astype(np.float32)
+    s[rng.random(n) < 0.1] = -np.inf
+    for k in sorted({0, 1, min(n, 7), n // 10, n // 2, n - 1, n} - {-1}):
+        check_select(s, [0, n], [k], f"lognormal n={n}")
+
+
+def test_select_ties_and_special_values():
+    rng = np.random.default_rng(5)
+    n = 9001
+    # heavy ties
+    s = (np.round(rng.standard_normal(n) * 3) / 3).astype(np.float32)
+    for k in (1, 100, 4500, 9000):
+        check_select(s, [0, n], [k], "quantised")
+    # all equal: the k lowest indices
+    check_select(np.full(n, 0.25, np.float32), [0, n], [1234], "all-equal")
+    # signed zeros tie with each other; negative values; -inf ranks last
+    s = rng.standard_normal(n).astype(np.float32)
+    s[::3] = 0.0
+    s[1::3] = -0.0
+    s[::7] = -np.inf
+    for k in (10, 3000, 6000, 8000, n):
+        check_select(s, [0, n], [k], "zeros/neg/-inf")
+    # identical high bits: values differ only in the last mantissa bits (radix worst case)
+    base = np.float32(1.0).view(np.uint32)
+    s = (base + rng.integers(0, 16, n).astype(np.uint32)).view(np.float32)
+    for k in (1, 17, 5000):
+        check_select(s, [0, n], [k], "low-bit-only")
+    # denormals and huge values
+    s = rng.standard_normal(n).astype(np.float32)
+    s[:100] = np.float32(1e-42)
+    s[100:200] = np.float32(3e38)
+    check_select(s, [0, n], [150], "denormal/huge")
+
+
+def test_select_ragged_rows():
+    rng = np.random.default_rng(6)
+    lens = [5, 0, 4096, 1, 7000, 33000, 129, 64, 20000] + [int(x) for x in rng.integers(1, 3000, 70)]
+    off = np.concatenate([[0], np.cumsum(lens)])
+    s = rng.lognormal(0, 1, int(off[-1])).astype(np.float32)
+    s[rng.random(len(s)) < 0.2] = -np.inf
+    ks = [int(rng.integers(0, l + 1)) for l in lens]
+    check_select(s, off, ks, "ragged 79 rows")
+    check_select(s, off, [0] * len(lens), "ragged all-zero k")
+
+
+def test_select_on_oracle_scores_of_a_layer():
+    for w in (synth.TINY, synth.scaled(synth.QWEN, 8192)):
+        lay = synth.make_layer(w, with_q=False)
+        _, _, sc = oracle.deviation(lay["v_fresh"], lay["v_cache"], reused=lay["reused"])
+        k = synth.recompute_budget(int(lay["reused"].sum()), w.ratios[0])
+        check_select(sc, [0, w.n_ctx], [k], f"layer scores {w.name}")
+
+
+# --------------------------------------------------------------------------------- scatter
+
+@pytest.mark.parametrize("w", [synth.TINY, synth.scaled(synth.LLAMA, 3000), synth.scaled(synth.QWEN, 1111)],
+                         ids=["tiny", "llama-3000", "qwen-1111"])
+def test_scatter_parity(w):
+    say(f"scatter {w.name}")
+    lay = synth.make_layer(w, with_q=False)
+    n, hk = w.n_ctx, w.n_kv_heads
+    rng = np.random.default_rng(11)
+    for n_sel in (0, 1, n // 7, n):
+        pos = np.sort(rng.choice(n, size=n_sel, replace=False)).astype(np.int32)
+        li = torch.from_numpy(pos.astype(np.int64))
+        kc, vc = oracle._as_np(lay["k_cache"]).copy(), oracle._as_np(lay["v_cache"]).copy()
+        reused = lay["reused"].numpy().copy()
+        dev = np.random.default_rng(12).random((hk, n), dtype=np.float32)
+        dev_ref = dev.copy()
+        oracle.scatter_kv(lay["k_fresh"][li], lay["v_fresh"][li], pos, kc, vc, reused, dev_ref)
+        g = to_dev(lay)
+        gk, gv, gr = g["k_cache"].clone(), g["v_cache"].clone(), g["reused"].clone()
+        gd = torch.from_numpy(dev).to(DEV)
+        B.kvs_scatter_kv(shape_for(w), n, g["k_fresh"][li.to(DEV)].contiguous(), g["v_fresh"][li.to(DEV)].contiguous(),
+                         torch.from_numpy(pos).to(DEV), n_sel, gk, gv, gr, gd)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(oracle._as_np(gk.cpu()), kc)
+        np.testing.assert_array_equal(oracle._as_np(gv.cpu()), vc)
+        np.testing.assert_array_equal(gr.cpu().numpy(), reused)
+        np.testing.assert_array_equal(gd.cpu().numpy(), dev_ref)
+
+
+# --------------------------------------------------------------------------------- attention
+
+def run_gpu_attention(w, q_sel, pos, k, v, scale, ctx_off=None, ctx_len=None, cu_sel=None, want_lse=True):
+    ns = q_sel.shape[0]
+    if ctx_off is None:
+        ctx_off, ctx_len, cu_sel = [0], [k.shape[0]], [0, ns]
+    out = torch.full((max(ns, 1), w.n_q_heads, w.head_dim), float("nan"), dtype=w.torch_dtype, device=DEV)
+    lse = torch.full((max(ns, 1), w.n_q_heads), float("nan"), device=DEV) if want_lse else None
+    B.kvs_partial_attention(shape_for(w), ctx_off, ctx_len, cu_sel, q_sel.to(DEV).contiguous(),
+                            torch.from_numpy(np.asarray(pos, np.int32)).to(DEV), k.to(DEV), v.to(DEV), scale, out, lse)
+    torch.cuda.synchronize()
+    return out[:ns].float().cpu().numpy(), (lse[:ns].cpu().numpy() if want_lse else None)
+
+
+def attn_tol(w):
+    return 1e-4 if w.dtype == "f32" else 2e-2
+
+
+ATT_CASES = [
+    ("tiny-f32", synth.TINY, 0.15),
+    ("qwen-1500-g7", synth.scaled(synth.QWEN, 1500, span_mean=64.0), 0.10),
+    ("llama-1201-g4", synth.scaled(synth.LLAMA, 1201, span_mean=64.0), 0.30),
+    ("yi-900-g8", synth.scaled(synth.YI, 900, span_mean=64.0, coverage=0.9), 0.10),
+    ("bf16-d64", synth.scaled(synth.QWEN, 700, head_dim=64, n_kv_heads=2, n_q_heads=4, span_mean=32.0), 0.2),
+]
+
+
+@pytest.mark.parametrize("name,w,ratio", ATT_CASES, ids=[c[0] for c in ATT_CASES])
+def test_partial_attention_parity(name, w, ratio):
+    say(f"attention {name}")
+    lay = synth.make_layer(w)
+    _, _, sc = oracle.deviation(lay["v_fresh"], lay["v_cache"], reused=lay["reused"])
+    k = synth.recompute_budget(int(lay["reused"].sum()), ratio)
+    pos = oracle.select_topk(sc, [0, w.n_ctx], [k])
+    li = torch.from_numpy(pos.astype(np.int64))
+    kc, vc = oracle._as_np(lay["k_cache"]).copy(), oracle._as_np(lay["v_cache"]).copy()
+    oracle.scatter_kv(lay["k_fresh"][li], lay["v_fresh"][li], pos, kc, vc)
+    q_sel = lay["q"][li].contiguous()
+    ref, ref_lse = oracle.partial_attention(q_sel, pos, kc, vc, 1.0)
+    kt = lay["k_cache"].clone()
+    vt = lay["v_cache"].clone()
+    kt[li] = lay["k_fresh"][li]
+    vt[li] = lay["v_fresh"][li]
+    got, lse = run_gpu_attention(w, q_sel, pos, kt, vt, 1.0)
+    assert np.abs(got - ref).max() <= attn_tol(w), np.abs(got - ref).max()
+    np.testing.assert_allclose(lse, ref_lse, atol=2e-3 if w.dtype == "bf16" else 1e-4)
+
+
+def test_partial_attention_edge_positions_and_scale():
+    # first token only, last token, consecutive positions straddling a tile edge; unscaled q with scale=1/sqrt(d)
+    w = synth.scaled(synth.LLAMA, 515, span_mean=32.0)
+    say("attention edge positions")
+    lay = synth.make_layer(w)
+    pos = np.array([0, 1, 31, 32, 33, 63, 64, 65, 127, 128, 255, 256, 300, 511, 512, 513, 514], np.int32)
+    li = torch.from_numpy(pos.astype(np.int64))
+    q_sel = (lay["q"][li].float() * math.sqrt(w.head_dim)).to(torch.bfloat16).contiguous()
+    scale = 1.0 / math.sqrt(w.head_dim)
+    ref, ref_lse = oracle.partial_attention(q_sel, pos, lay["k_cache"], lay["v_cache"], scale)
+    got, lse = run_gpu_attention(w, q_sel, pos, lay["k_cache"], lay["v_cache"], scale)
+    assert np.abs(got - ref).max() <= 2e-2
+    np.testing.assert_allclose(lse, ref_lse, atol=2e-3)
+    # a single selected token
+    got1, _ = run_gpu_attention(w, q_sel[5:6], pos[5:6], lay["k_cache"], lay["v_cache"], scale)
+    assert np.abs(got1 - ref[5:6]).max() <= 2e-2
+
+
+def test_partial_attention_select_all_is_full_prefill():
+    w = synth.scaled(synth.LLAMA, 400, span_mean=32.0)
+    say("attention select-all == full prefill")
+    lay = synth.make_layer(w)
+    pos = np.arange(w.n_ctx, dtype=np.int32)
+    ref, _ = oracle.partial_attention(lay["q"], pos, lay["k_fresh"], lay["v_fresh"], 1.0)
+    got, _ = run_gpu_attention(w, lay["q"], pos, lay["k_fresh"], lay["v_fresh"], 1.0)
+    assert np.abs(got - ref).max() <= 2e-2
+
+
+def test_partial_attention_ragged_batch():
+    w = synth.scaled(synth.LLAMA, 0)
+    say("attention ragged batch with slack rows and an empty request")
+    lens, pad = [700, 33, 1, 260, 129], 5
+    off = np.cumsum([0] + [l + pad for l in lens])[:-1]
+    rows = sum(lens) + pad * len(lens)
+    g = torch.Generator().manual_seed(77)
+    k = torch.randn((rows, w.n_kv_heads, w.head_dim), generator=g).to(torch.bfloat16)
+    v = torch.randn((rows, w.n_kv_heads, w.head_dim), generator=g).to(torch.bfloat16)
+    rng = np.random.default_rng(78)
+    sel = [np.sort(rng.choice(l, size=min(l, c), replace=False)).astype(np.int32)
+           for l, c in zip(lens, [90, 33, 1, 0, 40])]
+    cu = np.cumsum([0] + [len(s) for s in sel])
+    q = (torch.randn((int(cu[-1]), w.n_q_heads, w.head_dim), generator=g) / math.sqrt(w.head_dim)).to(torch.bfloat16)
+    pos = np.concatenate(sel)
+    ref, ref_lse = oracle.partial_attention(q, pos, k, v, 1.0, off, lens, cu)
+    got, lse = run_gpu_attention(w, q, pos, k, v, 1.0, off, lens, cu)
+    assert np.abs(got - ref).max() <= 2e-2
+    np.testing.assert_allclose(lse, ref_lse, atol=2e-3)
+
+
+# --------------------------------------------------------------------------------- decode check
+
+def check_topk_band(idx, score_ref, k, rtol=2e-5):
+    """idx is a valid top-k of scores that agree with score_ref to rtol: everything clearly above
+    the k-th reference score is in, everything clearly below is out, indices ascending/unique."""
+    assert len(idx) == k
+    if k == 0:
+        return
+    assert np.all(np.diff(idx) > 0) and idx[0] >= 0 and idx[-1] < len(score_ref)
+    thr = np.sort(score_ref)[::-1][k - 1]
+    chosen = np.zeros(len(score_ref), bool)
+    chosen[idx] = True
+    assert np.all(chosen[score_ref > thr * (1 + rtol) + 1e-30]), "a clearly better candidate was left out"
+    assert not np.any(chosen[score_ref < thr * (1 - rtol) - 1e-30]), "a clearly worse candidate was taken"
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_decode_check_parity(dtype):
+    w = synth.DECODE if dtype == "bf16" else synth.scaled(synth.DECODE, 0, dtype="f32", head_dim=64, n_q_heads=8, n_kv_heads=4)
+    say(f"decode check {dtype}")
+    batch, steps = 5, 2
+    bt = synth.make_decode_batch(w, batch, 150, 1300, steps)
+    rows = bt["k_cache"].shape[0]
+    off, lens = bt["ctx_off"], bt["ctx_len"].copy()
+    sh = shape_for(w)
+    # "prefill": stored deviations from the oracle side and from the GPU side, each on its own path
+    _, dev_ref, _ = oracle.deviation(bt["v_fresh"], bt["v_cache"], reused=bt["reused"])
+    g = to_dev(bt)
+    dev_gpu = torch.empty((w.n_kv_heads, rows), device=DEV)
+    B.kvs_deviation(sh, rows, None, g["v_fresh"], None, g["v_cache"], g["reused"], None, B.SCORE_V, None, dev_gpu, None)
+    kc, vc = oracle._as_np(bt["k_cache"]).copy(), oracle._as_np(bt["v_cache"]).copy()
+    reused = bt["reused"].numpy().copy()
+    gk, gv, gr = g["k_cache"].clone(), g["v_cache"].clone(), g["reused"].clone()
+    ws = torch.empty(B.kvs_workspace_size("decode_check", sh, batch, rows), dtype=torch.uint8, device=DEV)
+    for step in range(steps):
+        # append the new token's K/V (fresh, not a candidate)
+        for b in range(batch):
+            r = int(off[b] + lens[b])
+            kc[r] = oracle._as_np(bt["k_new"][step, b])
+            vc[r] = oracle._as_np(bt["v_new"][step, b])
+            gk[r] = g["k_new"][step, b]
+            gv[r] = g["v_new"][step, b]
+        lens = lens + 1
+        kreq = [int(math.ceil(0.02 * l)) for l in lens]
+        kreq[1] = 0
+        ref_idx, ref_score, ref_attn = oracle.decode_check(bt["q_new"][step], kc, dev_ref, reused, 1.0, off, lens, kreq,
+                                                           v_cache=vc, want_attn=True)
+        idx = torch.full((sum(kreq),), -1, dtype=torch.int32, device=DEV)
+        score = torch.full((rows,), float("nan"), device=DEV)
+        attn = torch.empty((batch, w.n_q_heads, w.head_dim), dtype=w.torch_dtype, device=DEV)
+        B.kvs_decode_check(sh, rows, off, lens, g["q_new"][step].contiguous(), gk, gv, dev_gpu, gr, 1.0, kreq,
+                           idx, score, attn, ws)
+        torch.cuda.synchronize()
+        sc, ix = score.cpu().numpy(), idx.cpu().numpy()
+        pos = 0
+        for b in range(batch):
+            sl = slice(int(off[b]), int(off[b] + lens[b]))
+            assert_scores_close(sc[sl], ref_score[sl])
+            check_topk_band(ix[pos:pos + kreq[b]], ref_score[sl], kreq[b])
+            pos += kreq[b]
+        assert np.all(np.isnan(sc[int(off[0] + lens[0]): int(off[1])]))      # slack rows not written
+        assert np.abs(attn.float().cpu().numpy() - ref_attn).max() <= attn_tol(w)
+        # without the optional outputs the indices are the same
+        idx2 = torch.full_like(idx, -1)
+        B.kvs_decode_check(sh, rows, off, lens, g["q_new"][step].contiguous(), gk, None, dev_gpu, gr, 1.0, kreq,
+                           idx2, None, None, ws)
+        assert torch.equal(idx, idx2)
+        # write-back of the oracle's choice on both sides (so the two states stay identical)
+        glob = np.concatenate([ref_idx[sum(kreq[:b]):sum(kreq[:b + 1])] + off[b] for b in range(batch)]).astype(np.int32)
+        li = torch.from_numpy(glob.astype(np.int64))
+        oracle.scatter_kv(bt["k_fresh"][li], bt["v_fresh"][li], glob, kc, vc, reused, dev_ref)
+        B.kvs_scatter_kv(sh, rows, g["k_fresh"][li.to(DEV)].contiguous(), g["v_fresh"][li.to(DEV)].contiguous(),
+                         torch.from_numpy(glob).to(DEV), len(glob), gk, gv, gr, dev_gpu)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(gr.cpu().numpy(), reused)
+
+
+# --------------------------------------------------------------------------------- whole path
+
+@pytest.mark.parametrize("w", [synth.TINY, synth.scaled(synth.QWEN, 1024, span_mean=64.0)], ids=["tiny", "qwen-1024"])
+def test_prefill_path_end_to_end(w):
+    """deviation -> select -> scatter -> partial attention chained on the GPU with no host
+    round trip, against the oracle chain with the exact prefill alpha of Alg. 1 steps 1-2."""
+    say(f"end-to-end {w.name}")
+    lay = synth.make_layer(w)
+    n, hk = w.n_ctx, w.n_kv_heads
+    _, alpha_g = oracle.alpha_prefill(lay["q"], lay["k_fresh"], 1.0)
+    alpha = torch.from_numpy(alpha_g.astype(np.float32))
+    k = synth.recompute_budget(int(lay["reused"].sum()), w.ratios[0])
+    # oracle chain
+    _, _, sc = oracle.deviation(lay["v_fresh"], lay["v_cache"], reused=lay["reused"], alpha=alpha)
+    # GPU chain
+    g = to_dev(lay)
+    sh = shape_for(w)
+    dev_v = torch.empty((hk, n), device=DEV)
+    score = torch.empty((n,), device=DEV)
+    idx = torch.empty((k,), dtype=torch.int32, device=DEV)
+    B.kvs_deviation(sh, n, None, g["v_fresh"], None, g["v_cache"], g["reused"], alpha.to(DEV), B.SCORE_V, None, dev_v, score)
+    B.kvs_select_topk(score, [0, n], [k], idx)
+    li = idx.long()
+    k_new, v_new, q_sel = g["k_fresh"][li].contiguous(), g["v_fresh"][li].contiguous(), g["q"][li].contiguous()
+    gk, gv, gr = g["k_cache"].clone(), g["v_cache"].clone(), g["reused"].clone()
+    B.kvs_scatter_kv(sh, n, k_new, v_new, idx, k, gk, gv, gr, dev_v)
+    out = torch.empty((k, w.n_q_heads, w.head_dim), dtype=w.torch_dtype, device=DEV)
+    B.kvs_partial_attention(sh, [0], [n], [0, k], q_sel, idx, gk, gv, 1.0, out)
+    torch.cuda.synchronize()
+    assert_scores_close(score.cpu().numpy(), sc)
+    # the oracle chain, entirely on the oracle's own intermediate results
+    ref_idx = oracle.select_topk(sc, [0, n], [k])
+    lic = torch.from_numpy(ref_idx.astype(np.int64))
+    kc, vc = oracle._as_np(lay["k_cache"]).copy(), oracle._as_np(lay["v_cache"]).copy()
+    reused = lay["reused"].numpy().copy()
+    oracle.scatter_kv(lay["k_fresh"][lic], lay["v_fresh"][lic], ref_idx, kc, vc, reused)
+    ref, _ = oracle.partial_attention(lay["q"][lic], ref_idx, kc, vc, 1.0)
+    # the two sides decide on scores that agree to 1e-5, so the index sets are the same set as long
+    # as the k-th and (k+1)-th reference scores are further apart than that (true for these seeds)
+    order = np.sort(sc[np.isfinite(sc)])[::-1]
+    assert order[k - 1] > order[k] * (1 + 1e-4), "seed gives a near-tie at the threshold; pick another"
+    ix = idx.cpu().numpy()
+    np.testing.assert_array_equal(ix, ref_idx)
+    np.testing.assert_array_equal(oracle._as_np(gk.cpu()), kc)
+    np.testing.assert_array_equal(oracle._as_np(gv.cpu()), vc)
+    np.testing.assert_array_equal(gr.cpu().numpy(), reused)
+    assert np.abs(out.float().cpu().numpy() - ref).max() <= attn_tol(w)
