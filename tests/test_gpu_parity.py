@@ -211,6 +211,19 @@ def attn_tol(w):
     return 1e-4 if w.dtype == "f32" else 2e-2
 
 
+def assert_attn_close(got, ref, w):
+    """2e-2 absolute (bf16) / 1e-4 (fp32).  A bf16 output cannot be closer to the exact value than
+    its own rounding step, 2^-8 relative at worst, so for |ref| > 5.12 (heavy-tailed cache noise
+    reaches |V| ~ 10) the bound follows the representable precision instead."""
+    got, ref = np.asarray(got, np.float64), np.asarray(ref, np.float64)
+    tol = np.full(ref.shape, attn_tol(w))
+    if w.dtype == "bf16":
+        tol = np.maximum(tol, np.abs(ref) * 2.0 ** -8)
+    err = np.abs(got - ref)
+    worst = np.unravel_index(np.argmax(err - tol), err.shape)
+    assert np.all(err <= tol), f"max excess at {worst}: got {got[worst]} ref {ref[worst]} err {err[worst]}"
+
+
 ATT_CASES = [
     ("tiny-f32", synth.TINY, 0.15),
     ("qwen-1500-g7", synth.scaled(synth.QWEN, 1500, span_mean=64.0), 0.10),
@@ -237,7 +250,7 @@ def test_partial_attention_parity(name, w, ratio):
     kt[li] = lay["k_fresh"][li]
     vt[li] = lay["v_fresh"][li]
     got, lse = run_gpu_attention(w, q_sel, pos, kt, vt, 1.0)
-    assert np.abs(got - ref).max() <= attn_tol(w), np.abs(got - ref).max()
+    assert_attn_close(got, ref, w)
     np.testing.assert_allclose(lse, ref_lse, atol=2e-3 if w.dtype == "bf16" else 1e-4)
 
 
@@ -252,11 +265,11 @@ def test_partial_attention_edge_positions_and_scale():
     scale = 1.0 / math.sqrt(w.head_dim)
     ref, ref_lse = oracle.partial_attention(q_sel, pos, lay["k_cache"], lay["v_cache"], scale)
     got, lse = run_gpu_attention(w, q_sel, pos, lay["k_cache"], lay["v_cache"], scale)
-    assert np.abs(got - ref).max() <= 2e-2
+    assert_attn_close(got, ref, w)
     np.testing.assert_allclose(lse, ref_lse, atol=2e-3)
     # a single selected token
     got1, _ = run_gpu_attention(w, q_sel[5:6], pos[5:6], lay["k_cache"], lay["v_cache"], scale)
-    assert np.abs(got1 - ref[5:6]).max() <= 2e-2
+    assert_attn_close(got1, ref[5:6], w)
 
 
 def test_partial_attention_select_all_is_full_prefill():
@@ -266,7 +279,7 @@ def test_partial_attention_select_all_is_full_prefill():
     pos = np.arange(w.n_ctx, dtype=np.int32)
     ref, _ = oracle.partial_attention(lay["q"], pos, lay["k_fresh"], lay["v_fresh"], 1.0)
     got, _ = run_gpu_attention(w, lay["q"], pos, lay["k_fresh"], lay["v_fresh"], 1.0)
-    assert np.abs(got - ref).max() <= 2e-2
+    assert_attn_close(got, ref, w)
 
 
 def test_partial_attention_ragged_batch():
@@ -286,7 +299,7 @@ def test_partial_attention_ragged_batch():
     pos = np.concatenate(sel)
     ref, ref_lse = oracle.partial_attention(q, pos, k, v, 1.0, off, lens, cu)
     got, lse = run_gpu_attention(w, q, pos, k, v, 1.0, off, lens, cu)
-    assert np.abs(got - ref).max() <= 2e-2
+    assert_attn_close(got, ref, w)
     np.testing.assert_allclose(lse, ref_lse, atol=2e-3)
 
 
@@ -351,7 +364,7 @@ def test_decode_check_parity(dtype):
             check_topk_band(ix[pos:pos + kreq[b]], ref_score[sl], kreq[b])
             pos += kreq[b]
         assert np.all(np.isnan(sc[int(off[0] + lens[0]): int(off[1])]))      # slack rows not written
-        assert np.abs(attn.float().cpu().numpy() - ref_attn).max() <= attn_tol(w)
+        assert_attn_close(attn.float().cpu().numpy(), ref_attn, w)
         # without the optional outputs the indices are the same
         idx2 = torch.full_like(idx, -1)
         B.kvs_decode_check(sh, rows, off, lens, g["q_new"][step].contiguous(), gk, None, dev_gpu, gr, 1.0, kreq,
@@ -413,4 +426,4 @@ def test_prefill_path_end_to_end(w):
     np.testing.assert_array_equal(oracle._as_np(gk.cpu()), kc)
     np.testing.assert_array_equal(oracle._as_np(gv.cpu()), vc)
     np.testing.assert_array_equal(gr.cpu().numpy(), reused)
-    assert np.abs(out.float().cpu().numpy() - ref).max() <= attn_tol(w)
+    assert_attn_close(out.float().cpu().numpy(), ref, w)
