@@ -106,7 +106,9 @@ extern "C" kvs_status kvs_partial_attention(const kvs_shape *shape, int32_t batc
     if (!aligned16(q_sel) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(out))
         return fail(KVS_EINVAL, "kvs_partial_attention: Q/K/V/out pointers must be 16-byte aligned");
     hipStream_t hs = (hipStream_t)stream;
-    const bool mfma = attention_mfma_supports(shape);
+    // the matrix-core kernel folds the scale into an exp2 argument and takes the row max before
+    // scaling, which needs scale > 0; anything else goes to the vector kernel
+    const bool mfma = attention_mfma_supports(shape) && scale > 0.f && scale < 3.0e38f;
     for (int32_t b0 = 0; b0 < batch; b0 += kAttnMaxReq) {
         const int nr = (batch - b0) < kAttnMaxReq ? (batch - b0) : kAttnMaxReq;
         AttnBatch bd;

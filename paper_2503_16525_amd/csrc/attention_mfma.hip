@@ -1,10 +1,339 @@
-// placeholder until the matrix-core kernel lands: reports no supported shape
+// Partial-recompute attention on the gfx950 matrix cores (bf16 in, fp32 accumulate), head_dim 128.
+// Computes Eq. (1) for the rows of the selected tokens only; each query attends causally, by its
+// original position, over the blended cache.
+//
+// Work decomposition
+//   * The G = n_q_heads / n_kv_heads query heads that share KV head g are flattened with the
+//     selected tokens into rows r = t*G + hh (t = selected token, ascending position).  Any G
+//     packs without padding (7 included): a row tile simply cuts the flattened list every
+//     32*NWAVES rows.
+//   * One workgroup = one KV head and one tile of 32*NWAVES rows; each wave owns 32 rows.  The
+//     workgroup streams K/V tiles of 64 keys through LDS from key 0 up to the largest position
+//     in its tile.  Only tiles that straddle a row's position need the causal compare; all
+//     tiles below the wave's smallest position take the unmasked path.
+//   * Workgroups are issued heaviest tile first, and KV head = blockIdx % n_kv_heads so that the
+//     workgroups resident on one XCD walk the same head's K/V and share it in that XCD's L2.
+//
+// Per KV tile, per wave (v_mfma_f32_32x32x16_bf16, 64-lane wavefront):
+//   S^T[key][q] = K[key][:] . Q[q][:]        A = K rows from LDS (16 B per lane), B = Q registers
+//   online softmax down each lane's own column (a query's 64 keys sit in two lanes, l and l^32)
+//   O^T[d][q]  += V^T[d][key] . P^T[key][q]  A = V^T rows from LDS, B = P straight from registers
+// Computing the transposed products makes the S accumulator layout coincide with the B-operand
+// layout of the second product, so P never leaves registers.  The K rows are fed to the first
+// product in a permuted order (bits 2 and 3 of the row index swapped) so that the 8 P values a
+// lane holds for one MFMA k-step belong to 8 consecutive keys, i.e. one 16-byte LDS read of V^T.
+// V is transposed on its way into LDS: lanes sweep head_dim in 4-byte steps for 8 consecutive
+// keys (coalesced 256 B per wave load), repack in registers, and write two 16-byte rows of V^T.
 #include "attention.h"
+
+#include <math.h>
+
 namespace kvs {
-bool attention_mfma_supports(const kvs_shape *) { return false; }
-kvs_status launch_attention_mfma(const kvs_shape *, const AttnBatch &, int64_t, const void *, const int32_t *,
-                                 const void *, const void *, float, void *, float *, hipStream_t)
+namespace {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
+
+constexpr int D = 128;            // head_dim
+constexpr int BN = 64;            // keys per LDS tile
+constexpr int K_LD = D + 8;       // K tile row pitch in bf16 (272 B: 16-byte reads of 16 rows hit 16 bank groups)
+constexpr int V_LD = BN + 8;      // V^T tile row pitch in bf16 (144 B)
+constexpr int K_TILE = BN * K_LD; // bf16 elements
+constexpr int V_TILE = D * V_LD;
+constexpr int STAGE = K_TILE + V_TILE;
+
+struct AttnTiles {
+    int64_t ctx_off[kAttnMaxReq];
+    int64_t cu_sel[kAttnMaxReq + 1];
+    int32_t ctx_len[kAttnMaxReq];
+    int32_t tile_begin[kAttnMaxReq + 1];
+    int32_t n_req;
+};
+
+__device__ __forceinline__ bf16x8 as_bf16x8(u32x4_t v) { return __builtin_bit_cast(bf16x8, v); }
+
+__device__ __forceinline__ uint32_t pack2(float lo, float hi)
 {
-    return fail(KVS_EUNSUPPORTED, "kvs_partial_attention: matrix-core path not built");
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    f32x2 f = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));
 }
+
+template <int NWAVES>
+__global__ __launch_bounds__(NWAVES * 64, 2) void attn_mfma_kernel(
+    const AttnTiles td, int n_q_heads, int n_kv_heads, int total_tiles,
+    const uint16_t *__restrict__ q_sel, const int32_t *__restrict__ sel_pos,
+    const uint16_t *__restrict__ k_cache, const uint16_t *__restrict__ v_cache,
+    float scale_log2, uint16_t *__restrict__ out, float *__restrict__ lse_out)
+{
+    constexpr int NT = NWAVES * 64;
+    constexpr int ROWS = NWAVES * 32;
+    constexpr int K_PIECES = BN * (D / 8) / NT;    // 16-byte K pieces per thread per tile
+    constexpr int V_ITEMS = (BN / 8) * (D / 2) / NT; // (key octet, channel pair) items per thread
+    extern __shared__ __attribute__((aligned(16))) uint16_t lds[];   // 2 stages of (K tile, V^T tile)
+    __shared__ int wg_max_pos[NWAVES];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int hf = lane >> 5, ln = lane & 31;
+
+    // ---- which (request, kv head, row tile) -----------------------------------------------------
+    const int g = blockIdx.x % n_kv_heads;
+    const int tile_lin = total_tiles - 1 - (int)(blockIdx.x / n_kv_heads);
+    int b = 0;
+    while (b + 1 < td.n_req && tile_lin >= td.tile_begin[b + 1]) ++b;
+    const int tile = tile_lin - td.tile_begin[b];
+    const int grp = n_q_heads / n_kv_heads;
+    const int64_t sel0 = td.cu_sel[b];
+    const int n_rows = (int)(td.cu_sel[b + 1] - sel0) * grp;
+    const int ctx_len = td.ctx_len[b];
+    const int64_t ctx_off = td.ctx_off[b];
+
+    // this lane's query row (both half-waves hold the same 32 queries)
+    const int rq = tile * ROWS + wave * 32 + ln;
+    const bool row_ok = rq < n_rows;
+    const int rqc = row_ok ? rq : n_rows - 1;
+    const int t_sel = rqc / grp, hh = rqc - t_sel * grp;
+    const int64_t s_glob = sel0 + t_sel;
+    int pos = sel_pos[s_glob];
+    pos = min(max(pos, 0), ctx_len - 1);             // memory safety; the caller guarantees the range
+    const int64_t q_row = (s_glob * n_q_heads + g * grp + hh) * (int64_t)D;
+
+    // wave-wide smallest / largest position
+    int pmin = pos, pmax = pos;
+#pragma unroll
+    for (int o = 1; o < 32; o <<= 1) {
+        pmin = min(pmin, __shfl_xor(pmin, o));
+        pmax = max(pmax, __shfl_xor(pmax, o));
+    }
+    if (lane == 0) wg_max_pos[wave] = pmax;
+
+    // ---- Q as the B operand: Q[query ln][16*ks + 8*hf + j] ----------------------------------------
+    bf16x8 qreg[D / 16];
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ++ks)
+        qreg[ks] = as_bf16x8(*reinterpret_cast<const u32x4_t *>(q_sel + q_row + 16 * ks + 8 * hf));
+
+    __syncthreads();
+    int wg_pmax = wg_max_pos[0];
+#pragma unroll
+    for (int w = 1; w < NWAVES; ++w) wg_pmax = max(wg_pmax, wg_max_pos[w]);
+    const int n_kv_tiles = wg_pmax / BN + 1;
+
+    // ---- global -> register staging of one K/V tile -------------------------------------------------
+    const int64_t kv_row_stride = (int64_t)n_kv_heads * D;      // bf16 elements between tokens
+    const uint16_t *kbase = k_cache + (ctx_off * n_kv_heads + g) * (int64_t)D;
+    const uint16_t *vbase = v_cache + (ctx_off * n_kv_heads + g) * (int64_t)D;
+    u32x4_t kst[K_PIECES];
+    uint32_t vst[V_ITEMS][8];
+
+    auto load_tile = [&](int kv0) {
+#pragma unroll
+        for (int i = 0; i < K_PIECES; ++i) {
+            const int id = i * NT + tid;
+            const int row = id >> 4, c16 = id & 15;
+            const int key = min(kv0 + row, ctx_len - 1);
+            kst[i] = *reinterpret_cast<const u32x4_t *>(kbase + key * kv_row_stride + c16 * 8);
+        }
+#pragma unroll
+        for (int it = 0; it < V_ITEMS; ++it) {
+            const int ko = wave + NWAVES * it;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int key = min(kv0 + 8 * ko + j, ctx_len - 1);
+                vst[it][j] = *reinterpret_cast<const uint32_t *>(vbase + key * kv_row_stride + 2 * lane);
+            }
+        }
+    };
+    auto store_tile = [&](int stage) {
+        uint16_t *ks = lds + stage * STAGE;
+        uint16_t *vs = ks + K_TILE;
+#pragma unroll
+        for (int i = 0; i < K_PIECES; ++i) {
+            const int id = i * NT + tid;
+            const int row = id >> 4, c16 = id & 15;
+            *reinterpret_cast<u32x4_t *>(ks + row * K_LD + c16 * 8) = kst[i];
+        }
+#pragma unroll
+        for (int it = 0; it < V_ITEMS; ++it) {
+            const int ko = wave + NWAVES * it;
+            u32x4_t lo, hi;   // channel 2*lane and 2*lane+1 of keys 8*ko .. 8*ko+7
+            lo.x = (vst[it][0] & 0xffffu) | (vst[it][1] << 16);
+            lo.y = (vst[it][2] & 0xffffu) | (vst[it][3] << 16);
+            lo.z = (vst[it][4] & 0xffffu) | (vst[it][5] << 16);
+            lo.w = (vst[it][6] & 0xffffu) | (vst[it][7] << 16);
+            hi.x = (vst[it][0] >> 16) | (vst[it][1] & 0xffff0000u);
+            hi.y = (vst[it][2] >> 16) | (vst[it][3] & 0xffff0000u);
+            hi.z = (vst[it][4] >> 16) | (vst[it][5] & 0xffff0000u);
+            hi.w = (vst[it][6] >> 16) | (vst[it][7] & 0xffff0000u);
+            *reinterpret_cast<u32x4_t *>(vs + (2 * lane) * V_LD + 8 * ko) = lo;
+            *reinterpret_cast<u32x4_t *>(vs + (2 * lane + 1) * V_LD + 8 * ko) = hi;
+        }
+    };
+
+    // ---- running softmax state and output accumulators ---------------------------------------------
+    floatx16 o_acc[D / 32];
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o_acc[db][r] = 0.f;
+    float m_run = -INFINITY;   // running max of scale*log2(e)*logit, shared by the two half-waves
+    float l_run = 0.f;         // this half-wave's share of the running sum
+
+    // K row fed to MFMA row ln: bits 2 and 3 swapped
+    const int krow = (ln & ~12) | ((ln & 4) << 1) | ((ln & 8) >> 1);
+
+    load_tile(0);
+    store_tile(0);
+    __syncthreads();
+
+    for (int jt = 0; jt < n_kv_tiles; ++jt) {
+        const int kv0 = jt * BN;
+        const int stage = jt & 1;
+        const bool more = jt + 1 < n_kv_tiles;
+        if (more) load_tile(kv0 + BN);
+
+        if (kv0 <= pmax) {                           // wave-uniform: this wave still has keys to see
+            const uint16_t *ks = lds + stage * STAGE;
+            const uint16_t *vs = ks + K_TILE;
+            floatx16 s_acc[2];
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) s_acc[kb][r] = 0.f;
+#pragma unroll
+            for (int ksx = 0; ksx < D / 16; ++ksx) {
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb) {
+                    const u32x4_t a = *reinterpret_cast<const u32x4_t *>(ks + (32 * kb + krow) * K_LD + 16 * ksx + 8 * hf);
+                    s_acc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a), qreg[ksx], s_acc[kb], 0, 0, 0);
+                }
+            }
+            // causal compare only where a key of this tile can exceed a position of this wave
+            if (kv0 + BN - 1 > pmin) {
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int key = kv0 + 32 * kb + 16 * (r >> 3) + 8 * hf + (r & 7);
+                        if (key > pos) s_acc[kb][r] = -INFINITY;
+                    }
+            }
+            float mx = s_acc[0][0];
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s_acc[kb][r]);
+            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            const float m_new = fmaxf(m_run, mx * scale_log2);
+            const float corr = __builtin_amdgcn_exp2f(m_run - m_new);
+            m_run = m_new;
+            float psum = 0.f;
+            u32x4_t pop[2][2];                          // B operands of the second product: [kb][a]
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb) {
+                float pv[16];
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    pv[r] = __builtin_amdgcn_exp2f(fmaf(s_acc[kb][r], scale_log2, -m_new));
+                    psum += pv[r];
+                }
+#pragma unroll
+                for (int a = 0; a < 2; ++a) {
+                    pop[kb][a].x = pack2(pv[8 * a + 0], pv[8 * a + 1]);
+                    pop[kb][a].y = pack2(pv[8 * a + 2], pv[8 * a + 3]);
+                    pop[kb][a].z = pack2(pv[8 * a + 4], pv[8 * a + 5]);
+                    pop[kb][a].w = pack2(pv[8 * a + 6], pv[8 * a + 7]);
+                }
+            }
+            l_run = l_run * corr + psum;
+#pragma unroll
+            for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) o_acc[db][r] *= corr;
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int a = 0; a < 2; ++a) {
+                    const int kstep = 2 * kb + a;
+#pragma unroll
+                    for (int db = 0; db < D / 32; ++db) {
+                        const u32x4_t va = *reinterpret_cast<const u32x4_t *>(vs + (32 * db + ln) * V_LD + 16 * kstep + 8 * hf);
+                        o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(va), as_bf16x8(pop[kb][a]), o_acc[db], 0, 0, 0);
+                    }
+                }
+        }
+        if (more) store_tile(stage ^ 1);
+        __syncthreads();
+    }
+
+    // ---- epilogue: normalise, convert, store ----------------------------------------------------------
+    const float l_tot = l_run + __shfl_xor(l_run, 32);
+    const float inv = 1.0f / l_tot;
+    if (row_ok) {
+        uint16_t *orow = out + q_row;
+#pragma unroll
+        for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+            for (int r4 = 0; r4 < 4; ++r4) {
+                const int d0 = 32 * db + 8 * r4 + 4 * hf;
+                uint2 w;
+                w.x = pack2(o_acc[db][4 * r4 + 0] * inv, o_acc[db][4 * r4 + 1] * inv);
+                w.y = pack2(o_acc[db][4 * r4 + 2] * inv, o_acc[db][4 * r4 + 3] * inv);
+                *reinterpret_cast<uint2 *>(orow + d0) = w;
+            }
+        if (lse_out && hf == 0)
+            lse_out[s_glob * n_q_heads + g * grp + hh] = (m_run + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f;
+    }
+}
+
+} // namespace
+
+bool attention_mfma_supports(const kvs_shape *shape)
+{
+    return shape->dtype == KVS_BF16 && shape->head_dim == D;
+}
+
+kvs_status launch_attention_mfma(const kvs_shape *shape, const AttnBatch &bd, int64_t n_sel,
+                                 const void *q_sel, const int32_t *sel_pos, const void *k_cache,
+                                 const void *v_cache, float scale, void *out, float *lse_out,
+                                 hipStream_t st)
+{
+    if (!attention_mfma_supports(shape)) return fail(KVS_EUNSUPPORTED, "kvs_partial_attention: matrix-core path needs bf16, head_dim 128");
+    if (!(scale > 0.f) || !isfinite(scale)) return fail(KVS_EUNSUPPORTED, "kvs_partial_attention: matrix-core path needs a positive finite scale");
+    constexpr int NWAVES = 4;
+    constexpr int ROWS = NWAVES * 32;
+    const int grp = shape->n_q_heads / shape->n_kv_heads;
+    AttnTiles td;
+    int64_t tiles = 0;
+    for (int i = 0; i < kAttnMaxReq; ++i) {
+        const bool live = i < bd.n_req;
+        td.ctx_off[i] = live ? bd.ctx_off[i] : 0;
+        td.ctx_len[i] = live ? (int32_t)bd.ctx_len[i] : 0;
+        td.cu_sel[i] = bd.cu_sel[i];
+        td.tile_begin[i] = (int32_t)tiles;
+        if (live) tiles += ((bd.cu_sel[i + 1] - bd.cu_sel[i]) * grp + ROWS - 1) / ROWS;
+        if (tiles * shape->n_kv_heads > 0x7fffffffLL) return fail(KVS_EINVAL, "kvs_partial_attention: too many row tiles");
+    }
+    td.cu_sel[kAttnMaxReq] = bd.cu_sel[kAttnMaxReq];
+    td.tile_begin[kAttnMaxReq] = (int32_t)tiles;
+    td.n_req = bd.n_req;
+    (void)n_sel;
+    if (tiles == 0) return KVS_OK;
+    const size_t lds_bytes = 2 * STAGE * sizeof(uint16_t);
+    static bool attr_set = false;   // idempotent; a race only repeats the same call
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_mfma_kernel<NWAVES>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+        if (e != hipSuccess) return fail(KVS_EHIP, "kvs_partial_attention: hipFuncSetAttribute: %s", hipGetErrorString(e));
+        attr_set = true;
+    }
+    const float scale_log2 = scale * 1.4426950408889634f;
+    hipLaunchKernelGGL((attn_mfma_kernel<NWAVES>), dim3((unsigned)(tiles * shape->n_kv_heads)), dim3(NWAVES * 64),
+                       lds_bytes, st, td, shape->n_q_heads, shape->n_kv_heads, (int)tiles,
+                       (const uint16_t *)q_sel, sel_pos, (const uint16_t *)k_cache, (const uint16_t *)v_cache,
+                       scale_log2, (uint16_t *)out, lse_out);
+    return check_launch("kvs_partial_attention(mfma)");
+}
+
 } // namespace kvs
