@@ -1,0 +1,325 @@
+#!/usr/bin/env python3
+"""Benchmark of the DHD hot path on one MI355X.
+
+A *step* is one pass of the whole hot path over one layer of the Llama-3.1-8B-shaped 32k-context
+workload (32 query heads, 8 KV heads, head_dim 128, bf16, ~90 % of the context reused):
+
+    prefill   kvs_deviation -> kvs_select_topk -> kvs_scatter_kv -> kvs_partial_attention
+    decode    kvs_decode_check (one new token) -> kvs_scatter_kv -> kvs_partial_attention
+
+Every step runs on its own layer's buffers (independent random projection weights per layer, as
+in the 32-layer stack), so each layer's K/V stream comes from HBM, not from a warm cache.  Inputs
+are resident in HBM before the timed region.  The rows that the recomputation would produce
+(q/k/v of the selected tokens) are gathered once in an untimed set-up pass -- producing them is
+the model's projection GEMMs, which are outside this path -- while the index lists the timed
+kernels consume are the ones the timed select / decode-check calls write.
+
+Prints ONE JSON line: whole-step throughput, the dominant kernel's roofline, per-call components
+and the CPU oracle timed on the host cores on a bounded sample of the same layer.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+from paper_2503_16525_amd import binding as B  # noqa: E402
+from paper_2503_16525_amd import synth  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 MFMA rate
+MAX_SLOTS = 64
+DECODE_RATIO = 0.02
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+class Slot:
+    """One layer's device buffers plus everything the timed step needs."""
+
+
+def attention_flops(pos: torch.Tensor, n_q_heads: int, d: int) -> float:
+    # QK^T and PV: 2 products x 2 flops x d per (query head, key), keys 0..p inclusive
+    return 4.0 * d * n_q_heads * float((pos.double() + 1).sum().item())
+
+
+def build_slot(w, layer: int, ratio: float, sh, alpha) -> Slot:
+    dev = "cuda"
+    n, hk, hq, d = w.n_ctx, w.n_kv_heads, w.n_q_heads, w.head_dim
+    lay = synth.make_layer(w, layer=layer, device=dev, projected=True)
+    s = Slot()
+    s.n = n
+    s.k_fresh, s.v_fresh = lay["k_fresh"], lay["v_fresh"]
+    # cache with one spare row for the decode token (appended before the timed region)
+    g = torch.Generator(device=dev)
+    g.manual_seed(synth.layer_seed(w, layer, salt=11))
+    tok = torch.randn((3, 1, max(hq, hk), d), generator=g, device=dev)
+    s.k_cache = torch.cat([lay["k_cache"], tok[0, :, :hk].to(torch.bfloat16)]).contiguous()
+    s.v_cache = torch.cat([lay["v_cache"], tok[1, :, :hk].to(torch.bfloat16)]).contiguous()
+    s.q_dec = (tok[2, :, :hq] / math.sqrt(d)).to(torch.bfloat16).contiguous()       # [1, Hq, d]
+    s.reused = torch.cat([lay["reused"], torch.zeros(1, dtype=torch.uint8, device=dev)]).contiguous()
+    s.reused0 = s.reused.clone()
+    s.n_reused = int(lay["reused"].sum().item())
+    s.k = synth.recompute_budget(s.n_reused, ratio)
+    s.k_dec = int(math.ceil(DECODE_RATIO * (n + 1)))
+    rows = n + 1
+    s.rows = rows
+    s.dev_v = torch.zeros((hk, rows), device=dev)
+    s.score = torch.empty((n,), device=dev)
+    s.idx = torch.empty((s.k,), dtype=torch.int32, device=dev)
+    s.idx_dec = torch.empty((s.k_dec,), dtype=torch.int32, device=dev)
+    s.out = torch.empty((s.k, hq, d), dtype=torch.bfloat16, device=dev)
+    s.out_dec = torch.empty((s.k_dec, hq, d), dtype=torch.bfloat16, device=dev)
+    s.alpha = alpha
+    # ---- untimed set-up pass: find what the step will select, gather the recomputed rows ----
+    q_full = lay["q"]
+    k0, v0 = s.k_cache.clone(), s.v_cache.clone()
+    B.kvs_deviation(sh, n, None, s.v_fresh, None, s.v_cache, s.reused, alpha, B.SCORE_V, None, s.dev_v, s.score)
+    B.kvs_select_topk(s.score, [0, n], [s.k], s.idx)
+    li = s.idx.long()
+    s.q_sel, s.k_new, s.v_new = q_full[li].contiguous(), s.k_fresh[li].contiguous(), s.v_fresh[li].contiguous()
+    B.kvs_scatter_kv(sh, rows, s.k_new, s.v_new, s.idx, s.k, s.k_cache, s.v_cache, s.reused, s.dev_v)
+    B.kvs_decode_check(sh, rows, [0], [rows], s.q_dec, s.k_cache, None, s.dev_v, s.reused, 1.0, [s.k_dec],
+                       s.idx_dec, None, None, WS)
+    ld = s.idx_dec.long()
+    s.q_sel_dec, s.k_new_dec, s.v_new_dec = q_full[ld].contiguous(), s.k_fresh[ld].contiguous(), s.v_fresh[ld].contiguous()
+    s.flops = attention_flops(s.idx, hq, d)
+    s.flops_dec = attention_flops(s.idx_dec, hq, d)
+    # rows to put back when a slot is used a second time
+    both = torch.cat([li, ld])
+    s.idx_all = both.to(torch.int32).contiguous()
+    s.k_orig, s.v_orig = k0[both].contiguous(), v0[both].contiguous()
+    s.k_cache.copy_(k0)
+    s.v_cache.copy_(v0)
+    s.reused.copy_(s.reused0)
+    s.idx.fill_(-1)
+    s.idx_dec.fill_(-1)
+    del q_full, lay, k0, v0
+    return s
+
+
+def restore_slot(s: Slot, sh) -> None:
+    B.kvs_scatter_kv(sh, s.rows, s.k_orig, s.v_orig, s.idx_all, s.idx_all.numel(), s.k_cache, s.v_cache, None, None)
+    s.reused.copy_(s.reused0)
+
+
+def run_step(s: Slot, sh, ev=None) -> None:
+    """The timed work: seven C-ABI calls on the current stream, no host synchronisation."""
+    n, rows = s.n, s.rows
+    if ev:
+        ev[0].record()
+    B.kvs_deviation(sh, n, None, s.v_fresh, None, s.v_cache, s.reused, s.alpha, B.SCORE_V, None, s.dev_v, s.score)
+    B.kvs_select_topk(s.score, [0, n], [s.k], s.idx)
+    if ev:
+        ev[1].record()
+    B.kvs_scatter_kv(sh, rows, s.k_new, s.v_new, s.idx, s.k, s.k_cache, s.v_cache, s.reused, s.dev_v)
+    if ev:
+        ev[2].record()
+    B.kvs_partial_attention(sh, [0], [rows], [0, s.k], s.q_sel, s.idx, s.k_cache, s.v_cache, 1.0, s.out)
+    if ev:
+        ev[3].record()
+    B.kvs_decode_check(sh, rows, [0], [rows], s.q_dec, s.k_cache, None, s.dev_v, s.reused, 1.0, [s.k_dec],
+                       s.idx_dec, None, None, WS)
+    if ev:
+        ev[4].record()
+    B.kvs_scatter_kv(sh, rows, s.k_new_dec, s.v_new_dec, s.idx_dec, s.k_dec, s.k_cache, s.v_cache, s.reused, s.dev_v)
+    B.kvs_partial_attention(sh, [0], [rows], [0, s.k_dec], s.q_sel_dec, s.idx_dec, s.k_cache, s.v_cache, 1.0, s.out_dec)
+    if ev:
+        ev[5].record()
+
+
+WS = None
+
+
+def cpu_baseline_and_parity(w, ratio: float, sh, alpha, n_sample: int) -> dict:
+    """Oracle on the host cores over layer 0 of the same workload: deviation/select/scatter in
+    full, attention on an evenly spaced sample of the selected queries.  The same oracle results
+    double as a parity check of the GPU path on this exact input."""
+    import oracle
+    n, hk, hq, d = w.n_ctx, w.n_kv_heads, w.n_q_heads, w.head_dim
+    lay = synth.make_layer(w, layer=0, device="cuda", projected=True)
+    host = {k: v.cpu() for k, v in lay.items()}
+    alpha_h = alpha.cpu() if alpha is not None else None
+    times = {}
+    t0 = time.perf_counter()
+    _, dev_ref, score_ref = oracle.deviation(host["v_fresh"], host["v_cache"], reused=host["reused"], alpha=alpha_h)
+    times["deviation_ms"] = (time.perf_counter() - t0) * 1e3
+    k = synth.recompute_budget(int(host["reused"].sum()), ratio)
+    t0 = time.perf_counter()
+    idx_ref = oracle.select_topk(score_ref, [0, n], [k])
+    times["select_ms"] = (time.perf_counter() - t0) * 1e3
+    li = torch.from_numpy(idx_ref.astype(np.int64))
+    kc, vc = oracle._as_np(host["k_cache"]).copy(), oracle._as_np(host["v_cache"]).copy()
+    k_new, v_new = host["k_fresh"][li].contiguous(), host["v_fresh"][li].contiguous()
+    t0 = time.perf_counter()
+    oracle.scatter_kv(k_new, v_new, idx_ref, kc, vc)
+    times["scatter_ms"] = (time.perf_counter() - t0) * 1e3
+    pick = np.unique(np.linspace(0, k - 1, n_sample).round().astype(np.int64))
+    pos_s = idx_ref[pick]
+    q_s = host["q"][li[pick]].contiguous()
+    t0 = time.perf_counter()
+    out_ref, _ = oracle.partial_attention(q_s, pos_s, kc, vc, 1.0)
+    t_att = time.perf_counter() - t0
+    fl = 4.0 * d * hq * float((pos_s.astype(np.float64) + 1).sum())
+    times["attention_sample_ms"] = t_att * 1e3
+    # ---- parity of the GPU path on the same input ----
+    dev_v = torch.empty((hk, n), device="cuda")
+    score = torch.empty((n,), device="cuda")
+    B.kvs_deviation(sh, n, None, lay["v_fresh"], None, lay["v_cache"], lay["reused"], alpha, B.SCORE_V, None, dev_v, score)
+    sc = score.cpu().numpy()
+    fin = np.isfinite(score_ref)
+    assert np.array_equal(np.isfinite(sc), fin), "candidate mask differs from the oracle"
+    np.testing.assert_allclose(sc[fin], score_ref[fin], rtol=1e-5)
+    idx = torch.empty((k,), dtype=torch.int32, device="cuda")
+    B.kvs_select_topk(torch.from_numpy(score_ref).cuda(), [0, n], [k], idx)
+    assert np.array_equal(idx.cpu().numpy(), idx_ref), "top-k differs from the oracle"
+    gk, gv = lay["k_cache"].clone(), lay["v_cache"].clone()
+    B.kvs_scatter_kv(sh, n, k_new.cuda(), v_new.cuda(), idx, k, gk, gv, None, None)
+    assert np.array_equal(oracle._as_np(gk.cpu()), kc) and np.array_equal(oracle._as_np(gv.cpu()), vc)
+    out = torch.empty((len(pick), hq, d), dtype=torch.bfloat16, device="cuda")
+    B.kvs_partial_attention(sh, [0], [n], [0, len(pick)], q_s.cuda(), torch.from_numpy(pos_s).cuda(), gk, gv, 1.0, out)
+    err = np.abs(out.float().cpu().numpy() - out_ref)
+    tol = np.maximum(2e-2, np.abs(out_ref) * 2.0 ** -8)
+    assert np.all(err <= tol), f"attention differs from the oracle by {err.max()}"
+    log(f"[bench] parity vs oracle on layer 0: scores rtol 1e-5 ok, top-{k} exact, scatter exact, "
+        f"attention max err {err.max():.4f} on {len(pick)} sampled queries")
+    return {
+        "value": fl / t_att / 1e12, "unit": "TFLOP/s", "cores": oracle.max_threads(), "kind": "oracle",
+        "sample": (f"layer 0 of the same workload: attention on {len(pick)} of {k} selected queries x {hq} heads "
+                   f"(evenly spaced, {fl / 1e9:.1f} GFLOP, {t_att:.1f} s); deviation/select/scatter on the full layer"),
+        "deviation_ms": times["deviation_ms"], "select_ms": times["select_ms"], "scatter_ms": times["scatter_ms"],
+        "attention_extrapolated_ms_per_layer": None,
+    }
+
+
+def read_traffic(kernel: str):
+    """HBM bytes per launch of `kernel`, if a committed rocprofv3 --pmc summary states it."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.md")
+    try:
+        for line in open(path):
+            if line.startswith("|") and kernel in line and "bytes_per_launch" in line:
+                return float(line.split("bytes_per_launch=")[1].split()[0].strip("|"))
+    except OSError:
+        pass
+    return None
+
+
+def main() -> int:
+    global WS
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--ratio", type=float, default=0.15, help="recompute ratio (fraction of reused tokens)")
+    ap.add_argument("--alpha", choices=["none", "synthetic"], default="none",
+                    help="attention column mass fed to kvs_deviation: none = magnitude-only score (alpha = 1), "
+                         "synthetic = a harmonic-tail profile (the exact O(N^2) alpha is not affordable at 32k)")
+    ap.add_argument("--cpu-sample", type=int, default=256, help="selected queries in the oracle's attention sample (0 = skip the CPU leg)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build is single-GPU by design (one process, one MI355X); run with --gpus 1",
+              file=sys.stderr)
+        return 2
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    B.load(build_if_missing=True)
+    w = synth.LLAMA
+    sh = B.shape_of(w)
+    n, hk, hq, d = w.n_ctx, w.n_kv_heads, w.n_q_heads, w.head_dim
+    WS = torch.empty(B.kvs_workspace_size("decode_check", sh, 1, n + 1), dtype=torch.uint8, device="cuda")
+    alpha_n = synth.synthetic_alpha(w, device="cuda") if args.alpha == "synthetic" else None
+
+    n_slots = max(1, min(args.warmup + args.steps, MAX_SLOTS))
+    t0 = time.perf_counter()
+    slots = [build_slot(w, layer, args.ratio, sh, alpha_n) for layer in range(n_slots)]
+    torch.cuda.synchronize()
+    log(f"[bench] {n_slots} layers resident ({torch.cuda.memory_allocated() / 2**30:.1f} GiB) in {time.perf_counter() - t0:.1f} s; "
+        f"k={slots[0].k} of {slots[0].n_reused} reused, decode k={slots[0].k_dec}")
+
+    used = [False] * n_slots
+
+    def step(i: int, ev=None):
+        s = slots[i % n_slots]
+        if used[i % n_slots]:
+            restore_slot(s, sh)      # only when --steps + --warmup exceeds the resident layers
+        used[i % n_slots] = True
+        run_step(s, sh, ev)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i, events[i])
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t_start) * 1e3
+    ms_per_step = wall_ms / args.steps
+
+    seg = np.array([[ev[j].elapsed_time(ev[j + 1]) for j in range(5)] for ev in events])  # ms
+    t_devsel, t_scat, t_attn, t_dec, t_decrec = seg.mean(0)
+    used_slots = [slots[(args.warmup + i) % n_slots] for i in range(args.steps)]
+    flops = float(np.mean([s.flops for s in used_slots]))
+    flops_dec = float(np.mean([s.flops_dec for s in used_slots]))
+    k_mean = float(np.mean([s.k for s in used_slots]))
+    se = 2
+    row_b = hk * d * se
+    # V fresh + cache in, mask in, (alpha in), dev_v out, score out
+    bytes_dev = 2 * n * row_b + n + 4 * n * hk * (2 if alpha_n is not None else 1) + 4 * n
+    bytes_sel = 4 * n + 4 * k_mean
+    bytes_scat = 4 * k_mean * row_b + 4 * k_mean
+    bytes_dec = (n + 1) * (row_b + 4 * hk + 1) + 4 * slots[0].k_dec
+
+    attn_tflops = flops / (t_attn * 1e-3) / 1e12
+    result = {
+        "metric": "partial-recompute attention TFLOP/s + deviation/select GB/s per layer, % roofline",
+        "value": (flops + flops_dec) / (ms_per_step * 1e-3) / 1e12,
+        "unit": "TFLOP/s",
+        "value_definition": "exact attention flops of the step (prefill selection + decode recompute) / whole-step time, all seven calls included",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{w.name}: {hq} q heads, {hk} kv heads, head_dim {d}, context {n}, "
+                               f"~90% reused in geometric spans (mean 512), lognormal(-3,1.5) cache deviation, "
+                               f"recompute ratio {args.ratio}, alpha {args.alpha}, decode re-check 2% of cache entries; "
+                               f"one step = one layer of the 32-layer stack",
+                   "layers_resident": n_slots, "k_selected": k_mean, "k_decode": slots[0].k_dec},
+        "roofline": {"kernel": "attn_mfma_kernel (kvs_partial_attention, prefill selection)", "bound": "mfma",
+                     "achieved": attn_tflops, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": attn_tflops / MFMA_BF16_PEAK_TFLOPS, "traffic": read_traffic("attn_mfma_kernel"),
+                     "flops_per_launch": flops, "avg_launch_ms": float(t_attn)},
+        "components": {
+            "deviation_select": {"ms": float(t_devsel), "GBps": (bytes_dev + bytes_sel) / (t_devsel * 1e-3) / 1e9,
+                                 "frac_hbm": (bytes_dev + bytes_sel) / (t_devsel * 1e-3) / 1e9 / HBM_PEAK_GBS},
+            "scatter": {"ms": float(t_scat), "GBps": bytes_scat / (t_scat * 1e-3) / 1e9,
+                        "frac_hbm": bytes_scat / (t_scat * 1e-3) / 1e9 / HBM_PEAK_GBS},
+            "partial_attention": {"ms": float(t_attn), "TFLOPs": attn_tflops, "frac_mfma": attn_tflops / MFMA_BF16_PEAK_TFLOPS},
+            "decode_check": {"ms": float(t_dec), "GBps": bytes_dec / (t_dec * 1e-3) / 1e9,
+                             "frac_hbm": bytes_dec / (t_dec * 1e-3) / 1e9 / HBM_PEAK_GBS},
+            "decode_recompute": {"ms": float(t_decrec), "attention_TFLOP": flops_dec / 1e12},
+        },
+    }
+    if args.cpu_sample > 0:
+        cb = cpu_baseline_and_parity(w, args.ratio, sh, alpha_n, args.cpu_sample)
+        cb["attention_extrapolated_ms_per_layer"] = flops / (cb["value"] * 1e12) * 1e3
+        result["cpu_baseline"] = cb
+    else:
+        result["cpu_baseline"] = None
+    print(json.dumps(result), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
