@@ -121,28 +121,45 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_mfma_kernel(
     const int n_kv_tiles = wg_pmax / BN + 1;
 
     // ---- global -> register staging of one K/V tile -------------------------------------------------
-    const int64_t kv_row_stride = (int64_t)n_kv_heads * D;      // bf16 elements between tokens
-    const uint16_t *kbase = k_cache + (ctx_off * n_kv_heads + g) * (int64_t)D;
-    const uint16_t *vbase = v_cache + (ctx_off * n_kv_heads + g) * (int64_t)D;
+    // Addresses are a wave-uniform tile base (scalar registers) plus a per-lane 32-bit byte offset
+    // that never changes, so the loop carries no vector address arithmetic.  Only a tile that
+    // reaches past the end of the context (the last one of a request) clamps its rows.
+    const uint32_t row_bytes = (uint32_t)n_kv_heads * D * 2u;          // bytes between tokens
+    const char *kbase = reinterpret_cast<const char *>(k_cache + (ctx_off * n_kv_heads + g) * (int64_t)D);
+    const char *vbase = reinterpret_cast<const char *>(v_cache + (ctx_off * n_kv_heads + g) * (int64_t)D);
     u32x4_t kst[K_PIECES];
     uint32_t vst[V_ITEMS][8];
+    const uint32_t k_lane_off = (uint32_t)(tid >> 4) * row_bytes + (uint32_t)(tid & 15) * 16u;
+    const uint32_t v_lane_off = (uint32_t)lane * 4u;
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
 
     auto load_tile = [&](int kv0) {
+        const char *kt = kbase + (int64_t)kv0 * row_bytes;
+        const char *vt = vbase + (int64_t)kv0 * row_bytes;
+        if (kv0 + BN <= ctx_len) {
 #pragma unroll
-        for (int i = 0; i < K_PIECES; ++i) {
-            const int id = i * NT + tid;
-            const int row = id >> 4, c16 = id & 15;
-            const int key = min(kv0 + row, ctx_len - 1);
-            kst[i] = *reinterpret_cast<const u32x4_t *>(kbase + key * kv_row_stride + c16 * 8);
-        }
+            for (int i = 0; i < K_PIECES; ++i)
+                kst[i] = *reinterpret_cast<const u32x4_t *>(kt + (size_t)(i * (NT / 16)) * row_bytes + k_lane_off);
 #pragma unroll
-        for (int it = 0; it < V_ITEMS; ++it) {
-            const int ko = wave + NWAVES * it;
+            for (int it = 0; it < V_ITEMS; ++it) {
+                const char *vo = vt + (size_t)(8 * (wave_u + NWAVES * it)) * row_bytes;
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const int key = min(kv0 + 8 * ko + j, ctx_len - 1);
-                vst[it][j] = *reinterpret_cast<const uint32_t *>(vbase + key * kv_row_stride + 2 * lane);
+                for (int j = 0; j < 8; ++j)
+                    vst[it][j] = *reinterpret_cast<const uint32_t *>(vo + (size_t)j * row_bytes + v_lane_off);
             }
+        } else {
+#pragma unroll
+            for (int i = 0; i < K_PIECES; ++i) {
+                const int key = min(kv0 + i * (NT / 16) + (tid >> 4), ctx_len - 1);
+                kst[i] = *reinterpret_cast<const u32x4_t *>(kbase + (int64_t)key * row_bytes + (tid & 15) * 16);
+            }
+#pragma unroll
+            for (int it = 0; it < V_ITEMS; ++it)
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const int key = min(kv0 + 8 * (wave_u + NWAVES * it) + j, ctx_len - 1);
+                    vst[it][j] = *reinterpret_cast<const uint32_t *>(vbase + (int64_t)key * row_bytes + v_lane_off);
+                }
         }
     };
     auto store_tile = [&](int stage) {
@@ -158,14 +175,15 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_mfma_kernel(
         for (int it = 0; it < V_ITEMS; ++it) {
             const int ko = wave + NWAVES * it;
             u32x4_t lo, hi;   // channel 2*lane and 2*lane+1 of keys 8*ko .. 8*ko+7
-            lo.x = (vst[it][0] & 0xffffu) | (vst[it][1] << 16);
-            lo.y = (vst[it][2] & 0xffffu) | (vst[it][3] << 16);
-            lo.z = (vst[it][4] & 0xffffu) | (vst[it][5] << 16);
-            lo.w = (vst[it][6] & 0xffffu) | (vst[it][7] << 16);
-            hi.x = (vst[it][0] >> 16) | (vst[it][1] & 0xffff0000u);
-            hi.y = (vst[it][2] >> 16) | (vst[it][3] & 0xffff0000u);
-            hi.z = (vst[it][4] >> 16) | (vst[it][5] & 0xffff0000u);
-            hi.w = (vst[it][6] >> 16) | (vst[it][7] & 0xffff0000u);
+            // v_perm_b32: bytes 0-3 come from the second operand, 4-7 from the first
+            lo.x = __builtin_amdgcn_perm(vst[it][1], vst[it][0], 0x05040100u);
+            lo.y = __builtin_amdgcn_perm(vst[it][3], vst[it][2], 0x05040100u);
+            lo.z = __builtin_amdgcn_perm(vst[it][5], vst[it][4], 0x05040100u);
+            lo.w = __builtin_amdgcn_perm(vst[it][7], vst[it][6], 0x05040100u);
+            hi.x = __builtin_amdgcn_perm(vst[it][1], vst[it][0], 0x07060302u);
+            hi.y = __builtin_amdgcn_perm(vst[it][3], vst[it][2], 0x07060302u);
+            hi.z = __builtin_amdgcn_perm(vst[it][5], vst[it][4], 0x07060302u);
+            hi.w = __builtin_amdgcn_perm(vst[it][7], vst[it][6], 0x07060302u);
             *reinterpret_cast<u32x4_t *>(vs + (2 * lane) * V_LD + 8 * ko) = lo;
             *reinterpret_cast<u32x4_t *>(vs + (2 * lane + 1) * V_LD + 8 * ko) = hi;
         }
@@ -246,11 +264,16 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_mfma_kernel(
                     pop[kb][a].w = pack2(pv[8 * a + 6], pv[8 * a + 7]);
                 }
             }
-            l_run = l_run * corr + psum;
+            // rescale the running sum and the output accumulators only when some row's max moved
+            // (wave-uniform test; after the first few tiles it rarely does)
+            if (__builtin_amdgcn_ballot_w64(corr != 1.0f) != 0) {
+                l_run *= corr;
 #pragma unroll
-            for (int db = 0; db < D / 32; ++db)
+                for (int db = 0; db < D / 32; ++db)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) o_acc[db][r] *= corr;
+                    for (int r = 0; r < 16; ++r) o_acc[db][r] *= corr;
+            }
+            l_run += psum;
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
