@@ -34,6 +34,10 @@ namespace {
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
 
+#ifndef KVS_ATTN_NWAVES
+#define KVS_ATTN_NWAVES 8
+#endif
+
 constexpr int D = 128;            // head_dim
 constexpr int BN = 64;            // keys per LDS tile
 constexpr int K_LD = D + 8;       // K tile row pitch in bf16 (272 B: 16-byte reads of 16 rows hit 16 bank groups)
@@ -310,21 +314,12 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_mfma_kernel(
     }
 }
 
-} // namespace
 
-bool attention_mfma_supports(const kvs_shape *shape)
+template <int NWAVES>
+kvs_status launch_mfma_variant(const kvs_shape *shape, const AttnBatch &bd, const void *q_sel, const int32_t *sel_pos,
+                               const void *k_cache, const void *v_cache, float scale, void *out, float *lse_out,
+                               hipStream_t st)
 {
-    return shape->dtype == KVS_BF16 && shape->head_dim == D;
-}
-
-kvs_status launch_attention_mfma(const kvs_shape *shape, const AttnBatch &bd, int64_t n_sel,
-                                 const void *q_sel, const int32_t *sel_pos, const void *k_cache,
-                                 const void *v_cache, float scale, void *out, float *lse_out,
-                                 hipStream_t st)
-{
-    if (!attention_mfma_supports(shape)) return fail(KVS_EUNSUPPORTED, "kvs_partial_attention: matrix-core path needs bf16, head_dim 128");
-    if (!(scale > 0.f) || !isfinite(scale)) return fail(KVS_EUNSUPPORTED, "kvs_partial_attention: matrix-core path needs a positive finite scale");
-    constexpr int NWAVES = 4;
     constexpr int ROWS = NWAVES * 32;
     const int grp = shape->n_q_heads / shape->n_kv_heads;
     AttnTiles td;
@@ -341,7 +336,6 @@ kvs_status launch_attention_mfma(const kvs_shape *shape, const AttnBatch &bd, in
     td.cu_sel[kAttnMaxReq] = bd.cu_sel[kAttnMaxReq];
     td.tile_begin[kAttnMaxReq] = (int32_t)tiles;
     td.n_req = bd.n_req;
-    (void)n_sel;
     if (tiles == 0) return KVS_OK;
     const size_t lds_bytes = 2 * STAGE * sizeof(uint16_t);
     static bool attr_set = false;   // idempotent; a race only repeats the same call
@@ -357,6 +351,24 @@ kvs_status launch_attention_mfma(const kvs_shape *shape, const AttnBatch &bd, in
                        (const uint16_t *)q_sel, sel_pos, (const uint16_t *)k_cache, (const uint16_t *)v_cache,
                        scale_log2, (uint16_t *)out, lse_out);
     return check_launch("kvs_partial_attention(mfma)");
+}
+
+
+} // namespace
+
+bool attention_mfma_supports(const kvs_shape *shape)
+{
+    return shape->dtype == KVS_BF16 && shape->head_dim == D;
+}
+
+kvs_status launch_attention_mfma(const kvs_shape *shape, const AttnBatch &bd, int64_t n_sel,
+                                 const void *q_sel, const int32_t *sel_pos, const void *k_cache,
+                                 const void *v_cache, float scale, void *out, float *lse_out,
+                                 hipStream_t st)
+{
+    if (!attention_mfma_supports(shape)) return fail(KVS_EUNSUPPORTED, "kvs_partial_attention: matrix-core path needs bf16, head_dim 128");
+    if (!(scale > 0.f) || !isfinite(scale)) return fail(KVS_EUNSUPPORTED, "kvs_partial_attention: matrix-core path needs a positive finite scale");
+    return launch_mfma_variant<KVS_ATTN_NWAVES>(shape, bd, q_sel, sel_pos, k_cache, v_cache, scale, out, lse_out, st);
 }
 
 } // namespace kvs

@@ -3,10 +3,11 @@
 //     score_i = sum_g ( sum_{h in g} softmax_i(scale * q_h . K_i) ) * dev_v[g,i]
 //
 // Kernels, all on the caller's stream:
-//   1. logits     streams K once (16-byte pieces, LPH lanes per (token, kv head) cell, DPP
-//                 reduction as in the deviation kernel) and writes scale*q.K for every query head
-//                 to the workspace as fp32 [n_q_heads][n_rows];
-//   2. stats      per (request, head): softmax max and normaliser over the context;
+//   1. logits     streams K once (16-byte pieces, LPH lanes per (token, kv head) cell, the group's
+//                 query slices in registers, DPP reduction as in the deviation kernel), writes
+//                 scale*q.K for every query head to the workspace as fp32 [n_q_heads][n_rows] and
+//                 the (max, sum exp) of each 64-token tile;
+//   2. stats      per (request, head): merges the tile partials into the softmax max / normaliser;
 //   3. score      per token: normalised weights summed per group, times the stored deviation,
 //                 masked to the candidates;
 //   4. select     the same exact top-k kernel as kvs_select_topk, one row per request;
@@ -20,7 +21,7 @@ namespace kvs {
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kTok = 32;          // tokens per workgroup in the logits kernel
+constexpr int kTok = 64;          // tokens per workgroup in the logits kernel (= one wavefront in the partials step)
 constexpr int kMaxReq = kAttnMaxReq;
 
 struct DecodeBatch {
@@ -31,19 +32,45 @@ struct DecodeBatch {
     int32_t n_req;
 };
 
-// ---- 1. logits --------------------------------------------------------------------------------
-// LPH lanes per cell (head_dim * elem / 16 bytes); EPL = elements per 16-byte piece.
-template <int DTYPE, int LPH>
+// ---- 1. logits + per-tile softmax partials ---------------------------------------------------------
+// LPH lanes per (token, kv head) cell (head_dim * elem / 16 bytes); EPL = elements per 16-byte piece.
+// GRP > 0: the group size is a compile-time constant and every lane group always meets the same KV
+// head (cells per step is a multiple of n_kv_heads), so its slice of the group's queries lives in
+// registers.  GRP == 0: generic shapes, queries are read from LDS.
+template <int DTYPE, int EPL>
+__device__ __forceinline__ void unpack_piece(const uint4 w, float (&kx)[EPL])
+{
+    if constexpr (DTYPE == KVS_BF16) {
+        kx[0] = bf16_lo(w.x); kx[1] = bf16_hi(w.x); kx[2] = bf16_lo(w.y); kx[3] = bf16_hi(w.y);
+        kx[4] = bf16_lo(w.z); kx[5] = bf16_hi(w.z); kx[6] = bf16_lo(w.w); kx[7] = bf16_hi(w.w);
+    } else {
+        kx[0] = __uint_as_float(w.x); kx[1] = __uint_as_float(w.y);
+        kx[2] = __uint_as_float(w.z); kx[3] = __uint_as_float(w.w);
+    }
+}
+
+template <int LPH>
+__device__ __forceinline__ float cell_sum(float acc)
+{
+    if (LPH == 16) return row16_sum(acc);
+    if (LPH == 32) { acc = row16_sum(acc); return acc + __shfl_xor(acc, 16); }
+    acc += __shfl_xor(acc, 4);
+    acc += __shfl_xor(acc, 2);
+    return acc + __shfl_xor(acc, 1);
+}
+
+template <int DTYPE, int LPH, int GRP>
 __global__ __launch_bounds__(kThreads) void decode_logits_kernel(
     const DecodeBatch bd, int n_q_heads, int n_kv_heads, int64_t n_rows,
     const void *__restrict__ q_new, const uint4 *__restrict__ k_cache, float scale,
-    float *__restrict__ logits)
+    float *__restrict__ logits, float2 *__restrict__ partial /* [tile][n_q_heads] (max, sum exp) */)
 {
     constexpr int EPL = DTYPE == KVS_BF16 ? 8 : 4;
     constexpr int D = LPH * EPL;
+    constexpr int UNROLL = 4;
     extern __shared__ float lds[];
-    float *q_s = lds;                              // [n_q_heads][D], pre-multiplied by scale
-    float *lg_s = lds + n_q_heads * D;             // [n_q_heads][kTok]
+    float *lg_s = lds;                             // [n_q_heads][kTok]
+    float *q_s = lds + n_q_heads * kTok;           // [n_q_heads][D], pre-multiplied by scale (GRP == 0 only)
 
     int b = 0;
     while (b + 1 < bd.n_req && (int)blockIdx.x >= bd.tile_begin[b + 1]) ++b;
@@ -52,50 +79,70 @@ __global__ __launch_bounds__(kThreads) void decode_logits_kernel(
     const int tok0 = tile * kTok;
     const int tile_tok = min(kTok, len - tok0);
     const int64_t row0 = bd.ctx_off[b] + tok0;
-    const int grp = n_q_heads / n_kv_heads;
+    const int grp = GRP > 0 ? GRP : n_q_heads / n_kv_heads;
     const int tid = threadIdx.x;
-
-    for (int e = tid; e < n_q_heads * D; e += kThreads) {
-        const int64_t gi = (int64_t)(bd.req0 + b) * n_q_heads * D + e;
-        float v;
-        if (DTYPE == KVS_F32) v = ((const float *)q_new)[gi];
-        else v = __uint_as_float((uint32_t)((const uint16_t *)q_new)[gi] << 16);
-        q_s[e] = v * scale;
-    }
-    __syncthreads();
-
     constexpr int CPB = kThreads / LPH;             // cells per step
     const int sub = tid % LPH, cell_in_step = tid / LPH;
     const int tile_cells = tile_tok * n_kv_heads;
-    for (int base = 0; base < tile_cells; base += CPB) {
-        const int c = base + cell_in_step;
-        const bool live = c < tile_cells;
-        const int t = live ? c / n_kv_heads : 0;
-        const int g = live ? c - t * n_kv_heads : 0;
-        float kx[EPL];
-        if (live) {
-            const uint4 w = stream_load16(k_cache + ((row0 + t) * n_kv_heads + g) * LPH + sub);
-            if constexpr (DTYPE == KVS_BF16) {
-                kx[0] = bf16_lo(w.x); kx[1] = bf16_hi(w.x); kx[2] = bf16_lo(w.y); kx[3] = bf16_hi(w.y);
-                kx[4] = bf16_lo(w.z); kx[5] = bf16_hi(w.z); kx[6] = bf16_lo(w.w); kx[7] = bf16_hi(w.w);
+    const int64_t q_base = (int64_t)(bd.req0 + b) * n_q_heads * D;
+
+    auto load_q = [&](int64_t gi) -> float {
+        if (DTYPE == KVS_F32) return ((const float *)q_new)[gi] * scale;
+        return __uint_as_float((uint32_t)((const uint16_t *)q_new)[gi] << 16) * scale;
+    };
+
+    constexpr int GR = GRP > 0 ? GRP : 1;
+    float qr[GR][EPL];
+    if constexpr (GRP > 0) {
+        const int g = cell_in_step % n_kv_heads;   // fixed: CPB is a multiple of n_kv_heads
+#pragma unroll
+        for (int hh = 0; hh < GRP; ++hh)
+#pragma unroll
+            for (int i = 0; i < EPL; ++i) qr[hh][i] = load_q(q_base + (int64_t)(g * GRP + hh) * D + sub * EPL + i);
+    } else {
+        for (int e = tid; e < n_q_heads * D; e += kThreads) q_s[e] = load_q(q_base + e);
+        __syncthreads();
+    }
+
+    for (int base = 0; base < tile_cells; base += CPB * UNROLL) {
+        uint4 w[UNROLL];
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            const int c = base + u * CPB + cell_in_step;
+            if (c < tile_cells) {
+                const int t = c / n_kv_heads, g = c - t * n_kv_heads;
+                w[u] = stream_load16(k_cache + ((row0 + t) * n_kv_heads + g) * LPH + sub);
             } else {
-                kx[0] = __uint_as_float(w.x); kx[1] = __uint_as_float(w.y);
-                kx[2] = __uint_as_float(w.z); kx[3] = __uint_as_float(w.w);
+                w[u] = make_uint4(0, 0, 0, 0);
             }
-        } else {
-#pragma unroll
-            for (int i = 0; i < EPL; ++i) kx[i] = 0.f;
         }
-        for (int hh = 0; hh < grp; ++hh) {
-            const float *qh = q_s + (g * grp + hh) * D + sub * EPL;
-            float acc = 0.f;
 #pragma unroll
-            for (int i = 0; i < EPL; ++i) acc += qh[i] * kx[i];
-            // reduce over the LPH lanes of the cell (every lane of the wave takes part)
-            if (LPH == 16) acc = row16_sum(acc);
-            else if (LPH == 32) { acc = row16_sum(acc); acc += __shfl_xor(acc, 16); }
-            else { acc += __shfl_xor(acc, 4); acc += __shfl_xor(acc, 2); acc += __shfl_xor(acc, 1); }
-            if (live && sub == 0) lg_s[(g * grp + hh) * kTok + t] = acc;
+        for (int u = 0; u < UNROLL; ++u) {
+            const int c = base + u * CPB + cell_in_step;
+            const bool live = c < tile_cells;
+            const int t = live ? c / n_kv_heads : 0;
+            const int g = live ? c - t * n_kv_heads : 0;
+            float kx[EPL];
+            unpack_piece<DTYPE, EPL>(w[u], kx);
+            if constexpr (GRP > 0) {
+#pragma unroll
+                for (int hh = 0; hh < GRP; ++hh) {
+                    float acc = 0.f;
+#pragma unroll
+                    for (int i = 0; i < EPL; ++i) acc = fmaf(qr[hh][i], kx[i], acc);
+                    acc = cell_sum<LPH>(acc);
+                    if (live && sub == 0) lg_s[(g * GRP + hh) * kTok + t] = acc;
+                }
+            } else {
+                for (int hh = 0; hh < grp; ++hh) {
+                    const float *qh = q_s + (g * grp + hh) * D + sub * EPL;
+                    float acc = 0.f;
+#pragma unroll
+                    for (int i = 0; i < EPL; ++i) acc = fmaf(qh[i], kx[i], acc);
+                    acc = cell_sum<LPH>(acc);
+                    if (live && sub == 0) lg_s[(g * grp + hh) * kTok + t] = acc;
+                }
+            }
         }
     }
     __syncthreads();
@@ -103,21 +150,28 @@ __global__ __launch_bounds__(kThreads) void decode_logits_kernel(
         const int h = e / kTok, t = e % kTok;
         if (t < tile_tok) logits[(int64_t)h * n_rows + row0 + t] = lg_s[e];
     }
+    // softmax partials of this tile: wave w takes heads w, w+4, ...; lane = token
+    const int lane = tid & 63, wave = tid >> 6;
+    for (int h = wave; h < n_q_heads; h += kThreads / 64) {
+        const float x = lane < tile_tok ? lg_s[h * kTok + lane] : -INFINITY;
+        const float m = wave_max(x);
+        const float z = wave_sum(lane < tile_tok ? expf(x - m) : 0.f);
+        if (lane == 0) partial[(int64_t)blockIdx.x * n_q_heads + h] = make_float2(m, z);
+    }
 }
 
-// ---- 2. softmax statistics per (request, head) ---------------------------------------------------
+// ---- 2. softmax statistics per (request, head): merge the tile partials ------------------------------
 __global__ __launch_bounds__(kThreads) void decode_stats_kernel(
-    const DecodeBatch bd, int n_q_heads, int64_t n_rows, const float *__restrict__ logits,
+    const DecodeBatch bd, int n_q_heads, const float2 *__restrict__ partial,
     float2 *__restrict__ stats /* [batch][n_q_heads] (max, sum) */)
 {
     __shared__ float red[kThreads / 64];
     __shared__ float bc;
     const int b = blockIdx.x / n_q_heads, h = blockIdx.x % n_q_heads;
-    const int len = bd.ctx_len[b];
-    const float *row = logits + (int64_t)h * n_rows + bd.ctx_off[b];
+    const int t0 = bd.tile_begin[b], t1 = bd.tile_begin[b + 1];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     float m = -INFINITY;
-    for (int i = tid; i < len; i += kThreads) m = fmaxf(m, row[i]);
+    for (int t = t0 + tid; t < t1; t += kThreads) m = fmaxf(m, partial[(int64_t)t * n_q_heads + h].x);
     m = wave_max(m);
     if (lane == 0) red[wave] = m;
     __syncthreads();
@@ -125,7 +179,10 @@ __global__ __launch_bounds__(kThreads) void decode_stats_kernel(
     __syncthreads();
     m = bc;
     float z = 0.f;
-    for (int i = tid; i < len; i += kThreads) z += expf(row[i] - m);
+    for (int t = t0 + tid; t < t1; t += kThreads) {
+        const float2 p = partial[(int64_t)t * n_q_heads + h];
+        z += p.y * expf(p.x - m);
+    }
     z = wave_sum(z);
     __syncthreads();
     if (lane == 0) red[wave] = z;
@@ -229,7 +286,8 @@ size_t decode_workspace_bytes(const kvs_shape *shape, int32_t batch, int64_t n_r
     size_t logits = align_up(sizeof(float) * (size_t)shape->n_q_heads * (size_t)n_rows, 256);
     size_t stats = align_up(sizeof(float2) * (size_t)batch * (size_t)shape->n_q_heads, 256);
     size_t score = align_up(sizeof(float) * (size_t)n_rows, 256);
-    return logits + stats + score;
+    size_t partial = align_up(sizeof(float2) * ((size_t)n_rows / kTok + (size_t)batch + 1) * (size_t)shape->n_q_heads, 256);
+    return logits + stats + score + partial;
 }
 
 } // namespace kvs
@@ -274,6 +332,8 @@ extern "C" kvs_status kvs_decode_check(const kvs_shape *shape, int32_t batch, in
     float2 *stats = (float2 *)ws;
     ws += align_up(sizeof(float2) * (size_t)batch * (size_t)hq, 256);
     float *score = score_out ? score_out : (float *)ws;
+    ws += align_up(sizeof(float) * (size_t)n_rows, 256);
+    float2 *partial = (float2 *)ws;
     const int lph = (int)(d * elem_bytes(shape->dtype) / 16);
 
     for (int32_t b0 = 0; b0 < batch; b0 += kMaxReq) {
@@ -296,17 +356,32 @@ extern "C" kvs_status kvs_decode_check(const kvs_shape *shape, int32_t batch, in
         bd_tok.req0 = bd_thr.req0 = b0;
         bd_tok.n_req = bd_thr.n_req = nr;
         if (tiles_tok == 0) continue;
-        const size_t lds = sizeof(float) * (size_t)hq * (d + kTok);
+        const int grp = hq / hk;
+        const bool regq = (kThreads / lph) % hk == 0;   // every lane group keeps one kv head
+        const size_t lds = sizeof(float) * (size_t)hq * (kTok + (regq ? 0 : d));
         dim3 block(kThreads);
-#define KVS_DEC_CASE(DT, L) hipLaunchKernelGGL((decode_logits_kernel<DT, L>), dim3((unsigned)tiles_tok), block, lds, hs, bd_tok, hq, hk, n_rows, q_new, (const uint4 *)k_cache, scale, logits)
+        // partials of this launch start at the launch's first tile: offset the pointer so that the
+        // kernel can index by blockIdx
+        float2 *part_l = partial;
+#define KVS_DEC_LAUNCH(DT, L, G) hipLaunchKernelGGL((decode_logits_kernel<DT, L, G>), dim3((unsigned)tiles_tok), block, lds, hs, bd_tok, hq, hk, n_rows, q_new, (const uint4 *)k_cache, scale, logits, part_l)
+#define KVS_DEC_CASE(DT, L)                                                    \
+    do {                                                                       \
+        if (regq && grp == 1) KVS_DEC_LAUNCH(DT, L, 1);                        \
+        else if (regq && grp == 2) KVS_DEC_LAUNCH(DT, L, 2);                   \
+        else if (regq && grp == 4) KVS_DEC_LAUNCH(DT, L, 4);                   \
+        else if (regq && grp == 7) KVS_DEC_LAUNCH(DT, L, 7);                   \
+        else if (regq && grp == 8) KVS_DEC_LAUNCH(DT, L, 8);                   \
+        else KVS_DEC_LAUNCH(DT, L, 0);                                         \
+    } while (0)
         if (shape->dtype == KVS_BF16 && lph == 16) KVS_DEC_CASE(KVS_BF16, 16);
         else if (shape->dtype == KVS_BF16 && lph == 8) KVS_DEC_CASE(KVS_BF16, 8);
         else if (shape->dtype == KVS_F32 && lph == 16) KVS_DEC_CASE(KVS_F32, 16);
         else if (shape->dtype == KVS_F32 && lph == 32) KVS_DEC_CASE(KVS_F32, 32);
         else return fail(KVS_EUNSUPPORTED, "kvs_decode_check: head_dim %d", d);
 #undef KVS_DEC_CASE
+#undef KVS_DEC_LAUNCH
         if ((st = check_launch("kvs_decode_check(logits)")) != KVS_OK) return st;
-        hipLaunchKernelGGL(decode_stats_kernel, dim3((unsigned)(nr * hq)), block, 0, hs, bd_tok, hq, n_rows, logits, stats);
+        hipLaunchKernelGGL(decode_stats_kernel, dim3((unsigned)(nr * hq)), block, 0, hs, bd_tok, hq, part_l, stats);
         if ((st = check_launch("kvs_decode_check(stats)")) != KVS_OK) return st;
         hipLaunchKernelGGL(decode_score_kernel, dim3((unsigned)tiles_thr), block, 0, hs, bd_thr, hq, hk, n_rows,
                            logits, stats, dev_v, reused, score);

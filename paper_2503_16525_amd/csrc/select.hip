@@ -1,14 +1,23 @@
 // kvs_select_topk: exact top-k of each row of a ragged fp32 score matrix (Alg. 1 step 4),
 // order (score descending, index ascending), indices emitted in ascending order.
 //
-// One workgroup of 1024 lanes owns a row.  Scores are mapped to order-preserving unsigned keys
-// and kept in registers (rows up to 32768 entries) or re-read from L2 (longer rows).  A 4-pass
-// MSB-first radix select over an LDS histogram finds the key T of the k-th entry; the answer is
-// then { key > T } plus the first (k - #{key > T}) entries with key == T in index order.  That
-// set is written by an order-preserving compaction: wave ballots give per-(tile, wave) counts,
-// one wave scans them, and every selected lane computes its output slot in closed form
-//     slot = #greater before it + min(#equal before it, quota of equals).
-// Integer counting only: the result is exact and identical from run to run.
+// One workgroup of 1024 lanes (16 waves) owns a row; wave w owns the w-th contiguous sixteenth of
+// it, so everything that depends on element order is wave-local except 16 totals.  Scores are
+// mapped to order-preserving unsigned keys held in registers (rows up to 49152 entries) or re-read
+// from L2 (longer rows).  The key T of the k-th entry is found by an MSB-first radix select with
+// digits of 10, 11 and 11 bits:
+//   pass 1  histogram of the leading digit over the whole row.  fp32 scores share most of their
+//           leading bits, so the histogram is kept in 4 interleaved copies (copy = lane & 3):
+//           lanes that meet in one bin land in different LDS banks instead of serialising;
+//   pass 2/3 only the keys that share T's leading digit (a few percent of the row) matter; they are
+//           copied to an LDS list and histogrammed from there (if they do not fit, the passes rerun
+//           over the row).
+// The answer is { key > T } plus the first (k - #{key > T}) entries with key == T in index order,
+// written by an order-preserving compaction: ballots are counted on the scalar unit, each wave
+// keeps a running offset, and a selected lane's slot is
+//     #greater before it + min(#equal before it, quota of equals).
+// When no tie is cut (the usual case) the predicate collapses to key >= T.  Integer counting only:
+// the result is exact and identical from run to run.
 #include "kvs_internal.h"
 
 #include <new>
@@ -18,8 +27,10 @@ namespace {
 
 constexpr int kSelThreads = 1024;
 constexpr int kSelWaves = kSelThreads / kWave;   // 16
-constexpr int kChunkTiles = 32;                  // tiles (of 1024 entries) per compaction round, streaming path
 constexpr int kMaxRowsPerLaunch = 64;
+constexpr int kSurvCap = 6144;                   // LDS list of keys sharing the threshold's leading digit
+constexpr int kCopies = 4;                        // interleaved copies of the leading-digit histogram
+constexpr int kHist1Ints = 1024 * kCopies;
 
 struct SelectRows {
     int64_t begin[kMaxRowsPerLaunch];    // first score of the row
@@ -35,166 +46,206 @@ __device__ __forceinline__ uint32_t score_key(float s)
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
-__device__ __forceinline__ int wave_excl_scan(int v, int lane, int &total)
+// inclusive prefix sum over the 64 lanes with DPP row shifts and row broadcasts (no LDS round trips)
+__device__ __forceinline__ int wave_incl_scan(int v)
 {
-    int incl = v;
-#pragma unroll
-    for (int d = 1; d < kWave; d <<= 1) {
-        const int t = __shfl_up(incl, d);
-        if (lane >= d) incl += t;
-    }
-    total = __shfl(incl, kWave - 1);
-    return incl - v;
+    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, true);   // row_shr:1
+    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, true);   // row_shr:2
+    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, true);   // row_shr:4
+    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, true);   // row_shr:8
+    v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false);  // row_bcast:15 into rows 1 and 3
+    v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false);  // row_bcast:31 into rows 2 and 3
+    return v;
+}
+
+__device__ __forceinline__ int lanes_below(uint64_t m)
+{
+    return __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0));
 }
 
 // KPT > 0: row length <= KPT * 1024 and keys live in registers; KPT == 0: keys are re-read.
+//
+// Slots that hold no element (past the end of the row or of the wave's chunk) carry key 0.  Real
+// scores never map to a key below 2^22 (-inf maps to 0x007fffff; only NaN patterns go lower), so
+// key 0 sits alone in leading-digit bin 0, never reaches the threshold, and no validity mask has to
+// be carried through the passes.
 template <int KPT>
 __global__ __launch_bounds__(kSelThreads) void select_kernel(const float *__restrict__ scores,
                                                              int32_t *__restrict__ idx_out,
                                                              const SelectRows rows)
 {
-    __shared__ int hist[256];
-    __shared__ int bcast[2];                       // chosen digit, remaining k
-    __shared__ int cnt_gt[kChunkTiles * kSelWaves];
-    __shared__ int cnt_eq[kChunkTiles * kSelWaves];
-    __shared__ int chunk_tot[2];
+    __shared__ int hist1[kHist1Ints];               // 1024 leading-digit bins x kCopies interleaved copies
+    __shared__ int hist2[2048], hist3[2048];        // second / third digit (candidates only)
+    __shared__ uint32_t surv[kSurvCap];
+    __shared__ int wave_tot[kSelWaves], wave_tot2[kSelWaves];
+    __shared__ int bcast[3];                        // chosen digit, rank inside it, entries in it
 
     const int r = blockIdx.x;
     const int len = rows.len[r];
     const int k = rows.k[r];
-    if (k <= 0 || len <= 0) return;                // uniform over the workgroup
+    if (k <= 0 || len <= 0) return;                 // uniform over the workgroup
     const float *__restrict__ row = scores + rows.begin[r];
     int32_t *__restrict__ out = idx_out + rows.out_off[r];
-    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
-    const int n_tiles = (len + kSelThreads - 1) / kSelThreads;
+    const uint32_t tid = threadIdx.x, lane = tid & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
+    const int nj = (len + kSelThreads - 1) / kSelThreads;    // keys per lane
+    const uint32_t e0 = (uint32_t)(wave * nj) * kWave + lane; // this lane's first element; slot j holds e0 + 64 j
 
     constexpr int NREG = KPT > 0 ? KPT : 1;
     uint32_t keys[NREG];
-    if (KPT > 0) {
+    if constexpr (KPT > 0) {
+        // unconditional, clamped loads so that all of them are in flight together
 #pragma unroll
         for (int j = 0; j < NREG; ++j) {
-            const int e = j * kSelThreads + tid;
-            keys[j] = e < len ? score_key(row[e]) : 0u;
+            const uint32_t e = e0 + j * kWave;
+            const uint32_t key = score_key(row[min(e, (uint32_t)len - 1)]);
+            keys[j] = (j < nj && e < (uint32_t)len) ? key : 0u;
         }
     }
-    // ---- radix select: T = key of the k-th entry in descending order --------------------
-    uint32_t prefix = 0, mask = 0;
-    int remaining = k;
-    for (int pass = 0; pass < 4; ++pass) {
-        const int shift = 24 - 8 * pass;
-        if (tid < 256) hist[tid] = 0;
-        __syncthreads();
-        if (KPT > 0) {
+    // f(e, key) for every slot of this lane, in element order, without branches
+    auto for_keys = [&](auto f) {
+        if constexpr (KPT > 0) {
 #pragma unroll
-            for (int j = 0; j < NREG; ++j) {
-                const int e = j * kSelThreads + tid;
-                if (e < len && (keys[j] & mask) == prefix) atomicAdd(&hist[(keys[j] >> shift) & 255u], 1);
-            }
+            for (int j = 0; j < NREG; ++j) f(e0 + j * kWave, keys[j]);
         } else {
-            for (int j = 0; j < n_tiles; ++j) {
-                const int e = j * kSelThreads + tid;
-                if (e < len) {
-                    const uint32_t key = score_key(row[e]);
-                    if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1);
-                }
+            for (int j = 0; j < nj; ++j) {
+                const uint32_t e = e0 + j * kWave;
+                const uint32_t key = score_key(row[min(e, (uint32_t)len - 1)]);
+                f(e, e < (uint32_t)len ? key : 0u);
             }
         }
+    };
+    // Each thread holds the count `mine` of the bins it owns (bins ascending with tid).  Finds the
+    // thread whose bins hold the remaining-th entry counted from the top; that thread calls
+    // resolve(rank_from_top_inside_its_bins).  Every thread must call this.
+    auto find_owner = [&](int mine, int remaining, auto resolve) {
+        const int incl = wave_incl_scan(mine);
+        const int wtot = __builtin_amdgcn_readlane(incl, kWave - 1);
+        if (lane == 0) wave_tot[wave] = wtot;
         __syncthreads();
-        if (wave == 0) {
-            // lane l owns bins 4l..4l+3; suffix sums locate the bin that holds the remaining-th entry
-            const int b0 = hist[4 * lane], b1 = hist[4 * lane + 1], b2 = hist[4 * lane + 2], b3 = hist[4 * lane + 3];
-            const int mine = b0 + b1 + b2 + b3;
-            int total;
-            const int below = wave_excl_scan(mine, lane, total);   // entries in lower lanes' bins
-            const int above = total - below - mine;                 // entries in higher lanes' bins
-            if (above < remaining && remaining <= above + mine) {   // exactly one lane
-                int acc = above, digit = 4 * lane + 3;
-                if (acc + b3 >= remaining) { digit = 4 * lane + 3; }
-                else if ((acc += b3) + b2 >= remaining) { digit = 4 * lane + 2; }
-                else if ((acc += b2) + b1 >= remaining) { digit = 4 * lane + 1; }
-                else { acc += b1; digit = 4 * lane; }
-                bcast[0] = digit;
-                bcast[1] = remaining - acc;
-            }
-        }
+        int above = wtot - incl;                                 // higher lanes of this wave
+        for (int w = wave + 1; w < kSelWaves; ++w) above += wave_tot[w];
+        if (above < remaining && remaining <= above + mine) resolve(remaining - above);
         __syncthreads();
-        prefix |= (uint32_t)bcast[0] << shift;
-        mask |= 255u << shift;
-        remaining = bcast[1];
-        // the next pass's zeroing of hist is separated from these reads by its own barrier
-    }
-    const uint32_t T = prefix;
-    const int quota_eq = remaining;                // entries equal to T that are taken
+    };
+    // thread t owns bins 2t and 2t+1 of a 2048-bin histogram
+    auto find_bin2 = [&](const int *h, int rem) {
+        const int b_lo = h[2 * tid], b_hi = h[2 * tid + 1];
+        find_owner(b_lo + b_hi, rem, [&](int rank) {
+            if (rank <= b_hi) { bcast[0] = 2 * tid + 1; bcast[1] = rank; bcast[2] = b_hi; }
+            else { bcast[0] = 2 * tid; bcast[1] = rank - b_hi; bcast[2] = b_lo; }
+        });
+    };
 
-    // ---- ordered compaction ----------------------------------------------------------------
-    const uint64_t lt_mask = (lane == 0) ? 0ull : (~0ull >> (kWave - lane));
-    int base_gt = 0, base_eq = 0;
-    constexpr int TPC = KPT > 0 ? KPT : kChunkTiles;   // tiles per compaction round (unrolled)
-    for (int tile0 = 0; tile0 < n_tiles; tile0 += TPC) {
-        const int tiles = min(TPC, n_tiles - tile0);
 #pragma unroll
-        for (int j = 0; j < TPC; ++j) {
-            if (j < tiles) {
-                const int e = (tile0 + j) * kSelThreads + tid;
-                const bool valid = e < len;
-                const uint32_t key = KPT > 0 ? keys[KPT > 0 ? j : 0] : (valid ? score_key(row[e]) : 0u);
-                const uint64_t m_gt = __ballot(valid && key > T);
-                const uint64_t m_eq = __ballot(valid && key == T);
-                if (lane == 0) {
-                    cnt_gt[j * kSelWaves + wave] = __popcll(m_gt);
-                    cnt_eq[j * kSelWaves + wave] = __popcll(m_eq);
-                }
-            }
+    for (int i = 0; i < kHist1Ints / kSelThreads; ++i) hist1[i * kSelThreads + tid] = 0;
+    hist2[tid] = 0; hist2[tid + kSelThreads] = 0;
+    hist3[tid] = 0; hist3[tid + kSelThreads] = 0;
+    __syncthreads();
+
+    // ---- pass 1: leading 10 bits over the whole row ---------------------------------------------
+    const uint32_t copy = lane & (kCopies - 1);
+    for_keys([&](uint32_t, uint32_t key) { atomicAdd(&hist1[(key >> 22) * kCopies + copy], 1); });
+    __syncthreads();
+    {
+        int c = 0;
+#pragma unroll
+        for (int i = 0; i < kCopies; ++i) c += hist1[tid * kCopies + i];
+        find_owner(c, k, [&](int rank) { bcast[0] = tid; bcast[1] = rank; bcast[2] = c; });
+    }
+    const uint32_t d1 = (uint32_t)bcast[0];
+    int remaining = bcast[1];
+    const int n_cand = bcast[2];
+    uint32_t T;
+    int eq_total;
+    if (n_cand <= kSurvCap) {
+        // ---- copy the candidates to LDS (wave-local offsets, 16 totals exchanged) ---------------
+        int mine = 0;
+        for_keys([&](uint32_t, uint32_t key) { mine += __popcll(__ballot((key >> 22) == d1)); });
+        if (lane == 0) wave_tot2[wave] = mine;
+        __syncthreads();
+        uint32_t base = 0;
+        for (int w = 0; w < wave; ++w) base += wave_tot2[w];
+        for_keys([&](uint32_t, uint32_t key) {
+            const bool hit = (key >> 22) == d1;
+            const uint64_t m = __ballot(hit);
+            if (hit) surv[base + lanes_below(m)] = key;
+            base += __popcll(m);
+        });
+        __syncthreads();
+        // ---- passes 2 and 3 on the list ------------------------------------------------------------
+        for (uint32_t i = tid; i < (uint32_t)n_cand; i += kSelThreads) atomicAdd(&hist2[(surv[i] >> 11) & 2047u], 1);
+        __syncthreads();
+        find_bin2(hist2, remaining);
+        const uint32_t d2 = (uint32_t)bcast[0];
+        remaining = bcast[1];
+        for (uint32_t i = tid; i < (uint32_t)n_cand; i += kSelThreads) {
+            const uint32_t key = surv[i];
+            if (((key >> 11) & 2047u) == d2) atomicAdd(&hist3[key & 2047u], 1);
         }
         __syncthreads();
-        if (wave == 0) {
-            // exclusive scan of the (tile, wave) counts in index order; 8 entries per lane
-            const int n_ent = tiles * kSelWaves;
-            int g[8], q[8], sg = 0, sq = 0;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const int x = lane * 8 + i;
-                g[i] = x < n_ent ? cnt_gt[x] : 0;
-                q[i] = x < n_ent ? cnt_eq[x] : 0;
-                sg += g[i];
-                sq += q[i];
-            }
-            int tg, tq;
-            int pg = wave_excl_scan(sg, lane, tg);
-            int pq = wave_excl_scan(sq, lane, tq);
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const int x = lane * 8 + i;
-                if (x < n_ent) { cnt_gt[x] = pg; cnt_eq[x] = pq; }
-                pg += g[i];
-                pq += q[i];
-            }
-            if (lane == 0) { chunk_tot[0] = tg; chunk_tot[1] = tq; }
-        }
+        find_bin2(hist3, remaining);
+        T = (d1 << 22) | (d2 << 11) | (uint32_t)bcast[0];
+        remaining = bcast[1];
+        eq_total = bcast[2];
+    } else {
+        // ---- too many candidates for the list: passes 2 and 3 rerun over the row ------------------
+        for_keys([&](uint32_t, uint32_t key) {
+            if ((key >> 22) == d1) atomicAdd(&hist2[(key >> 11) & 2047u], 1);
+        });
         __syncthreads();
-#pragma unroll
-        for (int j = 0; j < TPC; ++j) {
-            if (j < tiles) {
-                const int e = (tile0 + j) * kSelThreads + tid;
-                const bool valid = e < len;
-                const uint32_t key = KPT > 0 ? keys[KPT > 0 ? j : 0] : (valid ? score_key(row[e]) : 0u);
-                const bool is_gt = valid && key > T, is_eq = valid && key == T;
-                const uint64_t m_gt = __ballot(is_gt);
-                const uint64_t m_eq = __ballot(is_eq);
-                const int gt_before = base_gt + cnt_gt[j * kSelWaves + wave] + __popcll(m_gt & lt_mask);
-                const int eq_before = base_eq + cnt_eq[j * kSelWaves + wave] + __popcll(m_eq & lt_mask);
-                if (is_gt) out[gt_before + min(eq_before, quota_eq)] = e;
-                else if (is_eq && eq_before < quota_eq) out[gt_before + eq_before] = e;
-            }
-        }
-        base_gt += chunk_tot[0];
-        base_eq += chunk_tot[1];
-        __syncthreads();                           // cnt_* and chunk_tot are rewritten next round
+        find_bin2(hist2, remaining);
+        const uint32_t p2 = (d1 << 11) | (uint32_t)bcast[0];
+        remaining = bcast[1];
+        for_keys([&](uint32_t, uint32_t key) {
+            if ((key >> 11) == p2) atomicAdd(&hist3[key & 2047u], 1);
+        });
+        __syncthreads();
+        find_bin2(hist3, remaining);
+        T = (p2 << 11) | (uint32_t)bcast[0];
+        remaining = bcast[1];
+        eq_total = bcast[2];
+    }
+    if (T == 0u) T = 1u;                             // only reachable with NaN scores: never select padding
+    const int quota_eq = remaining;                  // entries equal to T that are taken
+    const bool all_eq_taken = quota_eq == eq_total;  // no tie is cut: the answer is { key >= T }
+
+    // ---- ordered compaction ---------------------------------------------------------------------
+    int n_sel = 0, n_eq = 0;                         // this wave's totals (scalar)
+    if (all_eq_taken) {
+        for_keys([&](uint32_t, uint32_t key) { n_sel += __popcll(__ballot(key >= T)); });
+    } else {
+        for_keys([&](uint32_t, uint32_t key) {
+            n_sel += __popcll(__ballot(key > T));
+            n_eq += __popcll(__ballot(key == T));
+        });
+    }
+    if (lane == 0) { wave_tot[wave] = n_sel; wave_tot2[wave] = n_eq; }
+    __syncthreads();
+    uint32_t base_sel = 0, base_eq = 0;
+    for (int w = 0; w < wave; ++w) { base_sel += wave_tot[w]; base_eq += wave_tot2[w]; }
+    if (all_eq_taken) {
+        for_keys([&](uint32_t e, uint32_t key) {
+            const bool sel = key >= T;
+            const uint64_t m = __ballot(sel);
+            if (sel) out[base_sel + lanes_below(m)] = (int32_t)e;
+            base_sel += __popcll(m);
+        });
+    } else {
+        for_keys([&](uint32_t e, uint32_t key) {
+            const bool is_gt = key > T, is_eq = key == T;
+            const uint64_t m_gt = __ballot(is_gt), m_eq = __ballot(is_eq);
+            const uint32_t gt_before = base_sel + lanes_below(m_gt);
+            const uint32_t eq_before = base_eq + lanes_below(m_eq);
+            if (is_gt) out[gt_before + min(eq_before, (uint32_t)quota_eq)] = (int32_t)e;
+            else if (is_eq && eq_before < (uint32_t)quota_eq) out[gt_before + eq_before] = (int32_t)e;
+            base_sel += __popcll(m_gt);
+            base_eq += __popcll(m_eq);
+        });
     }
 }
 
 } // namespace
-
 
 // rows given as (begin, len) pairs so that callers with gaps between rows (decode contexts with
 // slack) can use the same kernel; arguments are already validated
@@ -220,8 +271,10 @@ kvs_status launch_select(const float *scores, int32_t n_rows, const int64_t *beg
         if (max_len == 0) continue;
         dim3 grid(nr), block(kSelThreads);
         if (max_len <= 4 * kSelThreads) hipLaunchKernelGGL(select_kernel<4>, grid, block, 0, hs, scores, idx_out, rows);
+        else if (max_len <= 8 * kSelThreads) hipLaunchKernelGGL(select_kernel<8>, grid, block, 0, hs, scores, idx_out, rows);
         else if (max_len <= 16 * kSelThreads) hipLaunchKernelGGL(select_kernel<16>, grid, block, 0, hs, scores, idx_out, rows);
         else if (max_len <= 32 * kSelThreads) hipLaunchKernelGGL(select_kernel<32>, grid, block, 0, hs, scores, idx_out, rows);
+        else if (max_len <= 48 * kSelThreads) hipLaunchKernelGGL(select_kernel<48>, grid, block, 0, hs, scores, idx_out, rows);
         else hipLaunchKernelGGL(select_kernel<0>, grid, block, 0, hs, scores, idx_out, rows);
         kvs_status st = check_launch("kvs_select_topk");
         if (st != KVS_OK) return st;
