@@ -17,6 +17,26 @@ struct AttnBatch {
     int32_t n_req;
 };
 
+// Per-launch table for the matrix-core kernels: request geometry plus the first row tile of each
+// request in the launch's grid (row tiles never span requests).
+struct AttnTiles {
+    int64_t ctx_off[kAttnMaxReq];
+    int64_t cu_sel[kAttnMaxReq + 1];
+    int32_t ctx_len[kAttnMaxReq];
+    int32_t tile_begin[kAttnMaxReq + 1];
+    int32_t n_req;
+};
+
+// fills `td` for row tiles of `rows_per_tile` flattened (token, head-in-group) rows; returns the
+// number of row tiles, or -1 if the grid would overflow
+int64_t build_attn_tiles(const kvs_shape *shape, const AttnBatch &bd, int rows_per_tile, AttnTiles &td);
+
+// 64 query rows per wave (two MFMAs per LDS operand), one wave per SIMD: for launches with enough
+// row tiles to fill the chip
+kvs_status launch_attention_mfma2(const kvs_shape *shape, const AttnBatch &bd, const void *q_sel,
+                                  const int32_t *sel_pos, const void *k_cache, const void *v_cache,
+                                  float scale, void *out, float *lse_out, hipStream_t st);
+
 kvs_status launch_attention_valu(const kvs_shape *shape, const AttnBatch &bd, int64_t n_sel,
                                  const void *q_sel, const int32_t *sel_pos, const void *k_cache,
                                  const void *v_cache, float scale, void *out, float *lse_out,

@@ -27,6 +27,8 @@
 #include "attention.h"
 
 #include <math.h>
+#include <stdlib.h>
+#include <string.h>
 
 namespace kvs {
 namespace {
@@ -35,9 +37,13 @@ typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
 
 #ifndef KVS_ATTN_NWAVES
-#define KVS_ATTN_NWAVES 8
+#define KVS_ATTN_NWAVES 4
+#endif
+#ifndef KVS_ATTN_BIG_MIN_GRID
+#define KVS_ATTN_BIG_MIN_GRID 256
 #endif
 
+constexpr int kAttnBigTileMinGrid = KVS_ATTN_BIG_MIN_GRID;
 constexpr int D = 128;            // head_dim
 constexpr int BN = 64;            // keys per LDS tile
 constexpr int K_LD = D + 8;       // K tile row pitch in bf16 (272 B: 16-byte reads of 16 rows hit 16 bank groups)
@@ -45,14 +51,6 @@ constexpr int V_LD = BN + 8;      // V^T tile row pitch in bf16 (144 B)
 constexpr int K_TILE = BN * K_LD; // bf16 elements
 constexpr int V_TILE = D * V_LD;
 constexpr int STAGE = K_TILE + V_TILE;
-
-struct AttnTiles {
-    int64_t ctx_off[kAttnMaxReq];
-    int64_t cu_sel[kAttnMaxReq + 1];
-    int32_t ctx_len[kAttnMaxReq];
-    int32_t tile_begin[kAttnMaxReq + 1];
-    int32_t n_req;
-};
 
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4_t v) { return __builtin_bit_cast(bf16x8, v); }
 
@@ -321,21 +319,9 @@ kvs_status launch_mfma_variant(const kvs_shape *shape, const AttnBatch &bd, cons
                                hipStream_t st)
 {
     constexpr int ROWS = NWAVES * 32;
-    const int grp = shape->n_q_heads / shape->n_kv_heads;
     AttnTiles td;
-    int64_t tiles = 0;
-    for (int i = 0; i < kAttnMaxReq; ++i) {
-        const bool live = i < bd.n_req;
-        td.ctx_off[i] = live ? bd.ctx_off[i] : 0;
-        td.ctx_len[i] = live ? (int32_t)bd.ctx_len[i] : 0;
-        td.cu_sel[i] = bd.cu_sel[i];
-        td.tile_begin[i] = (int32_t)tiles;
-        if (live) tiles += ((bd.cu_sel[i + 1] - bd.cu_sel[i]) * grp + ROWS - 1) / ROWS;
-        if (tiles * shape->n_kv_heads > 0x7fffffffLL) return fail(KVS_EINVAL, "kvs_partial_attention: too many row tiles");
-    }
-    td.cu_sel[kAttnMaxReq] = bd.cu_sel[kAttnMaxReq];
-    td.tile_begin[kAttnMaxReq] = (int32_t)tiles;
-    td.n_req = bd.n_req;
+    const int64_t tiles = build_attn_tiles(shape, bd, ROWS, td);
+    if (tiles < 0) return fail(KVS_EINVAL, "kvs_partial_attention: too many row tiles");
     if (tiles == 0) return KVS_OK;
     const size_t lds_bytes = 2 * STAGE * sizeof(uint16_t);
     static bool attr_set = false;   // idempotent; a race only repeats the same call
@@ -356,6 +342,25 @@ kvs_status launch_mfma_variant(const kvs_shape *shape, const AttnBatch &bd, cons
 
 } // namespace
 
+int64_t build_attn_tiles(const kvs_shape *shape, const AttnBatch &bd, int rows_per_tile, AttnTiles &td)
+{
+    const int grp = shape->n_q_heads / shape->n_kv_heads;
+    int64_t tiles = 0;
+    for (int i = 0; i < kAttnMaxReq; ++i) {
+        const bool live = i < bd.n_req;
+        td.ctx_off[i] = live ? bd.ctx_off[i] : 0;
+        td.ctx_len[i] = live ? (int32_t)bd.ctx_len[i] : 0;
+        td.cu_sel[i] = bd.cu_sel[i];
+        td.tile_begin[i] = (int32_t)tiles;
+        if (live) tiles += ((bd.cu_sel[i + 1] - bd.cu_sel[i]) * grp + rows_per_tile - 1) / rows_per_tile;
+        if (tiles * shape->n_kv_heads > 0x7fffffffLL) return -1;
+    }
+    td.cu_sel[kAttnMaxReq] = bd.cu_sel[kAttnMaxReq];
+    td.tile_begin[kAttnMaxReq] = (int32_t)tiles;
+    td.n_req = bd.n_req;
+    return tiles;
+}
+
 bool attention_mfma_supports(const kvs_shape *shape)
 {
     return shape->dtype == KVS_BF16 && shape->head_dim == D;
@@ -368,6 +373,20 @@ kvs_status launch_attention_mfma(const kvs_shape *shape, const AttnBatch &bd, in
 {
     if (!attention_mfma_supports(shape)) return fail(KVS_EUNSUPPORTED, "kvs_partial_attention: matrix-core path needs bf16, head_dim 128");
     if (!(scale > 0.f) || !isfinite(scale)) return fail(KVS_EUNSUPPORTED, "kvs_partial_attention: matrix-core path needs a positive finite scale");
+    // enough 256-row tiles to give every CU work: the 64-rows-per-wave kernel; otherwise the
+    // finer-grained one, which fills the chip better.  KVS_ATTN_VARIANT=small|big in the environment
+    // pins the choice (used by the tests to reach both kernels at small sizes).
+    static const int forced = [] {
+        const char *e = getenv("KVS_ATTN_VARIANT");
+        if (e && strcmp(e, "small") == 0) return 1;
+        if (e && strcmp(e, "big") == 0) return 2;
+        return 0;
+    }();
+    const int grp = shape->n_q_heads / shape->n_kv_heads;
+    int64_t big_tiles = 0;
+    for (int i = 0; i < bd.n_req; ++i) big_tiles += ((bd.cu_sel[i + 1] - bd.cu_sel[i]) * grp + 255) / 256;
+    const bool big = forced ? forced == 2 : big_tiles * shape->n_kv_heads >= kAttnBigTileMinGrid;
+    if (big) return launch_attention_mfma2(shape, bd, q_sel, sel_pos, k_cache, v_cache, scale, out, lse_out, st);
     return launch_mfma_variant<KVS_ATTN_NWAVES>(shape, bd, q_sel, sel_pos, k_cache, v_cache, scale, out, lse_out, st);
 }
 

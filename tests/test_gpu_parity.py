@@ -212,13 +212,16 @@ def attn_tol(w):
 
 
 def assert_attn_close(got, ref, w):
-    """2e-2 absolute (bf16) / 1e-4 (fp32).  A bf16 output cannot be closer to the exact value than
-    its own rounding step, 2^-8 relative at worst, so for |ref| > 5.12 (heavy-tailed cache noise
-    reaches |V| ~ 10) the bound follows the representable precision instead."""
+    """fp32: 1e-4 absolute.  bf16: 2e-2 absolute plus 2^-8 relative.  The relative part is what bf16
+    itself costs on the matrix-core path: the output is stored in bf16 (rounding step up to 2^-9
+    of its magnitude) and the softmax weights enter the PV product as bf16 (each off by up to 2^-9,
+    so a row dominated by one key inherits that error at full size); with the heavy-tailed cache
+    noise outputs reach |o| ~ 10, where those two alone are ~0.04.  For |o| <= 1 the bound is
+    within 20 % of the plain 2e-2."""
     got, ref = np.asarray(got, np.float64), np.asarray(ref, np.float64)
     tol = np.full(ref.shape, attn_tol(w))
     if w.dtype == "bf16":
-        tol = np.maximum(tol, np.abs(ref) * 2.0 ** -8)
+        tol = tol + np.abs(ref) * 2.0 ** -8
     err = np.abs(got - ref)
     worst = np.unravel_index(np.argmax(err - tol), err.shape)
     assert np.all(err <= tol), f"max excess at {worst}: got {got[worst]} ref {ref[worst]} err {err[worst]}"
@@ -301,6 +304,27 @@ def test_partial_attention_ragged_batch():
     got, lse = run_gpu_attention(w, q, pos, k, v, 1.0, off, lens, cu)
     assert_attn_close(got, ref, w)
     np.testing.assert_allclose(lse, ref_lse, atol=2e-3)
+
+
+def test_partial_attention_first_tile_reference_fallback():
+    """Rows whose logits jump far above anything in their first 32 keys: the large-launch kernel
+    takes its softmax reference from the first tile and must notice the overflow and redo the
+    rows with exact maxima (other kernels just have to get the same answer)."""
+    w = synth.scaled(synth.LLAMA, 400)
+    say("attention with a 2^180 logit jump after the first tile")
+    n, hk, hq, d = w.n_ctx, w.n_kv_heads, w.n_q_heads, w.head_dim
+    g = torch.Generator().manual_seed(91)
+    k = torch.randn((n, hk, d), generator=g) * 0.05
+    k[40:] += 1.0                     # q.k jumps from ~0 to ~128 for q = ones
+    k[200:] += 0.5                    # and again
+    v = torch.randn((n, hk, d), generator=g)
+    pos = np.arange(0, n, 3, dtype=np.int32)
+    q = torch.ones((len(pos), hq, d)) + 0.01 * torch.randn((len(pos), hq, d), generator=g)
+    kb, vb, qb = k.to(torch.bfloat16), v.to(torch.bfloat16), q.to(torch.bfloat16)
+    ref, ref_lse = oracle.partial_attention(qb, pos, kb, vb, 1.0)
+    got, lse = run_gpu_attention(w, qb, pos, kb, vb, 1.0)
+    assert_attn_close(got, ref, w)
+    np.testing.assert_allclose(lse, ref_lse, rtol=2e-3, atol=2e-3)
 
 
 # --------------------------------------------------------------------------------- decode check
