@@ -1,0 +1,179 @@
+"""Parity at the benchmark's full sizes, in the launch configurations bench.py times: the
+Llama-3.1-8B-shaped 32k layer, the Yi-1.5-9B-shaped 131k layer and the 64-request decode batch.
+The oracle cannot recompute these outputs whole in reasonable time, so streaming steps (deviation,
+select, scatter) are compared in full and attention / decode scores on sampled rows that the oracle
+computes one by one, plus properties that hold at any size."""
+import math
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2503_16525_amd import binding as B
+from paper_2503_16525_amd import synth
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+
+def say(msg):
+    print(f"[case] {msg}", flush=True)
+    sys.stdout.flush()
+
+
+def attn_close(got, ref):
+    err = np.abs(np.asarray(got, np.float64) - ref)
+    tol = 2e-2 + np.abs(ref) * 2.0 ** -8
+    assert np.all(err <= tol), f"attention error {err.max()}"
+
+
+def prefill_layer(w, ratio, n_sample, projected):
+    """deviation -> select -> scatter -> attention at full size; returns nothing, asserts parity."""
+    sh = B.shape_of(w)
+    n, hk, hq, d = w.n_ctx, w.n_kv_heads, w.n_q_heads, w.head_dim
+    lay = synth.make_layer(w, device=DEV, projected=projected)
+    host = {k: v.cpu() for k, v in lay.items() if k != "q"}
+    # a1, full comparison
+    _, dev_ref, sc_ref = oracle.deviation(host["v_fresh"], host["v_cache"], reused=host["reused"])
+    dev_v = torch.empty((hk, n), device=DEV)
+    score = torch.empty((n,), device=DEV)
+    B.kvs_deviation(sh, n, None, lay["v_fresh"], None, lay["v_cache"], lay["reused"], None, B.SCORE_V, None, dev_v, score)
+    np.testing.assert_allclose(dev_v.cpu().numpy(), dev_ref, rtol=1e-5)
+    fin = np.isfinite(sc_ref)
+    sc = score.cpu().numpy()
+    assert np.array_equal(np.isfinite(sc), fin)
+    np.testing.assert_allclose(sc[fin], sc_ref[fin], rtol=1e-5)
+    # a2 on the oracle's scores, bit-exact
+    k = synth.recompute_budget(int(host["reused"].sum()), ratio)
+    idx_ref = oracle.select_topk(sc_ref, [0, n], [k])
+    idx = torch.empty((k,), dtype=torch.int32, device=DEV)
+    B.kvs_select_topk(torch.from_numpy(sc_ref).to(DEV), [0, n], [k], idx)
+    np.testing.assert_array_equal(idx.cpu().numpy(), idx_ref)
+    # a4, full comparison
+    li = torch.from_numpy(idx_ref.astype(np.int64))
+    kc, vc = oracle._as_np(host["k_cache"]).copy(), oracle._as_np(host["v_cache"]).copy()
+    reused = host["reused"].numpy().copy()
+    oracle.scatter_kv(host["k_fresh"][li], host["v_fresh"][li], idx_ref, kc, vc, reused, dev_ref)
+    gk, gv, gr = lay["k_cache"].clone(), lay["v_cache"].clone(), lay["reused"].clone()
+    B.kvs_scatter_kv(sh, n, lay["k_fresh"][li.to(DEV)].contiguous(), lay["v_fresh"][li.to(DEV)].contiguous(), idx, k,
+                     gk, gv, gr, dev_v)
+    np.testing.assert_array_equal(oracle._as_np(gk.cpu()), kc)
+    np.testing.assert_array_equal(oracle._as_np(gv.cpu()), vc)
+    np.testing.assert_array_equal(gr.cpu().numpy(), reused)
+    np.testing.assert_array_equal(dev_v.cpu().numpy() == 0, dev_ref == 0)
+    # a3 with ALL selected queries in one launch (the timed configuration); sampled rows vs oracle
+    q_sel = lay["q"][li.to(DEV)].contiguous()
+    out = torch.empty((k, hq, d), dtype=torch.bfloat16, device=DEV)
+    lse = torch.empty((k, hq), device=DEV)
+    B.kvs_partial_attention(sh, [0], [n], [0, k], q_sel, idx, gk, gv, 1.0, out, lse)
+    torch.cuda.synchronize()
+    pick = np.unique(np.concatenate([[0, 1, k - 2, k - 1], np.linspace(0, k - 1, n_sample).round().astype(np.int64)]))
+    ref, ref_lse = oracle.partial_attention(q_sel[pick].cpu(), idx_ref[pick], kc, vc, 1.0)
+    attn_close(out[pick].float().cpu().numpy(), ref)
+    np.testing.assert_allclose(lse[pick].cpu().numpy(), ref_lse, atol=2e-3)
+    # properties over every row: finite, and |o| bounded by the largest |V| a row can see
+    o = out.float()
+    assert bool(torch.isfinite(o).all()) and bool(torch.isfinite(lse).all())
+    assert float(o.abs().max()) <= float(gv.float().abs().max()) * (1 + 2.0 ** -7)
+    return lay, gk, gv, gr, dev_v, idx_ref
+
+
+@pytest.mark.parametrize("ratio", [0.05, 0.30])
+def test_llama_32k_layer_full_size(ratio):
+    say(f"llama 32k full size ratio {ratio}")
+    prefill_layer(synth.LLAMA, ratio, n_sample=24, projected=True)
+
+
+def test_yi_131k_layer_full_size():
+    say("yi 131k full size")
+    prefill_layer(synth.YI, 0.10, n_sample=6, projected=False)
+
+
+def test_yi_131k_select_per_head_rows():
+    """Top-k over 131k scores per KV head (four rows of one launch), bit-exact."""
+    w = synth.YI
+    say("yi 131k per-head top-k")
+    lay = synth.make_layer(w, with_q=False, device=DEV)
+    host_vf, host_vc = lay["v_fresh"].cpu(), lay["v_cache"].cpu()
+    _, dev_ref, _ = oracle.deviation(host_vf, host_vc)
+    n, hk = w.n_ctx, w.n_kv_heads
+    rows = np.where(lay["reused"].cpu().numpy()[None, :] != 0, dev_ref, -np.inf).astype(np.float32)
+    k = 12452
+    ref = oracle.select_topk(rows.reshape(-1), [i * n for i in range(hk + 1)], [k] * hk)
+    idx = torch.empty((hk * k,), dtype=torch.int32, device=DEV)
+    B.kvs_select_topk(torch.from_numpy(rows.reshape(-1)).to(DEV), [i * n for i in range(hk + 1)], [k] * hk, idx)
+    np.testing.assert_array_equal(idx.cpu().numpy(), ref)
+
+
+def test_decode_batch_full_size():
+    """64 requests with 4k-16k reused tokens each, one decode step: scores on sampled requests in
+    full, top-k validity on every request, then write-back and the recompute attention sampled."""
+    w = synth.DECODE
+    say("decode batch 64 x (4k..16k)")
+    sh = B.shape_of(w)
+    batch = 64
+    bt = synth.make_decode_batch(w, batch, 4096, 16384, 1, device=DEV)
+    rows = bt["k_cache"].shape[0]
+    off, lens = bt["ctx_off"], bt["ctx_len"].copy()
+    hk, hq, d = w.n_kv_heads, w.n_q_heads, w.head_dim
+    dev_v = torch.empty((hk, rows), device=DEV)
+    B.kvs_deviation(sh, rows, None, bt["v_fresh"], None, bt["v_cache"], bt["reused"], None, B.SCORE_V, None, dev_v, None)
+    gk, gv, gr = bt["k_cache"], bt["v_cache"], bt["reused"]
+    for b in range(batch):                       # append the new token of each request
+        r = int(off[b] + lens[b])
+        gk[r] = bt["k_new"][0, b]
+        gv[r] = bt["v_new"][0, b]
+    lens = lens + 1
+    kreq = [int(math.ceil(0.02 * l)) for l in lens]
+    ws = torch.empty(B.kvs_workspace_size("decode_check", sh, batch, rows), dtype=torch.uint8, device=DEV)
+    idx = torch.full((sum(kreq),), -1, dtype=torch.int32, device=DEV)
+    score = torch.full((rows,), float("nan"), device=DEV)
+    attn = torch.empty((batch, hq, d), dtype=torch.bfloat16, device=DEV)
+    q_new = bt["q_new"][0].contiguous()
+    B.kvs_decode_check(sh, rows, off, lens, q_new, gk, gv, dev_v, gr, 1.0, kreq, idx, score, attn, ws)
+    torch.cuda.synchronize()
+    sc, ix = score.cpu().numpy(), idx.cpu().numpy()
+    # every request: ascending unique in-range candidates, and none better left out (on the GPU's own scores)
+    cu = np.concatenate([[0], np.cumsum(kreq)])
+    reused_h = gr.cpu().numpy()
+    for b in range(batch):
+        sl = slice(int(off[b]), int(off[b] + lens[b]))
+        got = ix[cu[b]:cu[b + 1]]
+        assert np.all(np.diff(got) > 0) and got[0] >= 0 and got[-1] < lens[b]
+        assert np.all(reused_h[sl][got] == 1)
+        row = sc[sl]
+        chosen = np.zeros(lens[b], bool)
+        chosen[got] = True
+        assert row[chosen].min() >= row[~chosen].max()
+    # sampled requests against the oracle (host copies of just those contexts)
+    dev_h = dev_v.cpu().numpy()
+    for b in (0, 17, 63):
+        sl = slice(int(off[b]), int(off[b] + lens[b]))
+        kc, vc = oracle._as_np(gk[sl].cpu()), oracle._as_np(gv[sl].cpu())
+        ref_idx, ref_sc, ref_attn = oracle.decode_check(q_new[b:b + 1].cpu(), kc, dev_h[:, sl].copy(), reused_h[sl].copy(), 1.0,
+                                                        [0], [lens[b]], [kreq[b]], v_cache=vc, want_attn=True)
+        fin = np.isfinite(ref_sc)
+        assert np.array_equal(np.isfinite(sc[sl]), fin)
+        np.testing.assert_allclose(sc[sl][fin], ref_sc[fin], rtol=1e-5)
+        attn_close(attn[b:b + 1].float().cpu().numpy(), ref_attn)
+        thr = np.sort(ref_sc)[::-1][kreq[b] - 1]
+        got = set(ix[cu[b]:cu[b + 1]].tolist())
+        assert set(np.nonzero(ref_sc > thr * (1 + 2e-5))[0].tolist()) <= got
+        assert not (set(np.nonzero(ref_sc < thr * (1 - 2e-5))[0].tolist()) & got)
+    # write-back + ragged recompute attention (the decode-stage a4 + a3), sampled against the oracle
+    glob = torch.cat([idx[cu[b]:cu[b + 1]] + int(off[b]) for b in range(batch)]).contiguous()
+    gl = glob.long()
+    B.kvs_scatter_kv(sh, rows, bt["k_fresh"][gl].contiguous(), bt["v_fresh"][gl].contiguous(), glob, len(glob), gk, gv, gr, dev_v)
+    assert int(gr[gl].sum()) == 0 and float(dev_v[:, gl].abs().max()) == 0.0
+    g = torch.Generator(device=DEV).manual_seed(5)
+    q_sel = (torch.randn((len(glob), hq, d), generator=g, device=DEV) / math.sqrt(d)).to(torch.bfloat16)
+    out = torch.empty((len(glob), hq, d), dtype=torch.bfloat16, device=DEV)
+    B.kvs_partial_attention(sh, off, lens, cu, q_sel, idx, gk, gv, 1.0, out)
+    torch.cuda.synchronize()
+    for b in (0, 17, 63):
+        sl = slice(int(off[b]), int(off[b] + lens[b]))
+        rows_b = np.arange(cu[b], cu[b + 1])[:: max(1, kreq[b] // 6)]
+        ref, _ = oracle.partial_attention(q_sel[rows_b].cpu(), ix[rows_b], oracle._as_np(gk[sl].cpu()), oracle._as_np(gv[sl].cpu()), 1.0)
+        attn_close(out[rows_b].float().cpu().numpy(), ref)
