@@ -126,7 +126,7 @@ def run_step(s: Slot, sh, ev=None) -> None:
     B.kvs_scatter_kv(sh, rows, s.k_new, s.v_new, s.idx, s.k, s.k_cache, s.v_cache, s.reused, s.dev_v)
     if ev:
         ev[2].record()
-    B.kvs_partial_attention(sh, [0], [rows], [0, s.k], s.q_sel, s.idx, s.k_cache, s.v_cache, 1.0, s.out)
+    B.kvs_partial_attention(sh, [0], [rows], [0, s.k], s.q_sel, s.idx, s.k_cache, s.v_cache, 1.0, s.out, None, WS_ATT)
     if ev:
         ev[3].record()
     B.kvs_decode_check(sh, rows, [0], [rows], s.q_dec, s.k_cache, None, s.dev_v, s.reused, 1.0, [s.k_dec],
@@ -134,12 +134,13 @@ def run_step(s: Slot, sh, ev=None) -> None:
     if ev:
         ev[4].record()
     B.kvs_scatter_kv(sh, rows, s.k_new_dec, s.v_new_dec, s.idx_dec, s.k_dec, s.k_cache, s.v_cache, s.reused, s.dev_v)
-    B.kvs_partial_attention(sh, [0], [rows], [0, s.k_dec], s.q_sel_dec, s.idx_dec, s.k_cache, s.v_cache, 1.0, s.out_dec)
+    B.kvs_partial_attention(sh, [0], [rows], [0, s.k_dec], s.q_sel_dec, s.idx_dec, s.k_cache, s.v_cache, 1.0, s.out_dec, None, WS_ATT)
     if ev:
         ev[5].record()
 
 
-WS = None
+WS = None       # decode-check workspace
+WS_ATT = None   # partial-attention workspace (lets the small decode-recompute launch split its key range)
 
 
 def cpu_baseline_and_parity(w, ratio: float, sh, alpha, n_sample: int) -> dict:
@@ -171,6 +172,7 @@ def cpu_baseline_and_parity(w, ratio: float, sh, alpha, n_sample: int) -> dict:
     t0 = time.perf_counter()
     out_ref, _ = oracle.partial_attention(q_s, pos_s, kc, vc, 1.0)
     t_att = time.perf_counter() - t0
+    mag_ref, _ = oracle.partial_attention(q_s, pos_s, kc, (vc & np.uint16(0x7FFF)), 1.0)   # attention over |V|
     fl = 4.0 * d * hq * float((pos_s.astype(np.float64) + 1).sum())
     times["attention_sample_ms"] = t_att * 1e3
     # ---- parity of the GPU path on the same input ----
@@ -190,7 +192,7 @@ def cpu_baseline_and_parity(w, ratio: float, sh, alpha, n_sample: int) -> dict:
     out = torch.empty((len(pick), hq, d), dtype=torch.bfloat16, device="cuda")
     B.kvs_partial_attention(sh, [0], [n], [0, len(pick)], q_s.cuda(), torch.from_numpy(pos_s).cuda(), gk, gv, 1.0, out)
     err = np.abs(out.float().cpu().numpy() - out_ref)
-    tol = 2e-2 + np.abs(out_ref) * 2.0 ** -8
+    tol = 2e-2 + mag_ref * 2.0 ** -8     # bf16 weights and bf16 output, relative to sum_i a_i |v_i|
     assert np.all(err <= tol), f"attention differs from the oracle by {err.max()}"
     log(f"[bench] parity vs oracle on layer 0: scores rtol 1e-5 ok, top-{k} exact, scatter exact, "
         f"attention max err {err.max():.4f} on {len(pick)} sampled queries")
@@ -216,7 +218,7 @@ def read_traffic(kernel: str):
 
 
 def main() -> int:
-    global WS
+    global WS, WS_ATT
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
@@ -239,6 +241,7 @@ def main() -> int:
     sh = B.shape_of(w)
     n, hk, hq, d = w.n_ctx, w.n_kv_heads, w.n_q_heads, w.head_dim
     WS = torch.empty(B.kvs_workspace_size("decode_check", sh, 1, n + 1), dtype=torch.uint8, device="cuda")
+    WS_ATT = torch.empty(B.kvs_workspace_size("partial_attention", sh, 1, n + 1, 1024), dtype=torch.uint8, device="cuda")
     alpha_n = synth.synthetic_alpha(w, device="cuda") if args.alpha == "synthetic" else None
 
     n_slots = max(1, min(args.warmup + args.steps, MAX_SLOTS))

@@ -69,11 +69,11 @@ extern "C" const char *kvs_version(void) { return "kvshare-hip gfx950 1"; }
 extern "C" size_t kvs_workspace_size(const char *call, const kvs_shape *shape, int32_t batch,
                                      int64_t n_rows_total, int64_t n_sel_total)
 {
-    (void)n_sel_total;
     if (!call || !shape || batch < 0 || n_rows_total < 0) return 0;
     if (strcmp(call, "decode_check") == 0) return kvs::decode_workspace_bytes(shape, batch, n_rows_total);
     if (strcmp(call, "select_topk") == 0) return 256;
-    if (strcmp(call, "partial_attention") == 0) return 256;
+    if (strcmp(call, "partial_attention") == 0)
+        return kvs::attention_mfma_supports(shape) ? kvs::attention_workspace_bytes(shape, batch, n_sel_total) : 256;
     return 0;
 }
 
@@ -86,11 +86,10 @@ extern "C" kvs_status kvs_partial_attention(const kvs_shape *shape, int32_t batc
                                             void *workspace, size_t workspace_bytes, void *stream)
 {
     using namespace kvs;
-    (void)workspace;
-    (void)workspace_bytes;
     kvs_status st = check_shape(shape);
     if (st != KVS_OK) return st;
     if (batch < 0) return fail(KVS_EINVAL, "kvs_partial_attention: batch < 0");
+    if (workspace && (reinterpret_cast<uintptr_t>(workspace) & 255u)) return fail(KVS_EINVAL, "kvs_partial_attention: workspace must be 256-byte aligned");
     if (batch == 0) return KVS_OK;
     if (!ctx_off || !ctx_len || !cu_sel) return fail(KVS_EINVAL, "kvs_partial_attention: ctx_off/ctx_len/cu_sel is NULL");
     if (cu_sel[0] != 0) return fail(KVS_EINVAL, "kvs_partial_attention: cu_sel[0] must be 0");
@@ -123,7 +122,7 @@ extern "C" kvs_status kvs_partial_attention(const kvs_shape *shape, int32_t batc
         bd.n_req = nr;
         const int64_t ns = cu_sel[b0 + nr] - cu_sel[b0];
         if (ns == 0) continue;
-        st = mfma ? launch_attention_mfma(shape, bd, ns, q_sel, sel_pos, k_cache, v_cache, scale, out, lse_out, hs)
+        st = mfma ? launch_attention_mfma(shape, bd, ns, q_sel, sel_pos, k_cache, v_cache, scale, out, lse_out, workspace, workspace_bytes, hs)
                   : launch_attention_valu(shape, bd, ns, q_sel, sel_pos, k_cache, v_cache, scale, out, lse_out, hs);
         if (st != KVS_OK) return st;
     }

@@ -46,7 +46,9 @@ kvs_status launch_attention_valu(const kvs_shape *shape, const AttnBatch &bd, in
 kvs_status launch_attention_mfma(const kvs_shape *shape, const AttnBatch &bd, int64_t n_sel,
                                  const void *q_sel, const int32_t *sel_pos, const void *k_cache,
                                  const void *v_cache, float scale, void *out, float *lse_out,
-                                 hipStream_t st);
+                                 void *workspace, size_t workspace_bytes, hipStream_t st);
+// workspace that lets small launches split their key range (0 bytes still works, unsplit)
+size_t attention_workspace_bytes(const kvs_shape *shape, int32_t batch, int64_t n_sel_total);
 bool attention_mfma_supports(const kvs_shape *shape);
 
 } // namespace kvs

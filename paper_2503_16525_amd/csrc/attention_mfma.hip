@@ -62,12 +62,17 @@ __device__ __forceinline__ uint32_t pack2(float lo, float hi)
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));
 }
 
-template <int NWAVES>
+// SPLIT: the key range of a row tile is cut into n_splits contiguous pieces handled by different
+// workgroups (small launches would otherwise leave most of the chip idle while a few workgroups
+// walk 32k keys each); every piece writes its unnormalised accumulators and (max, sum) to the
+// workspace and attn_merge_kernel combines them.
+template <int NWAVES, bool SPLIT>
 __global__ __launch_bounds__(NWAVES * 64, 2) void attn_mfma_kernel(
     const AttnTiles td, int n_q_heads, int n_kv_heads, int total_tiles,
     const uint16_t *__restrict__ q_sel, const int32_t *__restrict__ sel_pos,
     const uint16_t *__restrict__ k_cache, const uint16_t *__restrict__ v_cache,
-    float scale_log2, uint16_t *__restrict__ out, float *__restrict__ lse_out)
+    float scale_log2, uint16_t *__restrict__ out, float *__restrict__ lse_out,
+    int n_splits, float *__restrict__ part_o, float2 *__restrict__ part_ml)
 {
     constexpr int NT = NWAVES * 64;
     constexpr int ROWS = NWAVES * 32;
@@ -81,7 +86,9 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_mfma_kernel(
 
     // ---- which (request, kv head, row tile) -----------------------------------------------------
     const int g = blockIdx.x % n_kv_heads;
-    const int tile_lin = total_tiles - 1 - (int)(blockIdx.x / n_kv_heads);
+    const int rest = (int)(blockIdx.x / n_kv_heads);
+    const int split = SPLIT ? rest % n_splits : 0;
+    const int tile_lin = total_tiles - 1 - (SPLIT ? rest / n_splits : rest);
     int b = 0;
     while (b + 1 < td.n_req && tile_lin >= td.tile_begin[b + 1]) ++b;
     const int tile = tile_lin - td.tile_begin[b];
@@ -121,6 +128,10 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_mfma_kernel(
 #pragma unroll
     for (int w = 1; w < NWAVES; ++w) wg_pmax = max(wg_pmax, wg_max_pos[w]);
     const int n_kv_tiles = wg_pmax / BN + 1;
+    // the KV tiles this workgroup walks: all of them, or its contiguous share
+    const int t_chunk = SPLIT ? (n_kv_tiles + n_splits - 1) / n_splits : n_kv_tiles;
+    const int t_lo = SPLIT ? min(n_kv_tiles, split * t_chunk) : 0;
+    const int t_hi = SPLIT ? min(n_kv_tiles, t_lo + t_chunk) : n_kv_tiles;
 
     // ---- global -> register staging of one K/V tile -------------------------------------------------
     // Addresses are a wave-uniform tile base (scalar registers) plus a per-lane 32-bit byte offset
@@ -197,20 +208,25 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_mfma_kernel(
     for (int db = 0; db < D / 32; ++db)
 #pragma unroll
         for (int r = 0; r < 16; ++r) o_acc[db][r] = 0.f;
-    float m_run = -INFINITY;   // running max of scale*log2(e)*logit, shared by the two half-waves
+    // running max of scale*log2(e)*logit, shared by the two half-waves.  It starts at a huge
+    // negative *finite* value so that a tile in which a row sees no key at all (possible when the
+    // key range is split) gives exp2(-inf - m) = 0 and a rescale factor of 1 instead of a NaN
+    float m_run = -1.0e30f;
     float l_run = 0.f;         // this half-wave's share of the running sum
 
     // K row fed to MFMA row ln: bits 2 and 3 swapped
     const int krow = (ln & ~12) | ((ln & 4) << 1) | ((ln & 8) >> 1);
 
-    load_tile(0);
-    store_tile(0);
+    if (t_lo < t_hi) {
+        load_tile(t_lo * BN);
+        store_tile(t_lo & 1);
+    }
     __syncthreads();
 
-    for (int jt = 0; jt < n_kv_tiles; ++jt) {
+    for (int jt = t_lo; jt < t_hi; ++jt) {
         const int kv0 = jt * BN;
         const int stage = jt & 1;
-        const bool more = jt + 1 < n_kv_tiles;
+        const bool more = jt + 1 < t_hi;
         if (more) load_tile(kv0 + BN);
 
         if (kv0 <= pmax) {                           // wave-uniform: this wave still has keys to see
@@ -294,6 +310,22 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_mfma_kernel(
 
     // ---- epilogue: normalise, convert, store ----------------------------------------------------------
     const float l_tot = l_run + __shfl_xor(l_run, 32);
+    if (SPLIT) {
+        if (row_ok) {
+            const int64_t slot = (s_glob * n_q_heads + g * grp + hh) * (int64_t)n_splits + split;
+            float *prow = part_o + slot * D;
+#pragma unroll
+            for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    const int d0 = 32 * db + 8 * r4 + 4 * hf;
+                    *reinterpret_cast<float4 *>(prow + d0) = make_float4(o_acc[db][4 * r4 + 0], o_acc[db][4 * r4 + 1],
+                                                                         o_acc[db][4 * r4 + 2], o_acc[db][4 * r4 + 3]);
+                }
+            if (hf == 0) part_ml[slot] = make_float2(m_run, l_tot);
+        }
+        return;
+    }
     const float inv = 1.0f / l_tot;
     if (row_ok) {
         uint16_t *orow = out + q_row;
@@ -313,10 +345,42 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_mfma_kernel(
 }
 
 
+// combines the split pieces of every row: out = sum_s w_s O_s / sum_s w_s l_s with
+// w_s = 2^(m_s - max m); pieces that saw no key carry l = 0 and drop out
+__global__ __launch_bounds__(256) void attn_merge_kernel(int64_t n_rows, int n_splits,
+                                                         const float *__restrict__ part_o,
+                                                         const float2 *__restrict__ part_ml,
+                                                         uint16_t *__restrict__ out, float *__restrict__ lse_out)
+{
+    const int64_t row = (int64_t)blockIdx.x * (256 / D) + threadIdx.x / D;
+    const int c = threadIdx.x % D;
+    if (row >= n_rows) return;
+    const float2 *ml = part_ml + row * n_splits;
+    float m = -1.0e30f;
+    for (int s = 0; s < n_splits; ++s)
+        if (ml[s].y > 0.f) m = fmaxf(m, ml[s].x);
+    float l = 0.f, o = 0.f;
+    for (int s = 0; s < n_splits; ++s) {
+        const float2 p = ml[s];
+        if (p.y > 0.f) {
+            const float w = __builtin_amdgcn_exp2f(p.x - m);
+            l += w * p.y;
+            o += w * part_o[(row * n_splits + s) * D + c];
+        }
+    }
+    out[row * D + c] = (uint16_t)f32_to_bf16_bits(o / l);
+    if (lse_out && c == 0) lse_out[row] = (m + __builtin_amdgcn_logf(l)) * 0.6931471805599453f;
+}
+
+constexpr size_t kPartBytesPerSlot = D * sizeof(float) + sizeof(float2);
+constexpr int kSplitMaxWgs = 1024;        // splits are chosen so that the grid stays near this
+constexpr int kSplitBelowWgs = 384;       // launches with fewer workgroups than this get split
+constexpr int kSplitMax = 16;
+
 template <int NWAVES>
 kvs_status launch_mfma_variant(const kvs_shape *shape, const AttnBatch &bd, const void *q_sel, const int32_t *sel_pos,
                                const void *k_cache, const void *v_cache, float scale, void *out, float *lse_out,
-                               hipStream_t st)
+                               void *workspace, size_t workspace_bytes, hipStream_t st)
 {
     constexpr int ROWS = NWAVES * 32;
     AttnTiles td;
@@ -326,19 +390,55 @@ kvs_status launch_mfma_variant(const kvs_shape *shape, const AttnBatch &bd, cons
     const size_t lds_bytes = 2 * STAGE * sizeof(uint16_t);
     static bool attr_set = false;   // idempotent; a race only repeats the same call
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_mfma_kernel<NWAVES>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_mfma_kernel<NWAVES, false>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_mfma_kernel<NWAVES, true>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
         if (e != hipSuccess) return fail(KVS_EHIP, "kvs_partial_attention: hipFuncSetAttribute: %s", hipGetErrorString(e));
         attr_set = true;
     }
     const float scale_log2 = scale * 1.4426950408889634f;
-    hipLaunchKernelGGL((attn_mfma_kernel<NWAVES>), dim3((unsigned)(tiles * shape->n_kv_heads)), dim3(NWAVES * 64),
-                       lds_bytes, st, td, shape->n_q_heads, shape->n_kv_heads, (int)tiles,
-                       (const uint16_t *)q_sel, sel_pos, (const uint16_t *)k_cache, (const uint16_t *)v_cache,
-                       scale_log2, (uint16_t *)out, lse_out);
-    return check_launch("kvs_partial_attention(mfma)");
+    // split the key range when the launch is too small to fill the chip, the contexts are long
+    // enough for every piece to have work, and the caller's workspace can hold the pieces
+    const int64_t wgs = tiles * shape->n_kv_heads;
+    int64_t max_ctx = 0;
+    for (int i = 0; i < bd.n_req; ++i) max_ctx = bd.ctx_len[i] > max_ctx ? bd.ctx_len[i] : max_ctx;
+    const int64_t n_rows_total = (bd.cu_sel[bd.n_req] - bd.cu_sel[0]) * shape->n_q_heads;
+    int n_splits = 1;
+    if (wgs < kSplitBelowWgs && workspace) {
+        int64_t s = (kSplitMaxWgs + wgs - 1) / wgs;
+        if (s > kSplitMax) s = kSplitMax;
+        const int64_t by_len = max_ctx / (8 * BN);                      // at least 8 KV tiles per piece
+        if (s > by_len) s = by_len;
+        const int64_t by_ws = (int64_t)(workspace_bytes / (kPartBytesPerSlot * (size_t)(n_rows_total > 0 ? n_rows_total : 1)));
+        if (s > by_ws) s = by_ws;
+        if (s >= 2) n_splits = (int)s;
+    }
+    if (n_splits == 1) {
+        hipLaunchKernelGGL((attn_mfma_kernel<NWAVES, false>), dim3((unsigned)wgs), dim3(NWAVES * 64), lds_bytes, st, td,
+                           shape->n_q_heads, shape->n_kv_heads, (int)tiles, (const uint16_t *)q_sel, sel_pos,
+                           (const uint16_t *)k_cache, (const uint16_t *)v_cache, scale_log2, (uint16_t *)out, lse_out,
+                           1, (float *)nullptr, (float2 *)nullptr);
+        return check_launch("kvs_partial_attention(mfma)");
+    }
+    // pieces are indexed by the row's position in the whole call's output, so offset the tables by
+    // the first row of this launch
+    const int64_t row0 = bd.cu_sel[0] * shape->n_q_heads;
+    float *part_o = (float *)workspace - row0 * n_splits * D;
+    float2 *part_ml = (float2 *)((char *)workspace + (size_t)n_rows_total * n_splits * D * sizeof(float)) - row0 * n_splits;
+    hipLaunchKernelGGL((attn_mfma_kernel<NWAVES, true>), dim3((unsigned)(wgs * n_splits)), dim3(NWAVES * 64), lds_bytes, st, td,
+                       shape->n_q_heads, shape->n_kv_heads, (int)tiles, (const uint16_t *)q_sel, sel_pos,
+                       (const uint16_t *)k_cache, (const uint16_t *)v_cache, scale_log2, (uint16_t *)out, lse_out,
+                       n_splits, part_o, part_ml);
+    kvs_status stt = check_launch("kvs_partial_attention(mfma split)");
+    if (stt != KVS_OK) return stt;
+    hipLaunchKernelGGL(attn_merge_kernel, dim3((unsigned)((n_rows_total + 256 / D - 1) / (256 / D))), dim3(256), 0, st,
+                       n_rows_total, n_splits, (const float *)workspace,
+                       (const float2 *)((char *)workspace + (size_t)n_rows_total * n_splits * D * sizeof(float)),
+                       (uint16_t *)out + row0 * D, lse_out ? lse_out + row0 : nullptr);
+    return check_launch("kvs_partial_attention(merge)");
 }
-
 
 } // namespace
 
@@ -369,7 +469,7 @@ bool attention_mfma_supports(const kvs_shape *shape)
 kvs_status launch_attention_mfma(const kvs_shape *shape, const AttnBatch &bd, int64_t n_sel,
                                  const void *q_sel, const int32_t *sel_pos, const void *k_cache,
                                  const void *v_cache, float scale, void *out, float *lse_out,
-                                 hipStream_t st)
+                                 void *workspace, size_t workspace_bytes, hipStream_t st)
 {
     if (!attention_mfma_supports(shape)) return fail(KVS_EUNSUPPORTED, "kvs_partial_attention: matrix-core path needs bf16, head_dim 128");
     if (!(scale > 0.f) || !isfinite(scale)) return fail(KVS_EUNSUPPORTED, "kvs_partial_attention: matrix-core path needs a positive finite scale");
@@ -387,7 +487,20 @@ kvs_status launch_attention_mfma(const kvs_shape *shape, const AttnBatch &bd, in
     for (int i = 0; i < bd.n_req; ++i) big_tiles += ((bd.cu_sel[i + 1] - bd.cu_sel[i]) * grp + 255) / 256;
     const bool big = forced ? forced == 2 : big_tiles * shape->n_kv_heads >= kAttnBigTileMinGrid;
     if (big) return launch_attention_mfma2(shape, bd, q_sel, sel_pos, k_cache, v_cache, scale, out, lse_out, st);
-    return launch_mfma_variant<KVS_ATTN_NWAVES>(shape, bd, q_sel, sel_pos, k_cache, v_cache, scale, out, lse_out, st);
+    return launch_mfma_variant<KVS_ATTN_NWAVES>(shape, bd, q_sel, sel_pos, k_cache, v_cache, scale, out, lse_out,
+                                                workspace, workspace_bytes, st);
+}
+
+size_t attention_workspace_bytes(const kvs_shape *shape, int32_t batch, int64_t n_sel_total)
+{
+    // pieces are only used for launches below kSplitBelowWgs workgroups, and then at most
+    // kSplitMaxWgs workgroup-pieces of 32*KVS_ATTN_NWAVES rows each exist
+    const int64_t rows = n_sel_total * shape->n_q_heads;
+    int64_t slots = rows * kSplitMax;
+    const int64_t cap = (int64_t)(kSplitMaxWgs + kSplitBelowWgs) * 32 * KVS_ATTN_NWAVES / shape->n_kv_heads * shape->n_kv_heads
+                        + (int64_t)batch * 32 * KVS_ATTN_NWAVES * kSplitMax;
+    if (slots > cap) slots = cap;
+    return (size_t)slots * kPartBytesPerSlot + 256;
 }
 
 } // namespace kvs

@@ -59,6 +59,19 @@ __device__ __forceinline__ uint32_t pack2(float lo, float hi)
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));
 }
 
+// Sum of the eight bf16 values of a packed P operand, exactly as the matrix core will see them.
+// The softmax normaliser is built from these rounded weights, not from the fp32 ones: numerator
+// and denominator then carry the same rounding, so a row dominated by a single key still returns
+// that key's V exactly (with a fixed exponent reference the dominant weight is not 1.0 and its
+// bf16 rounding error, up to 2^-9, would otherwise pass straight into the output).
+__device__ __forceinline__ float rounded_sum(const u32x4_t w)
+{
+    return ((bf16_lo(w.x) + bf16_hi(w.x)) + (bf16_lo(w.y) + bf16_hi(w.y))) +
+           ((bf16_lo(w.z) + bf16_hi(w.z)) + (bf16_lo(w.w) + bf16_hi(w.w)));
+}
+
+// WANT_LSE: additionally keep the unrounded sum of weights, from which the log-sum-exp is reported
+template <bool WANT_LSE>
 __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
     const AttnTiles td, int n_q_heads, int n_kv_heads, int total_tiles,
     const uint16_t *__restrict__ q_sel, const int32_t *__restrict__ sel_pos,
@@ -234,7 +247,8 @@ __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
 
     floatx16 o_acc[D / 32][NB];
     float m_ref[NB], l_run[NB];   // softmax exponent reference (shared by the two half-waves) and this
-                                  // half-wave's share of the running sum
+                                  // half-wave's share of the running sum of (bf16-rounded) weights
+    float l_exact[NB];            // same sum over the unrounded weights (WANT_LSE only)
     // P = exp2(scale*log2e*S - m_ref) -> bf16 B operands.  The reference is fixed for the whole
     // pass, so the output accumulators are touched by MFMAs only and can stay in the accumulation
     // registers; see the comment at the pass loop for why that is safe.
@@ -242,12 +256,9 @@ __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
         mask_tile(jt, s);
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
-            float pv[16], psum = 0.f;
+            float pv[16];
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                pv[r] = __builtin_amdgcn_exp2f(fmaf(s[nb][r], scale_log2, -m_ref[nb]));
-                psum += pv[r];
-            }
+            for (int r = 0; r < 16; ++r) pv[r] = __builtin_amdgcn_exp2f(fmaf(s[nb][r], scale_log2, -m_ref[nb]));
 #pragma unroll
             for (int a = 0; a < 2; ++a) {
                 pop[nb][a].x = pack2(pv[8 * a + 0], pv[8 * a + 1]);
@@ -255,7 +266,13 @@ __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
                 pop[nb][a].z = pack2(pv[8 * a + 4], pv[8 * a + 5]);
                 pop[nb][a].w = pack2(pv[8 * a + 6], pv[8 * a + 7]);
             }
-            l_run[nb] += psum;
+            l_run[nb] += rounded_sum(pop[nb][0]) + rounded_sum(pop[nb][1]);
+            if (WANT_LSE) {
+                float e = 0.f;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) e += pv[r];
+                l_exact[nb] += e;
+            }
         }
     };
     auto pv_product = [&](int jt, const u32x4_t (&pop)[NB][2]) {
@@ -300,12 +317,9 @@ __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
         u32x4_t pop[NB][2];
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
-            float pv[16], psum = 0.f;
+            float pv[16];
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                pv[r] = __builtin_amdgcn_exp2f(fmaf(s_in[nb][r], scale_log2, -m_ref[nb]));
-                psum += pv[r];
-            }
+            for (int r = 0; r < 16; ++r) pv[r] = __builtin_amdgcn_exp2f(fmaf(s_in[nb][r], scale_log2, -m_ref[nb]));
 #pragma unroll
             for (int a = 0; a < 2; ++a) {
                 pop[nb][a].x = pack2(pv[8 * a + 0], pv[8 * a + 1]);
@@ -313,7 +327,13 @@ __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
                 pop[nb][a].z = pack2(pv[8 * a + 4], pv[8 * a + 5]);
                 pop[nb][a].w = pack2(pv[8 * a + 6], pv[8 * a + 7]);
             }
-            l_run[nb] += psum;
+            l_run[nb] += rounded_sum(pop[nb][0]) + rounded_sum(pop[nb][1]);
+            if (WANT_LSE) {
+                float e = 0.f;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) e += pv[r];
+                l_exact[nb] += e;
+            }
         }
 #pragma unroll
         for (int a = 0; a < 2; ++a)
@@ -368,7 +388,7 @@ __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
             for (int nb = 0; nb < NB; ++nb) m_ref[nb] = row_max(s_cur[nb]);
         }
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb) l_run[nb] = 0.f;
+        for (int nb = 0; nb < NB; ++nb) { l_run[nb] = 0.f; l_exact[nb] = 0.f; }
 #pragma unroll
         for (int db = 0; db < D / 32; ++db)
 #pragma unroll
@@ -422,6 +442,7 @@ __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
         const float inv = 1.0f / l_tot[nb];
+        const float l_exact_tot = WANT_LSE ? l_exact[nb] + __shfl_xor(l_exact[nb], 32) : 0.f;
         if (row_ok[nb]) {
             uint16_t *orow = out + row_idx[nb] * D;
 #pragma unroll
@@ -434,8 +455,8 @@ __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
                     w.y = pack2(o_acc[db][nb][4 * r4 + 2] * inv, o_acc[db][nb][4 * r4 + 3] * inv);
                     *reinterpret_cast<uint2 *>(orow + d0) = w;
                 }
-            if (lse_out && hf == 0)
-                lse_out[row_idx[nb]] = (m_ref[nb] + __builtin_amdgcn_logf(l_tot[nb])) * 0.6931471805599453f;
+            if (WANT_LSE && hf == 0)
+                lse_out[row_idx[nb]] = (m_ref[nb] + __builtin_amdgcn_logf(l_exact_tot)) * 0.6931471805599453f;
         }
     }
 }
@@ -453,15 +474,24 @@ kvs_status launch_attention_mfma2(const kvs_shape *shape, const AttnBatch &bd, c
     const size_t lds_bytes = NSTAGE * STAGE * sizeof(uint16_t);
     static bool attr_set = false;   // idempotent; a race only repeats the same call
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_mfma2_kernel),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_mfma2_kernel<false>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_mfma2_kernel<true>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
         if (e != hipSuccess) return fail(KVS_EHIP, "kvs_partial_attention: hipFuncSetAttribute: %s", hipGetErrorString(e));
         attr_set = true;
     }
     const float scale_log2 = scale * 1.4426950408889634f;
-    hipLaunchKernelGGL(attn_mfma2_kernel, dim3((unsigned)(tiles * shape->n_kv_heads)), dim3(NT), lds_bytes, st,
-                       td, shape->n_q_heads, shape->n_kv_heads, (int)tiles, (const uint16_t *)q_sel, sel_pos,
-                       (const uint16_t *)k_cache, (const uint16_t *)v_cache, scale_log2, (uint16_t *)out, lse_out);
+    const dim3 grid((unsigned)(tiles * shape->n_kv_heads)), block(NT);
+    if (lse_out)
+        hipLaunchKernelGGL(attn_mfma2_kernel<true>, grid, block, lds_bytes, st, td, shape->n_q_heads, shape->n_kv_heads,
+                           (int)tiles, (const uint16_t *)q_sel, sel_pos, (const uint16_t *)k_cache,
+                           (const uint16_t *)v_cache, scale_log2, (uint16_t *)out, lse_out);
+    else
+        hipLaunchKernelGGL(attn_mfma2_kernel<false>, grid, block, lds_bytes, st, td, shape->n_q_heads, shape->n_kv_heads,
+                           (int)tiles, (const uint16_t *)q_sel, sel_pos, (const uint16_t *)k_cache,
+                           (const uint16_t *)v_cache, scale_log2, (uint16_t *)out, lse_out);
     return check_launch("kvs_partial_attention(mfma2)");
 }
 

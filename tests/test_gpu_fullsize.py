@@ -23,10 +23,17 @@ def say(msg):
     sys.stdout.flush()
 
 
-def attn_close(got, ref):
+def attn_close(got, ref, mag):
+    """2e-2 absolute plus 2^-8 of the attended magnitude sum_i a_i |v_i| (bf16 softmax weights and
+    bf16 output; same bound as in test_gpu_parity.py)."""
     err = np.abs(np.asarray(got, np.float64) - ref)
-    tol = 2e-2 + np.abs(ref) * 2.0 ** -8
+    tol = 2e-2 + np.asarray(mag, np.float64) * 2.0 ** -8
     assert np.all(err <= tol), f"attention error {err.max()}"
+
+
+def abs_bf16(a):
+    """|x| on raw bf16 bit patterns (clear the sign bit)."""
+    return (np.asarray(a).view(np.uint16) & np.uint16(0x7FFF)).view(np.uint16)
 
 
 def prefill_layer(w, ratio, n_sample, projected):
@@ -71,7 +78,8 @@ def prefill_layer(w, ratio, n_sample, projected):
     torch.cuda.synchronize()
     pick = np.unique(np.concatenate([[0, 1, k - 2, k - 1], np.linspace(0, k - 1, n_sample).round().astype(np.int64)]))
     ref, ref_lse = oracle.partial_attention(q_sel[pick].cpu(), idx_ref[pick], kc, vc, 1.0)
-    attn_close(out[pick].float().cpu().numpy(), ref)
+    mag, _ = oracle.partial_attention(q_sel[pick].cpu(), idx_ref[pick], kc, abs_bf16(vc), 1.0)
+    attn_close(out[pick].float().cpu().numpy(), ref, mag)
     np.testing.assert_allclose(lse[pick].cpu().numpy(), ref_lse, atol=2e-3)
     # properties over every row: finite, and |o| bounded by the largest |V| a row can see
     o = out.float()
@@ -157,7 +165,9 @@ def test_decode_batch_full_size():
         fin = np.isfinite(ref_sc)
         assert np.array_equal(np.isfinite(sc[sl]), fin)
         np.testing.assert_allclose(sc[sl][fin], ref_sc[fin], rtol=1e-5)
-        attn_close(attn[b:b + 1].float().cpu().numpy(), ref_attn)
+        _, _, mag_attn = oracle.decode_check(q_new[b:b + 1].cpu(), kc, dev_h[:, sl].copy(), reused_h[sl].copy(), 1.0,
+                                             [0], [lens[b]], [0], v_cache=abs_bf16(vc), want_attn=True)
+        attn_close(attn[b:b + 1].float().cpu().numpy(), ref_attn, mag_attn)
         thr = np.sort(ref_sc)[::-1][kreq[b] - 1]
         got = set(ix[cu[b]:cu[b + 1]].tolist())
         assert set(np.nonzero(ref_sc > thr * (1 + 2e-5))[0].tolist()) <= got
@@ -175,5 +185,7 @@ def test_decode_batch_full_size():
     for b in (0, 17, 63):
         sl = slice(int(off[b]), int(off[b] + lens[b]))
         rows_b = np.arange(cu[b], cu[b + 1])[:: max(1, kreq[b] // 6)]
-        ref, _ = oracle.partial_attention(q_sel[rows_b].cpu(), ix[rows_b], oracle._as_np(gk[sl].cpu()), oracle._as_np(gv[sl].cpu()), 1.0)
-        attn_close(out[rows_b].float().cpu().numpy(), ref)
+        kh, vh = oracle._as_np(gk[sl].cpu()), oracle._as_np(gv[sl].cpu())
+        ref, _ = oracle.partial_attention(q_sel[rows_b].cpu(), ix[rows_b], kh, vh, 1.0)
+        mag, _ = oracle.partial_attention(q_sel[rows_b].cpu(), ix[rows_b], kh, abs_bf16(vh), 1.0)
+        attn_close(out[rows_b].float().cpu().numpy(), ref, mag)
