@@ -299,9 +299,9 @@ def main() -> int:
                                f"recompute ratio {args.ratio}, alpha {args.alpha}, decode re-check 2% of cache entries; "
                                f"one step = one layer of the 32-layer stack",
                    "layers_resident": n_slots, "k_selected": k_mean, "k_decode": slots[0].k_dec},
-        "roofline": {"kernel": "attn_mfma_kernel (kvs_partial_attention, prefill selection)", "bound": "mfma",
+        "roofline": {"kernel": "attn_mfma2_kernel (kvs_partial_attention, prefill selection)", "bound": "mfma",
                      "achieved": attn_tflops, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": attn_tflops / MFMA_BF16_PEAK_TFLOPS, "traffic": read_traffic("attn_mfma_kernel"),
+                     "frac": attn_tflops / MFMA_BF16_PEAK_TFLOPS, "traffic": read_traffic("attn_mfma2_kernel prefill launch"),
                      "flops_per_launch": flops, "avg_launch_ms": float(t_attn)},
         "components": {
             "deviation_select": {"ms": float(t_devsel), "GBps": (bytes_dev + bytes_sel) / (t_devsel * 1e-3) / 1e9,
@@ -314,6 +314,16 @@ def main() -> int:
             "decode_recompute": {"ms": float(t_decrec), "attention_TFLOP": flops_dec / 1e12},
         },
     }
+    # One untimed launch of known traffic for the profiler: kvs_scatter_kv over every row of a layer
+    # is a plain copy (reads 2 x 64 MiB + 128 KiB of indices, writes 2 x 64 MiB); the HBM counters
+    # of the other kernels are scaled by what they report for this one.
+    cal = slots[0]
+    all_rows = torch.arange(n, dtype=torch.int32, device="cuda")
+    kdst, vdst = torch.empty_like(cal.k_fresh), torch.empty_like(cal.v_fresh)
+    B.kvs_scatter_kv(sh, n, cal.k_fresh, cal.v_fresh, all_rows, n, kdst, vdst, None, None)
+    torch.cuda.synchronize()
+    del kdst, vdst
+
     if args.cpu_sample > 0:
         cb = cpu_baseline_and_parity(w, args.ratio, sh, alpha_n, args.cpu_sample)
         cb["attention_extrapolated_ms_per_layer"] = flops / (cb["value"] * 1e12) * 1e3

@@ -28,8 +28,8 @@
  * KVS_EHIP: the HIP runtime refused a launch).  kvs_last_error() returns a thread-local
  * description of the most recent failure.  Nothing throws or aborts across this boundary.
  *
- * Supported shapes: dtype KVS_BF16 or KVS_F32; head_dim 64 or 128; n_kv_heads * head_dim *
- * sizeof(element) a multiple of 256 bytes.
+ * Supported shapes: dtype KVS_BF16 or KVS_F32; head_dim 64 or 128; any n_q_heads that is a
+ * multiple of n_kv_heads (n_kv_heads <= 64).
  */
 #ifndef KVS_H
 #define KVS_H
@@ -101,7 +101,8 @@ KVS_API kvs_status kvs_deviation(const kvs_shape *shape, int64_t n_tokens,
  * k_row    [host] int32[n_rows], 0 <= k_row[r] <= row length; rows longer than 2^31-1 are
  *          rejected
  * idx_out  [dev] int32[sum k_row]
- * workspace [dev] at least kvs_workspace_size("select_topk", ...) bytes, 256-byte aligned
+ * workspace currently unused by this call (NULL / 0 is valid); kept in the signature so that a
+ *          multi-workgroup variant for very long rows can be added without an ABI change
  */
 KVS_API kvs_status kvs_select_topk(const float *scores, int32_t n_rows, const int64_t *row_off,
                            const int32_t *k_row, int32_t *idx_out,
@@ -143,8 +144,14 @@ KVS_API kvs_status kvs_scatter_kv(const kvs_shape *shape, int64_t n_rows,
  *         within each request, each in [0, ctx_len[b])
  * out     [dev] [n_sel, n_q_heads, head_dim] in the shape's dtype
  * lse_out [dev] fp32[n_sel, n_q_heads] or NULL
- * bf16 inputs are contracted on the matrix cores with fp32 accumulation and an fp32 online
- * softmax; fp32 inputs take an fp32 vector path.
+ * workspace [dev] optional (NULL / 0 is valid), 256-byte aligned.  With at least
+ *         kvs_workspace_size("partial_attention", ...) bytes, launches too small to fill the chip
+ *         (few selected tokens over long contexts, e.g. the decode-stage recompute) cut each row
+ *         tile's key range into pieces handled by separate workgroups and merge them; results
+ *         are the same up to fp32 summation order.
+ * bf16 inputs (head_dim 128, scale > 0) are contracted on the matrix cores with fp32 accumulation
+ * and an fp32 softmax, the softmax weights entering the second product as bf16; every other case
+ * takes an fp32 vector path.
  */
 KVS_API kvs_status kvs_partial_attention(const kvs_shape *shape, int32_t batch,
                                  const int64_t *ctx_off, const int64_t *ctx_len,
