@@ -20,9 +20,21 @@
 // only on tiles that can straddle a row position of the wave, heaviest row tiles first, KV head =
 // blockIdx % n_kv_heads.
 //
-// LDS ring of three stages (K tile, V^T tile).  In iteration j the wave reads K of tile j+1 and
-// V^T of tile j and, at the bottom, writes tile j+2 into the stage that held tile j-1; one barrier
-// per iteration.
+// Software pipeline (fast sweep).  Step j issues, for one wave, three independent strands:
+//   * the score MFMAs of tile j+1        (K tile j+1 from LDS, Q from registers),
+//   * the PV MFMAs of tile j-1           (V^T tile j-1 from LDS, P of tile j-1 from registers),
+//   * the softmax of tile j              (vector instructions only),
+// so every MFMA of the step has vector work to run beside it; the source interleaves them in the
+// ratio the hardware sustains (an MFMA holds the issue port for roughly half of its 32 cycles, the
+// other half takes about four vector instructions) and scheduling barriers keep that order.
+//
+// LDS: K ring of four tiles, V^T ring of eight.  Step j first writes tile j+2 (loaded two steps
+// earlier) into the rings and sends out the global loads of tile j+4, then reads K of tile j+1 and
+// V^T of tile j-1 (the general loop: V^T of tile j).  One barrier per step, placed in the middle of
+// the step: the rings are deep enough that a slot is rewritten only two barriers after its last
+// reader, so no wave ever waits at a step boundary and the LDS operands of a step's first MFMAs are
+// fetched at the end of the step before.  Global loads use buffer instructions with scalar tile
+// offsets, so the loop carries no per-lane address arithmetic.
 #include "attention.h"
 
 #include <math.h>
@@ -41,13 +53,21 @@ constexpr int NT = NWAVES * 64;
 constexpr int WROWS = 32 * NB;
 constexpr int ROWS = NWAVES * WROWS;   // 256 rows per workgroup
 constexpr int K_LD = D + 8;        // K tile row pitch in bf16 (272 B)
-constexpr int V_LD = BN + 8;       // V^T tile row pitch in bf16 (80 B)
+constexpr int V_LD = D + 16;        // V tile row pitch in bf16 (288 B): 4 consecutive rows x 32 B hit 32 distinct banks
 constexpr int K_TILE = BN * K_LD;
-constexpr int V_TILE = D * V_LD;
-constexpr int STAGE = K_TILE + V_TILE;
-constexpr int NSTAGE = 3;
+constexpr int V_TILE = BN * V_LD;
+constexpr int K_RING = 4;   // >= 3, see the barrier argument at fast_step
+constexpr int V_RING = 8;   // >= 5
+constexpr int LDS_ELEMS = K_RING * K_TILE + V_RING * V_TILE;
 constexpr int K_PIECES = BN * (D / 8) / NT;   // 2
-static_assert(K_PIECES == 2 && (BN / 8) == NWAVES, "tile staging assumes 256 lanes and 32 keys");
+#ifndef KVS_ATTN_PIN_SCHEDULE
+#define KVS_ATTN_PIN_SCHEDULE 1
+#endif
+#if KVS_ATTN_PIN_SCHEDULE
+#define KVS_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)   // nothing is scheduled across this point
+#else
+#define KVS_SCHED_FENCE() do {} while (0)
+#endif
 
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4_t v) { return __builtin_bit_cast(bf16x8, v); }
 
@@ -64,11 +84,30 @@ __device__ __forceinline__ uint32_t pack2(float lo, float hi)
 // and denominator then carry the same rounding, so a row dominated by a single key still returns
 // that key's V exactly (with a fixed exponent reference the dominant weight is not 1.0 and its
 // bf16 rounding error, up to 2^-9, would otherwise pass straight into the output).
-__device__ __forceinline__ float rounded_sum(const u32x4_t w)
+// One accumulation register into a vector register, at this point of the program.  The scores of a
+// tile are produced by MFMAs into accumulation registers and consumed a step later by the softmax;
+// left to itself the compiler copies all of them out right behind the last MFMA, which stalls on
+// that MFMA.  The caller keeps at least 11 instructions between the MFMA and this read.
+__device__ __forceinline__ float acc_read(float acc)
 {
-    return ((bf16_lo(w.x) + bf16_hi(w.x)) + (bf16_lo(w.y) + bf16_hi(w.y))) +
-           ((bf16_lo(w.z) + bf16_hi(w.z)) + (bf16_lo(w.w) + bf16_hi(w.w)));
+    float v;
+    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(v) : "a"(acc));
+    return v;
 }
+__device__ __forceinline__ float add_rounded_pair(uint32_t w, float acc)   // acc + lo(w) + hi(w), one instruction
+{
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w), __builtin_bit_cast(bf16x2, 0x3f803f80u), acc, false);
+}
+__device__ __forceinline__ float add_rounded(const u32x4_t w, float acc)
+{
+    return add_rounded_pair(w.w, add_rounded_pair(w.z, add_rounded_pair(w.y, add_rounded_pair(w.x, acc))));
+}
+
+#ifdef KVS_DIAG_CLOCK
+__device__ long long kvs_diag_clk[4096];
+#endif
+
 
 // WANT_LSE: additionally keep the unrounded sum of weights, from which the log-sum-exp is reported
 template <bool WANT_LSE>
@@ -78,11 +117,14 @@ __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
     const uint16_t *__restrict__ k_cache, const uint16_t *__restrict__ v_cache,
     float scale_log2, uint16_t *__restrict__ out, float *__restrict__ lse_out)
 {
-    extern __shared__ __attribute__((aligned(16))) uint16_t lds[];   // NSTAGE x (K tile, V^T tile)
+    extern __shared__ __attribute__((aligned(16))) uint16_t lds[];   // K ring, then V^T ring
     __shared__ int wg_max_pos[NWAVES];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int hf = lane >> 5, ln = lane & 31;
+#ifdef KVS_DIAG_CLOCK
+    const long long diag_t0 = clock64(), diag_w0 = wall_clock64();
+#endif
 
     // ---- which (request, kv head, row tile) -----------------------------------------------------
     const int g = blockIdx.x % n_kv_heads;
@@ -144,24 +186,27 @@ __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
     const int n_kv_tiles = wg_pmax / BN + 1;
 
     // ---- global -> register -> LDS staging of one K/V tile ------------------------------------------
+    // Buffer loads: the tile's position goes into the scalar offset, the per-lane part is constant.
+    // Every address is kept inside the request's rows by construction (tiles wholly inside the
+    // context, or per-row clamping); the buffer's record count is a second guard only.
     const uint32_t row_bytes = (uint32_t)n_kv_heads * D * 2u;          // bytes between tokens
-    const char *kbase = reinterpret_cast<const char *>(k_cache + (ctx_off * n_kv_heads + g) * (int64_t)D);
-    const char *vbase = reinterpret_cast<const char *>(v_cache + (ctx_off * n_kv_heads + g) * (int64_t)D);
-    struct Staged { u32x4_t k[K_PIECES]; uint32_t v[8]; };   // one tile on its way from HBM to LDS
+    const uint32_t head_bytes = ((uint32_t)ctx_len - 1u) * row_bytes + D * 2u;   // this head's span of the request
+    const __amdgpu_buffer_rsrc_t krs = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint16_t *>(k_cache + (ctx_off * n_kv_heads + g) * (int64_t)D), 0, head_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t vrs = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint16_t *>(v_cache + (ctx_off * n_kv_heads + g) * (int64_t)D), 0, head_bytes, 0x00020000);
+    struct Staged { u32x4_t k[K_PIECES], v[K_PIECES]; };   // one tile on its way from HBM to LDS
     const uint32_t k_lane_off = (uint32_t)(tid >> 4) * row_bytes + (uint32_t)(tid & 15) * 16u;
-    const uint32_t v_lane_off = (uint32_t)lane * 4u;
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
 
-    // tile jt wholly inside the context: uniform tile base + constant per-lane offsets
+    // tile jt wholly inside the context
     auto load_tile_inside = [&](int jt, Staged &st) {
-        const char *kt = kbase + (int64_t)jt * BN * row_bytes;
-        const char *vt = vbase + ((int64_t)jt * BN + 8 * wave_u) * row_bytes;
+        const uint32_t kt = (uint32_t)jt * BN * row_bytes;
 #pragma unroll
-        for (int i = 0; i < K_PIECES; ++i)
-            st.k[i] = *reinterpret_cast<const u32x4_t *>(kt + (size_t)(i * (NT / 16)) * row_bytes + k_lane_off);
-#pragma unroll
-        for (int j = 0; j < 8; ++j)
-            st.v[j] = *reinterpret_cast<const uint32_t *>(vt + (size_t)j * row_bytes + v_lane_off);
+        for (int i = 0; i < K_PIECES; ++i) {
+            st.k[i] = __builtin_amdgcn_raw_buffer_load_b128(krs, k_lane_off, kt + (uint32_t)(i * (NT / 16)) * row_bytes, 0);
+            st.v[i] = __builtin_amdgcn_raw_buffer_load_b128(vrs, k_lane_off, kt + (uint32_t)(i * (NT / 16)) * row_bytes, 0);
+        }
     };
     auto load_tile = [&](int jt, Staged &st) {      // any tile: rows past the context are clamped
         const int kv0 = jt * BN;
@@ -171,35 +216,37 @@ __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
 #pragma unroll
             for (int i = 0; i < K_PIECES; ++i) {
                 const int key = min(kv0 + i * (NT / 16) + (tid >> 4), ctx_len - 1);
-                st.k[i] = *reinterpret_cast<const u32x4_t *>(kbase + (int64_t)key * row_bytes + (tid & 15) * 16);
-            }
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const int key = min(kv0 + 8 * wave_u + j, ctx_len - 1);
-                st.v[j] = *reinterpret_cast<const uint32_t *>(vbase + (int64_t)key * row_bytes + v_lane_off);
+                st.k[i] = __builtin_amdgcn_raw_buffer_load_b128(krs, (uint32_t)key * row_bytes + (uint32_t)(tid & 15) * 16u, 0, 0);
+                st.v[i] = __builtin_amdgcn_raw_buffer_load_b128(vrs, (uint32_t)key * row_bytes + (uint32_t)(tid & 15) * 16u, 0, 0);
             }
         }
     };
+    uint16_t *const k_ring = lds;
+    uint16_t *const v_ring = lds + K_RING * K_TILE;
     auto store_tile = [&](int jt, const Staged &st) {
-        uint16_t *ks = lds + (jt % NSTAGE) * STAGE;
-        uint16_t *vs = ks + K_TILE;
+        uint16_t *ks = k_ring + (jt & (K_RING - 1)) * K_TILE;
+        uint16_t *vs = v_ring + (jt & (V_RING - 1)) * V_TILE;
 #pragma unroll
         for (int i = 0; i < K_PIECES; ++i) {
             const int id = i * NT + tid;
             *reinterpret_cast<u32x4_t *>(ks + (id >> 4) * K_LD + (id & 15) * 8) = st.k[i];
+            *reinterpret_cast<u32x4_t *>(vs + (id >> 4) * V_LD + (id & 15) * 8) = st.v[i];
         }
-        u32x4_t lo, hi;   // channel 2*lane and 2*lane+1 of keys 8*wave .. 8*wave+7
-        // v_perm_b32: bytes 0-3 come from the second operand, 4-7 from the first
-        lo.x = __builtin_amdgcn_perm(st.v[1], st.v[0], 0x05040100u);
-        lo.y = __builtin_amdgcn_perm(st.v[3], st.v[2], 0x05040100u);
-        lo.z = __builtin_amdgcn_perm(st.v[5], st.v[4], 0x05040100u);
-        lo.w = __builtin_amdgcn_perm(st.v[7], st.v[6], 0x05040100u);
-        hi.x = __builtin_amdgcn_perm(st.v[1], st.v[0], 0x07060302u);
-        hi.y = __builtin_amdgcn_perm(st.v[3], st.v[2], 0x07060302u);
-        hi.z = __builtin_amdgcn_perm(st.v[5], st.v[4], 0x07060302u);
-        hi.w = __builtin_amdgcn_perm(st.v[7], st.v[6], 0x07060302u);
-        *reinterpret_cast<u32x4_t *>(vs + (2 * lane) * V_LD + 8 * wave) = lo;
-        *reinterpret_cast<u32x4_t *>(vs + (2 * lane + 1) * V_LD + 8 * wave) = hi;
+    };
+    // the same staging in pieces, for the pipelined sweep (tile wholly inside the context)
+    auto load_k_piece = [&](int jt, Staged &st, int i) {
+        st.k[i] = __builtin_amdgcn_raw_buffer_load_b128(krs, k_lane_off, ((uint32_t)jt * BN + (uint32_t)(i * (NT / 16))) * row_bytes, 0);
+    };
+    auto load_v_piece = [&](int jt, Staged &st, int i) {
+        st.v[i] = __builtin_amdgcn_raw_buffer_load_b128(vrs, k_lane_off, ((uint32_t)jt * BN + (uint32_t)(i * (NT / 16))) * row_bytes, 0);
+    };
+    auto store_k_piece = [&](int jt, const Staged &st, int i) {
+        const int id = i * NT + tid;
+        *reinterpret_cast<u32x4_t *>(k_ring + (jt & (K_RING - 1)) * K_TILE + (id >> 4) * K_LD + (id & 15) * 8) = st.k[i];
+    };
+    auto store_v_piece = [&](int jt, const Staged &st, int i) {
+        const int id = i * NT + tid;
+        *reinterpret_cast<u32x4_t *>(v_ring + (jt & (V_RING - 1)) * V_TILE + (id >> 4) * V_LD + (id & 15) * 8) = st.v[i];
     };
 
     // ---- the three pieces of one tile's work ----------------------------------------------------------
@@ -207,20 +254,35 @@ __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
     // 16*(r>>3) + 8*hf + (r&7) of the tile
     const int krow = (ln & ~12) | ((ln & 4) << 1) | ((ln & 8) >> 1);
     const uint32_t k_read_off = (uint32_t)(krow * K_LD + 8 * hf);      // + 16*ks
-    const uint32_t v_read_off = (uint32_t)(ln * V_LD + 8 * hf);        // + 32*db*V_LD + 16*kstep
+    // V stays row-major [key][channel] in LDS; the A operand of the PV product (channel = MFMA row,
+    // 8 consecutive keys per lane) comes out of two transposing LDS reads.  In each group of 16
+    // lanes, lane s points at 8 bytes (4 channels) and lane i receives, as element j, element i%4 of
+    // the lane i/4 + 4j: with lane s on key k0 + s/4, channels d0 + 4*(s%4) .. +3, lane i ends up
+    // with channel d0 + i of keys k0 .. k0+3.  Groups 0/1 are channels 0-15 / 16-31 of the block,
+    // groups 2/3 the same for the half-wave's second set of 8 keys.
+    const int tr_s = lane & 15, tr_g = lane >> 4;
+    const uint32_t v_read_off = (uint32_t)((8 * (tr_g >> 1) + (tr_s >> 2)) * V_LD + 16 * (tr_g & 1) + 4 * (tr_s & 3));
+    // + 16*kstep*V_LD + 32*db for keys 0-3 of the lane's 8, + 4*V_LD more for keys 4-7
+    auto read_vt = [&](const uint16_t *vs, int kstep, int db) -> u32x4_t {
+        typedef short v4i16 __attribute__((ext_vector_type(4)));
+        typedef __attribute__((address_space(3))) v4i16 lds_v4i16;
+        const uint16_t *p = vs + 16 * kstep * V_LD + 32 * db;
+        const v4i16 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16 *)(p));
+        const v4i16 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16 *)(p + 4 * V_LD));
+        const uint2 l2 = __builtin_bit_cast(uint2, lo), h2 = __builtin_bit_cast(uint2, hi);
+        u32x4_t r = {l2.x, l2.y, h2.x, h2.y};
+        return r;
+    };
+    const floatx16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
     auto qk = [&](int jt, floatx16 (&s)[NB]) {
-        const uint16_t *ks = lds + (jt % NSTAGE) * STAGE;
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) s[nb][r] = 0.f;
+        const uint16_t *ks = k_ring + (jt & (K_RING - 1)) * K_TILE + k_read_off;
 #pragma unroll
         for (int ksx = 0; ksx < D / 16; ++ksx) {
-            const u32x4_t a = *reinterpret_cast<const u32x4_t *>(ks + k_read_off + 16 * ksx);
+            const u32x4_t a = *reinterpret_cast<const u32x4_t *>(ks + 16 * ksx);
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb)
-                s[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a), qreg[nb][ksx], s[nb], 0, 0, 0);
+                s[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a), qreg[nb][ksx], ksx == 0 ? zero : s[nb], 0, 0, 0);
         }
     };
 
@@ -249,101 +311,106 @@ __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
     float m_ref[NB], l_run[NB];   // softmax exponent reference (shared by the two half-waves) and this
                                   // half-wave's share of the running sum of (bf16-rounded) weights
     float l_exact[NB];            // same sum over the unrounded weights (WANT_LSE only)
-    // P = exp2(scale*log2e*S - m_ref) -> bf16 B operands.  The reference is fixed for the whole
-    // pass, so the output accumulators are touched by MFMAs only and can stay in the accumulation
-    // registers; see the comment at the pass loop for why that is safe.
+    // Four scores r0..r0+3 of query block nb -> two packed bf16 pairs of the P operand, and their
+    // contribution to the running sums.  P = exp2(scale*log2e*S - m_ref); the reference is fixed for
+    // the whole pass, so the output accumulators are touched by MFMAs only and can stay in the
+    // accumulation registers; see the comment at the pass loop for why that is safe.
+    auto softmax4 = [&](const floatx16 &s, int nb, int r0, u32x4_t (&pop)[2]) {
+        const float e0 = __builtin_amdgcn_exp2f(fmaf(s[r0 + 0], scale_log2, -m_ref[nb]));
+        const float e1 = __builtin_amdgcn_exp2f(fmaf(s[r0 + 1], scale_log2, -m_ref[nb]));
+        const float e2 = __builtin_amdgcn_exp2f(fmaf(s[r0 + 2], scale_log2, -m_ref[nb]));
+        const float e3 = __builtin_amdgcn_exp2f(fmaf(s[r0 + 3], scale_log2, -m_ref[nb]));
+        const uint32_t w0 = pack2(e0, e1), w1 = pack2(e2, e3);
+        pop[r0 >> 3][(r0 & 7) >> 1] = w0;
+        pop[r0 >> 3][((r0 & 7) >> 1) + 1] = w1;
+        l_run[nb] = add_rounded_pair(w1, add_rounded_pair(w0, l_run[nb]));
+        if (WANT_LSE) l_exact[nb] += (e0 + e1) + (e2 + e3);
+    };
     auto softmax = [&](int jt, floatx16 (&s)[NB], u32x4_t (&pop)[NB][2]) {
         mask_tile(jt, s);
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb) {
-            float pv[16];
+        for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) pv[r] = __builtin_amdgcn_exp2f(fmaf(s[nb][r], scale_log2, -m_ref[nb]));
-#pragma unroll
-            for (int a = 0; a < 2; ++a) {
-                pop[nb][a].x = pack2(pv[8 * a + 0], pv[8 * a + 1]);
-                pop[nb][a].y = pack2(pv[8 * a + 2], pv[8 * a + 3]);
-                pop[nb][a].z = pack2(pv[8 * a + 4], pv[8 * a + 5]);
-                pop[nb][a].w = pack2(pv[8 * a + 6], pv[8 * a + 7]);
-            }
-            l_run[nb] += rounded_sum(pop[nb][0]) + rounded_sum(pop[nb][1]);
-            if (WANT_LSE) {
-                float e = 0.f;
-#pragma unroll
-                for (int r = 0; r < 16; ++r) e += pv[r];
-                l_exact[nb] += e;
-            }
-        }
+            for (int r0 = 0; r0 < 16; r0 += 4) softmax4(s[nb], nb, r0, pop[nb]);
     };
     auto pv_product = [&](int jt, const u32x4_t (&pop)[NB][2]) {
-        const uint16_t *vs = lds + (jt % NSTAGE) * STAGE + K_TILE;
+        const uint16_t *vs = v_ring + (jt & (V_RING - 1)) * V_TILE + v_read_off;
 #pragma unroll
         for (int a = 0; a < 2; ++a)
 #pragma unroll
             for (int db = 0; db < D / 32; ++db) {
-                const u32x4_t va = *reinterpret_cast<const u32x4_t *>(vs + v_read_off + 32 * db * V_LD + 16 * a);
+                const u32x4_t va = read_vt(vs, a, db);
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb)
                     o_acc[db][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(va), as_bf16x8(pop[nb][a]), o_acc[db][nb], 0, 0, 0);
             }
     };
 
-    // One tile of the fast sweep: no masking, no tail handling, one straight-line block.  On entry
-    // tiles jt and jt+1 are in the LDS ring and `held` carries tile jt+2; the global loads of tile
-    // jt+3 go out first (they have this whole step and the next to land), then all LDS operands of
-    // the step (K of tile jt+1, V^T of tile jt), the score MFMAs of tile jt+1 ahead of the softmax of
-    // tile jt so that the vector work runs in their shadow, and the PV MFMAs of tile jt.
-    auto fast_step = [&](int jt, floatx16 (&s_in)[NB], floatx16 (&s_out)[NB], const Staged &held, Staged &next) {
-        load_tile_inside(jt + 3, next);
-        const uint16_t *ks = lds + ((jt + 1) % NSTAGE) * STAGE;
-        const uint16_t *vs = lds + (jt % NSTAGE) * STAGE + K_TILE;
-        u32x4_t ka[D / 16], va[2][D / 32];
+    // One step of the fast sweep (tile jt needs no causal compare for this wave and tile jt+4 lies
+    // wholly inside the context): scores of tile jt+1, softmax of tile jt, PV of tile jt-1, written
+    // as eight slices of four MFMAs and four scores each, LDS operands fetched one slice ahead
+    // (ka / va enter with slice 0's operands and leave with those of the next step).
+    // On entry tiles jt-1 .. jt+1 are in the LDS rings, `set` carries tile jt+2, s_in the scores of
+    // tile jt and p_in the weights of tile jt-1.
+    // Ring safety with the barrier in mid-step: a slot written at the start of step j was last read
+    // in step j-2 or earlier (K of tile j-2 in step j-3, V^T of tile j-6 in step j-5 at the latest),
+    // and every wave passed the barrier of step j-1 after that read and before this write; tile j+2
+    // is first read in step j+1, after this step's barrier.
+    auto fast_step = [&](int jt, const floatx16 (&s_in)[NB], floatx16 (&s_out)[NB],
+                         const u32x4_t (&p_in)[NB][2], u32x4_t (&p_out)[NB][2], Staged &set,
+                         u32x4_t &ka, u32x4_t &va) {
+        const uint16_t *ks = k_ring + ((jt + 1) & (K_RING - 1)) * K_TILE + k_read_off;
+        const uint16_t *vs = v_ring + ((jt - 1) & (V_RING - 1)) * V_TILE + v_read_off;
+        const uint16_t *ks_next = k_ring + ((jt + 2) & (K_RING - 1)) * K_TILE + k_read_off;
+        const uint16_t *vs_next = v_ring + (jt & (V_RING - 1)) * V_TILE + v_read_off;
 #pragma unroll
-        for (int ksx = 0; ksx < D / 16; ++ksx) ka[ksx] = *reinterpret_cast<const u32x4_t *>(ks + k_read_off + 16 * ksx);
-#pragma unroll
-        for (int a = 0; a < 2; ++a)
-#pragma unroll
-            for (int db = 0; db < D / 32; ++db)
-                va[a][db] = *reinterpret_cast<const u32x4_t *>(vs + v_read_off + 32 * db * V_LD + 16 * a);
-        const floatx16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb)
-            s_out[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(ka[0]), qreg[nb][0], zero, 0, 0, 0);
-#pragma unroll
-        for (int ksx = 1; ksx < D / 16; ++ksx)
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb)
-                s_out[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(ka[ksx]), qreg[nb][ksx], s_out[nb], 0, 0, 0);
-        u32x4_t pop[NB][2];
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb) {
-            float pv[16];
-#pragma unroll
-            for (int r = 0; r < 16; ++r) pv[r] = __builtin_amdgcn_exp2f(fmaf(s_in[nb][r], scale_log2, -m_ref[nb]));
-#pragma unroll
-            for (int a = 0; a < 2; ++a) {
-                pop[nb][a].x = pack2(pv[8 * a + 0], pv[8 * a + 1]);
-                pop[nb][a].y = pack2(pv[8 * a + 2], pv[8 * a + 3]);
-                pop[nb][a].z = pack2(pv[8 * a + 4], pv[8 * a + 5]);
-                pop[nb][a].w = pack2(pv[8 * a + 6], pv[8 * a + 7]);
+        for (int i = 0; i < 8; ++i) {
+            // issue order of the slice (kept by the scheduling barriers): next slice's LDS operands,
+            // then one MFMA at a time, each followed by the vector work that runs beside it
+            u32x4_t ka_n, va_n;
+            if (i < 7) {
+                ka_n = *reinterpret_cast<const u32x4_t *>(ks + 16 * (i + 1));
+                va_n = read_vt(vs, (i + 1) >> 2, (i + 1) & 3);
+            } else {
+                ka_n = *reinterpret_cast<const u32x4_t *>(ks_next);
+                va_n = read_vt(vs_next, 0, 0);
             }
-            l_run[nb] += rounded_sum(pop[nb][0]) + rounded_sum(pop[nb][1]);
-            if (WANT_LSE) {
-                float e = 0.f;
-#pragma unroll
-                for (int r = 0; r < 16; ++r) e += pv[r];
-                l_exact[nb] += e;
-            }
+            const int nbs = i >> 2, r0 = 4 * (i & 3), a = i >> 2, db = i & 3;
+            KVS_SCHED_FENCE();
+            s_out[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(ka), qreg[0][i], i == 0 ? zero : s_out[0], 0, 0, 0);
+            const float x0 = fmaf(acc_read(s_in[nbs][r0 + 0]), scale_log2, -m_ref[nbs]);
+            const float x1 = fmaf(acc_read(s_in[nbs][r0 + 1]), scale_log2, -m_ref[nbs]);
+            const float x2 = fmaf(acc_read(s_in[nbs][r0 + 2]), scale_log2, -m_ref[nbs]);
+            const float x3 = fmaf(acc_read(s_in[nbs][r0 + 3]), scale_log2, -m_ref[nbs]);
+            KVS_SCHED_FENCE();
+            s_out[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(ka), qreg[1][i], i == 0 ? zero : s_out[1], 0, 0, 0);
+            const float e0 = __builtin_amdgcn_exp2f(x0);
+            const float e1 = __builtin_amdgcn_exp2f(x1);
+            const float e2 = __builtin_amdgcn_exp2f(x2);
+            const float e3 = __builtin_amdgcn_exp2f(x3);
+            KVS_SCHED_FENCE();
+            o_acc[db][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(va), as_bf16x8(p_in[0][a]), o_acc[db][0], 0, 0, 0);
+            const uint32_t w0 = pack2(e0, e1), w1 = pack2(e2, e3);
+            p_out[nbs][r0 >> 3][(r0 & 7) >> 1] = w0;
+            p_out[nbs][r0 >> 3][((r0 & 7) >> 1) + 1] = w1;
+            l_run[nbs] = add_rounded_pair(w1, add_rounded_pair(w0, l_run[nbs]));
+            if (WANT_LSE) l_exact[nbs] += (e0 + e1) + (e2 + e3);
+            KVS_SCHED_FENCE();
+            o_acc[db][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(va), as_bf16x8(p_in[1][a]), o_acc[db][1], 0, 0, 0);
+            // staging, a piece per slice so that no burst of LDS writes or global loads holds up the
+            // MFMAs: tile jt+2 goes from `set` to LDS before the barrier, the loads of tile jt+4 refill
+            // each register right after it was written out
+            if (i == 0) store_k_piece(jt + 2, set, 0);
+            if (i == 1) { store_k_piece(jt + 2, set, 1); load_k_piece(jt + 4, set, 0); }
+            if (i == 2) { store_v_piece(jt + 2, set, 0); load_k_piece(jt + 4, set, 1); }
+            if (i == 3) store_v_piece(jt + 2, set, 1);
+            if (i == 4) load_v_piece(jt + 4, set, 0);
+            if (i == 5) load_v_piece(jt + 4, set, 1);
+            KVS_SCHED_FENCE();
+            ka = ka_n;
+            va = va_n;
+            if (i == 3) __syncthreads();
         }
-#pragma unroll
-        for (int a = 0; a < 2; ++a)
-#pragma unroll
-            for (int db = 0; db < D / 32; ++db)
-#pragma unroll
-                for (int nb = 0; nb < NB; ++nb)
-                    o_acc[db][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(va[a][db]), as_bf16x8(pop[nb][a]), o_acc[db][nb], 0, 0, 0);
-        store_tile(jt + 2, held);
-        __syncthreads();
     };
 
     // ---- passes -------------------------------------------------------------------------------------------
@@ -357,28 +424,29 @@ __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
     float l_tot[NB];
     for (int pass = 0; pass < 2; ++pass) {
         if (pass == 1) {
-            // exact row maxima: one tile at a time through stage 0
+            // exact row maxima: one tile at a time through the first ring stages
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb) m_ref[nb] = -INFINITY;
             for (int jt = 0; jt < n_kv_tiles; ++jt) {
                 Staged st;
                 load_tile(jt, st);
-                store_tile(jt, st);
+                store_tile(0, st);
                 __syncthreads();
                 floatx16 s[NB];
-                qk(jt, s);
+                qk(0, s);
                 mask_tile(jt, s);
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb) m_ref[nb] = fmaxf(m_ref[nb], row_max(s[nb]));
                 __syncthreads();
             }
         }
-        // tiles 0 and 1 into the ring, tile 2 on its way, scores of tile 0
+        // tiles 0 and 1 into the rings, tiles 2 and 3 on their way, scores of tile 0
         Staged held, next;
         load_tile(0, held);
         store_tile(0, held);
         if (n_kv_tiles > 1) { load_tile(1, held); store_tile(1, held); }
         if (n_kv_tiles > 2) load_tile(2, held);
+        if (n_kv_tiles > 3) load_tile(3, next);
         __syncthreads();
         floatx16 s_cur[NB], s_nxt[NB];
         qk(0, s_cur);
@@ -392,36 +460,55 @@ __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
 #pragma unroll
         for (int db = 0; db < D / 32; ++db)
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) o_acc[db][nb][r] = 0.f;
+            for (int nb = 0; nb < NB; ++nb) o_acc[db][nb] = zero;
 
         int jt = 0;
-        // Fast sweep, two tiles per trip so the two score buffers swap roles without copies.  It
-        // covers the tiles that need no causal compare for any row of this wave and whose look-ahead
-        // tiles lie wholly inside the context; each wave leaves it at its own point and finishes in
-        // the general loop below (both loops stage the same tile and hit one barrier per tile, so
-        // the waves of a workgroup may sit in different loops).
-        const int j_unmasked = (pmin + 1) / BN;                       // tiles 0 .. j_unmasked-1: every key <= pmin
-        const int j_lookahead = min(n_kv_tiles, ctx_len / BN);        // tiles that exist and need no row clamp
-        for (; jt + 1 < j_unmasked && jt + 4 < j_lookahead; jt += 2) {
-            fast_step(jt, s_cur, s_nxt, held, next);
-            fast_step(jt + 1, s_nxt, s_cur, next, held);
+        // Fast sweep over the tiles that need no causal compare for any row of this wave and whose
+        // look-ahead tiles lie wholly inside the context.  Each wave leaves it at its own point and
+        // finishes in the general loop below: both write the same tile into the rings at the start
+        // of the same step and hit one barrier per step, so the waves of a workgroup may sit in
+        // different loops.  Tiles past the last one may get staged here; nothing reads them.
+        const int j_unmasked = (pmin + 1) / BN;     // tiles 0 .. j_unmasked-1: every key <= pmin
+        const int j_inside = ctx_len / BN;          // tiles 0 .. j_inside-1 need no row clamp
+        if (j_unmasked >= 3 && j_inside >= 7) {
+            // step 0 has no earlier tile to multiply: scores of tile 1, softmax of tile 0
+            u32x4_t p_a[NB][2], p_b[NB][2];
+            store_tile(2, held);
+            load_tile_inside(4, held);
+            qk(1, s_nxt);
+            softmax(0, s_cur, p_a);
+            __syncthreads();
+            u32x4_t ka = *reinterpret_cast<const u32x4_t *>(k_ring + 2 * K_TILE + k_read_off);   // K of tile 2, V^T of tile 0
+            u32x4_t va = read_vt(v_ring + v_read_off, 0, 0);
+            // two steps per trip so that the score, weight and staging buffers swap roles without copies
+            for (jt = 1; jt + 1 < j_unmasked && jt + 5 < j_inside; jt += 2) {
+                fast_step(jt, s_nxt, s_cur, p_a, p_b, next, ka, va);
+                fast_step(jt + 1, s_cur, s_nxt, p_b, p_a, held, ka, va);
+            }
+            pv_product(jt - 1, p_a);
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) s_cur[nb] = s_nxt[nb];
+            const Staged t = held;   // jt is odd here: tile jt+2 sits in `next`
+            held = next;
+            next = t;
         }
-        // general loop; invariant at the top: `held` carries tile jt+2 if that tile exists
+        // general loop; invariant at the top: s_cur = scores of tile jt, `held` carries tile jt+2 and
+        // `next` tile jt+3 (where those exist)
         for (; jt < n_kv_tiles; ++jt) {
-            if (jt + 3 < n_kv_tiles) load_tile(jt + 3, next);
-            // scores of the next tile first (past the last tile the stage holds stale data and the
+            if (jt + 2 < n_kv_tiles) store_tile(jt + 2, held);
+            if (jt + 4 < n_kv_tiles) load_tile(jt + 4, held);
+            // scores of the next tile first (past the last tile the slot holds stale data and the
             // result is discarded)
             qk(jt + 1, s_nxt);
             u32x4_t pop[NB][2];
             softmax(jt, s_cur, pop);
             pv_product(jt, pop);
-            if (jt + 2 < n_kv_tiles) store_tile(jt + 2, held);
             __syncthreads();
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb) s_cur[nb] = s_nxt[nb];
+            const Staged t = held;
             held = next;
+            next = t;
         }
 
         bool bad = false;
@@ -438,6 +525,14 @@ __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
         if (redo_flag == 0) break;
     }
 
+#ifdef KVS_DIAG_CLOCK
+    if (tid == 0 && blockIdx.x < 1024) {
+        kvs_diag_clk[4 * blockIdx.x] = clock64() - diag_t0;
+        kvs_diag_clk[4 * blockIdx.x + 1] = wall_clock64() - diag_w0;
+        kvs_diag_clk[4 * blockIdx.x + 2] = n_kv_tiles;
+        kvs_diag_clk[4 * blockIdx.x + 3] = diag_w0;
+    }
+#endif
     // ---- epilogue: normalise, convert, store ----------------------------------------------------------
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
@@ -471,7 +566,7 @@ kvs_status launch_attention_mfma2(const kvs_shape *shape, const AttnBatch &bd, c
     const int64_t tiles = build_attn_tiles(shape, bd, ROWS, td);
     if (tiles < 0) return fail(KVS_EINVAL, "kvs_partial_attention: too many row tiles");
     if (tiles == 0) return KVS_OK;
-    const size_t lds_bytes = NSTAGE * STAGE * sizeof(uint16_t);
+    const size_t lds_bytes = LDS_ELEMS * sizeof(uint16_t);
     static bool attr_set = false;   // idempotent; a race only repeats the same call
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_mfma2_kernel<false>),
@@ -496,3 +591,10 @@ kvs_status launch_attention_mfma2(const kvs_shape *shape, const AttnBatch &bd, c
 }
 
 } // namespace kvs
+
+#ifdef KVS_DIAG_CLOCK
+extern "C" __attribute__((visibility("default"))) int kvs_diag_read(long long *host, int n)
+{
+    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(kvs::kvs_diag_clk), sizeof(long long) * n);
+}
+#endif
