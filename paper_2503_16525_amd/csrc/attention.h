@@ -31,11 +31,28 @@ struct AttnTiles {
 // number of row tiles, or -1 if the grid would overflow
 int64_t build_attn_tiles(const kvs_shape *shape, const AttnBatch &bd, int rows_per_tile, AttnTiles &td);
 
-// 64 query rows per wave (two MFMAs per LDS operand), one wave per SIMD: for launches with enough
-// row tiles to fill the chip
+// Key-range splitting (both matrix-core kernels): a piece stores its unnormalised fp32 accumulators
+// and (exponent reference, sum of the weights as the matrix core saw them, sum of the unrounded
+// weights, unused) per row; slot = row * n_splits + piece.
+constexpr size_t kAttnPartBytesPerSlot = 128 * sizeof(float) + 4 * sizeof(float);
+constexpr int kAttnSplitMax = 16;
+constexpr int kAttnSplitBelowWgs = 384;    // launches with fewer workgroups than this get split ...
+#ifndef KVS_ATTN_SPLIT_TARGET
+#define KVS_ATTN_SPLIT_TARGET 768
+#endif
+constexpr int kAttnSplitTargetWgs = KVS_ATTN_SPLIT_TARGET;   // ... into about this many workgroup-pieces
+// out = sum_s w_s O_s / sum_s w_s l_s with w_s = 2^(m_s - max m); pieces with l = 0 drop out;
+// the log-sum-exp comes from the unrounded sums
+kvs_status launch_attention_merge(int64_t n_rows, int n_splits, const float *part_o, const float4 *part_ml,
+                                  uint16_t *out, float *lse_out, hipStream_t st);
+
+// 64 query rows per wave (two MFMAs per LDS operand), one wave per SIMD, 256-row tiles.  n_splits > 1
+// (from attention_mfma2_splits, which needs the workspace size) cuts every row tile's key range.
+int attention_mfma2_splits(const kvs_shape *shape, const AttnBatch &bd, size_t workspace_bytes);
 kvs_status launch_attention_mfma2(const kvs_shape *shape, const AttnBatch &bd, const void *q_sel,
                                   const int32_t *sel_pos, const void *k_cache, const void *v_cache,
-                                  float scale, void *out, float *lse_out, hipStream_t st);
+                                  float scale, void *out, float *lse_out, void *workspace, int n_splits,
+                                  hipStream_t st);
 
 kvs_status launch_attention_valu(const kvs_shape *shape, const AttnBatch &bd, int64_t n_sel,
                                  const void *q_sel, const int32_t *sel_pos, const void *k_cache,

@@ -72,7 +72,7 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_mfma_kernel(
     const uint16_t *__restrict__ q_sel, const int32_t *__restrict__ sel_pos,
     const uint16_t *__restrict__ k_cache, const uint16_t *__restrict__ v_cache,
     float scale_log2, uint16_t *__restrict__ out, float *__restrict__ lse_out,
-    int n_splits, float *__restrict__ part_o, float2 *__restrict__ part_ml)
+    int n_splits, float *__restrict__ part_o, float4 *__restrict__ part_ml)
 {
     constexpr int NT = NWAVES * 64;
     constexpr int ROWS = NWAVES * 32;
@@ -322,7 +322,7 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_mfma_kernel(
                     *reinterpret_cast<float4 *>(prow + d0) = make_float4(o_acc[db][4 * r4 + 0], o_acc[db][4 * r4 + 1],
                                                                          o_acc[db][4 * r4 + 2], o_acc[db][4 * r4 + 3]);
                 }
-            if (hf == 0) part_ml[slot] = make_float2(m_run, l_tot);
+            if (hf == 0) part_ml[slot] = make_float4(m_run, l_tot, l_tot, 0.f);
         }
         return;
     }
@@ -346,36 +346,55 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_mfma_kernel(
 
 
 // combines the split pieces of every row: out = sum_s w_s O_s / sum_s w_s l_s with
-// w_s = 2^(m_s - max m); pieces that saw no key carry l = 0 and drop out
+// w_s = 2^(m_s - max m); pieces that saw no key carry l = 0 and drop out.  32 lanes per row, four
+// channels per lane, all pieces' loads issued before they are used.
 __global__ __launch_bounds__(256) void attn_merge_kernel(int64_t n_rows, int n_splits,
                                                          const float *__restrict__ part_o,
-                                                         const float2 *__restrict__ part_ml,
+                                                         const float4 *__restrict__ part_ml,
                                                          uint16_t *__restrict__ out, float *__restrict__ lse_out)
 {
-    const int64_t row = (int64_t)blockIdx.x * (256 / D) + threadIdx.x / D;
-    const int c = threadIdx.x % D;
+    const int64_t row = (int64_t)blockIdx.x * 8 + threadIdx.x / 32;
+    const int c = (threadIdx.x % 32) * 4;
     if (row >= n_rows) return;
-    const float2 *ml = part_ml + row * n_splits;
-    float m = -1.0e30f;
-    for (int s = 0; s < n_splits; ++s)
-        if (ml[s].y > 0.f) m = fmaxf(m, ml[s].x);
-    float l = 0.f, o = 0.f;
-    for (int s = 0; s < n_splits; ++s) {
-        const float2 p = ml[s];
-        if (p.y > 0.f) {
-            const float w = __builtin_amdgcn_exp2f(p.x - m);
-            l += w * p.y;
-            o += w * part_o[(row * n_splits + s) * D + c];
+    const float4 *ml = part_ml + row * n_splits;
+    const float *po = part_o + row * n_splits * D + c;
+    float4 v[kAttnSplitMax];
+    float4 p[kAttnSplitMax];
+#pragma unroll
+    for (int s = 0; s < kAttnSplitMax; ++s)
+        if (s < n_splits) {
+            p[s] = ml[s];
+            v[s] = *reinterpret_cast<const float4 *>(po + s * D);
         }
-    }
-    out[row * D + c] = (uint16_t)f32_to_bf16_bits(o / l);
-    if (lse_out && c == 0) lse_out[row] = (m + __builtin_amdgcn_logf(l)) * 0.6931471805599453f;
+    float m = -1.0e30f;
+#pragma unroll
+    for (int s = 0; s < kAttnSplitMax; ++s)
+        if (s < n_splits && p[s].y > 0.f) m = fmaxf(m, p[s].x);
+    float l = 0.f, l_exact = 0.f;
+    float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+    for (int s = 0; s < kAttnSplitMax; ++s)
+        if (s < n_splits && p[s].y > 0.f) {
+            const float w = __builtin_amdgcn_exp2f(p[s].x - m);
+            l += w * p[s].y;
+            l_exact += w * p[s].z;
+            o.x += w * v[s].x;
+            o.y += w * v[s].y;
+            o.z += w * v[s].z;
+            o.w += w * v[s].w;
+        }
+    const float inv = 1.0f / l;
+    uint2 w2;
+    w2.x = f32_to_bf16_bits(o.x * inv) | (f32_to_bf16_bits(o.y * inv) << 16);
+    w2.y = f32_to_bf16_bits(o.z * inv) | (f32_to_bf16_bits(o.w * inv) << 16);
+    *reinterpret_cast<uint2 *>(out + row * D + c) = w2;
+    if (lse_out && c == 0) lse_out[row] = (m + __builtin_amdgcn_logf(l_exact)) * 0.6931471805599453f;
 }
 
-constexpr size_t kPartBytesPerSlot = D * sizeof(float) + sizeof(float2);
+constexpr size_t kPartBytesPerSlot = kAttnPartBytesPerSlot;
 constexpr int kSplitMaxWgs = 1024;        // splits are chosen so that the grid stays near this
-constexpr int kSplitBelowWgs = 384;       // launches with fewer workgroups than this get split
-constexpr int kSplitMax = 16;
+constexpr int kSplitBelowWgs = kAttnSplitBelowWgs;
+constexpr int kSplitMax = kAttnSplitMax;
 
 template <int NWAVES>
 kvs_status launch_mfma_variant(const kvs_shape *shape, const AttnBatch &bd, const void *q_sel, const int32_t *sel_pos,
@@ -419,28 +438,35 @@ kvs_status launch_mfma_variant(const kvs_shape *shape, const AttnBatch &bd, cons
         hipLaunchKernelGGL((attn_mfma_kernel<NWAVES, false>), dim3((unsigned)wgs), dim3(NWAVES * 64), lds_bytes, st, td,
                            shape->n_q_heads, shape->n_kv_heads, (int)tiles, (const uint16_t *)q_sel, sel_pos,
                            (const uint16_t *)k_cache, (const uint16_t *)v_cache, scale_log2, (uint16_t *)out, lse_out,
-                           1, (float *)nullptr, (float2 *)nullptr);
+                           1, (float *)nullptr, (float4 *)nullptr);
         return check_launch("kvs_partial_attention(mfma)");
     }
     // pieces are indexed by the row's position in the whole call's output, so offset the tables by
     // the first row of this launch
     const int64_t row0 = bd.cu_sel[0] * shape->n_q_heads;
     float *part_o = (float *)workspace - row0 * n_splits * D;
-    float2 *part_ml = (float2 *)((char *)workspace + (size_t)n_rows_total * n_splits * D * sizeof(float)) - row0 * n_splits;
+    float4 *part_ml = (float4 *)((char *)workspace + (size_t)n_rows_total * n_splits * D * sizeof(float)) - row0 * n_splits;
     hipLaunchKernelGGL((attn_mfma_kernel<NWAVES, true>), dim3((unsigned)(wgs * n_splits)), dim3(NWAVES * 64), lds_bytes, st, td,
                        shape->n_q_heads, shape->n_kv_heads, (int)tiles, (const uint16_t *)q_sel, sel_pos,
                        (const uint16_t *)k_cache, (const uint16_t *)v_cache, scale_log2, (uint16_t *)out, lse_out,
                        n_splits, part_o, part_ml);
     kvs_status stt = check_launch("kvs_partial_attention(mfma split)");
     if (stt != KVS_OK) return stt;
-    hipLaunchKernelGGL(attn_merge_kernel, dim3((unsigned)((n_rows_total + 256 / D - 1) / (256 / D))), dim3(256), 0, st,
-                       n_rows_total, n_splits, (const float *)workspace,
-                       (const float2 *)((char *)workspace + (size_t)n_rows_total * n_splits * D * sizeof(float)),
-                       (uint16_t *)out + row0 * D, lse_out ? lse_out + row0 : nullptr);
-    return check_launch("kvs_partial_attention(merge)");
+    return launch_attention_merge(n_rows_total, n_splits, (const float *)workspace,
+                                  (const float4 *)((char *)workspace + (size_t)n_rows_total * n_splits * D * sizeof(float)),
+                                  (uint16_t *)out + row0 * D, lse_out ? lse_out + row0 : nullptr, st);
 }
 
 } // namespace
+
+kvs_status launch_attention_merge(int64_t n_rows, int n_splits, const float *part_o, const float4 *part_ml,
+                                  uint16_t *out, float *lse_out, hipStream_t st)
+{
+    if (n_rows <= 0) return KVS_OK;
+    hipLaunchKernelGGL(attn_merge_kernel, dim3((unsigned)((n_rows + 7) / 8)), dim3(256), 0, st, n_rows, n_splits,
+                       part_o, part_ml, out, lse_out);
+    return check_launch("kvs_partial_attention(merge)");
+}
 
 int64_t build_attn_tiles(const kvs_shape *shape, const AttnBatch &bd, int rows_per_tile, AttnTiles &td)
 {
@@ -483,10 +509,21 @@ kvs_status launch_attention_mfma(const kvs_shape *shape, const AttnBatch &bd, in
         return 0;
     }();
     const int grp = shape->n_q_heads / shape->n_kv_heads;
-    int64_t big_tiles = 0;
-    for (int i = 0; i < bd.n_req; ++i) big_tiles += ((bd.cu_sel[i + 1] - bd.cu_sel[i]) * grp + 255) / 256;
-    const bool big = forced ? forced == 2 : big_tiles * shape->n_kv_heads >= kAttnBigTileMinGrid;
-    if (big) return launch_attention_mfma2(shape, bd, q_sel, sel_pos, k_cache, v_cache, scale, out, lse_out, st);
+    int64_t big_tiles = 0, rows = 0;
+    for (int i = 0; i < bd.n_req; ++i) {
+        big_tiles += ((bd.cu_sel[i + 1] - bd.cu_sel[i]) * grp + 255) / 256;
+        rows += (bd.cu_sel[i + 1] - bd.cu_sel[i]) * grp;
+    }
+    // with fewer 256-row tiles than compute units the large kernel still wins if the caller's
+    // workspace lets it cut the key ranges and its tiles are not mostly padding
+    const int splits2 = workspace ? attention_mfma2_splits(shape, bd, workspace_bytes) : 1;
+    const bool fills = big_tiles * shape->n_kv_heads >= kAttnBigTileMinGrid;
+    const bool dense_tiles = rows * 10 >= big_tiles * 256 * 6;
+    // (below ~160 such tiles the per-workgroup start-up of the large kernel costs more than it gains)
+    const bool big = forced ? forced == 2 : fills || (splits2 >= 2 && dense_tiles && big_tiles * shape->n_kv_heads >= 160);
+    if (big)
+        return launch_attention_mfma2(shape, bd, q_sel, sel_pos, k_cache, v_cache, scale, out, lse_out, workspace,
+                                      fills && !forced ? 1 : splits2, st);
     return launch_mfma_variant<KVS_ATTN_NWAVES>(shape, bd, q_sel, sel_pos, k_cache, v_cache, scale, out, lse_out,
                                                 workspace, workspace_bytes, st);
 }
@@ -497,8 +534,8 @@ size_t attention_workspace_bytes(const kvs_shape *shape, int32_t batch, int64_t 
     // kSplitMaxWgs workgroup-pieces of 32*KVS_ATTN_NWAVES rows each exist
     const int64_t rows = n_sel_total * shape->n_q_heads;
     int64_t slots = rows * kSplitMax;
-    const int64_t cap = (int64_t)(kSplitMaxWgs + kSplitBelowWgs) * 32 * KVS_ATTN_NWAVES / shape->n_kv_heads * shape->n_kv_heads
-                        + (int64_t)batch * 32 * KVS_ATTN_NWAVES * kSplitMax;
+    // (the 256-row kernel: at most kAttnSplitTargetWgs + kAttnSplitBelowWgs pieces of 256 rows)
+    const int64_t cap = (int64_t)(kSplitMaxWgs + kSplitBelowWgs) * 256 + (int64_t)batch * 256 * kSplitMax;
     if (slots > cap) slots = cap;
     return (size_t)slots * kPartBytesPerSlot + 256;
 }

@@ -38,6 +38,7 @@
 #include "attention.h"
 
 #include <math.h>
+#include <type_traits>
 
 namespace kvs {
 namespace {
@@ -99,23 +100,23 @@ __device__ __forceinline__ float add_rounded_pair(uint32_t w, float acc)   // ac
     typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
     return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w), __builtin_bit_cast(bf16x2, 0x3f803f80u), acc, false);
 }
-__device__ __forceinline__ float add_rounded(const u32x4_t w, float acc)
-{
-    return add_rounded_pair(w.w, add_rounded_pair(w.z, add_rounded_pair(w.y, add_rounded_pair(w.x, acc))));
-}
-
 #ifdef KVS_DIAG_CLOCK
 __device__ long long kvs_diag_clk[4096];
 #endif
 
 
-// WANT_LSE: additionally keep the unrounded sum of weights, from which the log-sum-exp is reported
-template <bool WANT_LSE>
+// WANT_LSE: additionally keep the unrounded sum of weights, from which the log-sum-exp is reported.
+// SPLIT: the key range of a row tile is cut into n_splits contiguous pieces handled by different
+// workgroups (launches with few row tiles over long contexts would otherwise leave most of the chip
+// idle); every piece writes its unnormalised accumulators and (reference, sum) to the workspace and
+// the merge kernel combines them.
+template <bool WANT_LSE, bool SPLIT>
 __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
     const AttnTiles td, int n_q_heads, int n_kv_heads, int total_tiles,
     const uint16_t *__restrict__ q_sel, const int32_t *__restrict__ sel_pos,
     const uint16_t *__restrict__ k_cache, const uint16_t *__restrict__ v_cache,
-    float scale_log2, uint16_t *__restrict__ out, float *__restrict__ lse_out)
+    float scale_log2, uint16_t *__restrict__ out, float *__restrict__ lse_out,
+    int n_splits, float *__restrict__ part_o, float4 *__restrict__ part_ml)
 {
     extern __shared__ __attribute__((aligned(16))) uint16_t lds[];   // K ring, then V^T ring
     __shared__ int wg_max_pos[NWAVES];
@@ -128,7 +129,9 @@ __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
 
     // ---- which (request, kv head, row tile) -----------------------------------------------------
     const int g = blockIdx.x % n_kv_heads;
-    const int tile_lin = total_tiles - 1 - (int)(blockIdx.x / n_kv_heads);
+    const int rest = (int)(blockIdx.x / n_kv_heads);
+    const int split = SPLIT ? rest % n_splits : 0;
+    const int tile_lin = total_tiles - 1 - (SPLIT ? rest / n_splits : rest);
     int b = 0;
     while (b + 1 < td.n_req && tile_lin >= td.tile_begin[b + 1]) ++b;
     const int tile = tile_lin - td.tile_begin[b];
@@ -184,6 +187,10 @@ __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
 #pragma unroll
     for (int w = 1; w < NWAVES; ++w) wg_pmax = max(wg_pmax, wg_max_pos[w]);
     const int n_kv_tiles = wg_pmax / BN + 1;
+    // this workgroup's share of the key tiles: [t_lo, t_hi)
+    const int t_chunk = SPLIT ? (n_kv_tiles + n_splits - 1) / n_splits : n_kv_tiles;
+    const int t_lo = SPLIT ? min(n_kv_tiles, split * t_chunk) : 0;
+    const int t_hi = SPLIT ? min(n_kv_tiles, t_lo + t_chunk) : n_kv_tiles;
 
     // ---- global -> register -> LDS staging of one K/V tile ------------------------------------------
     // Buffer loads: the tile's position goes into the scalar offset, the per-lane part is constant.
@@ -197,7 +204,6 @@ __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
         const_cast<uint16_t *>(v_cache + (ctx_off * n_kv_heads + g) * (int64_t)D), 0, head_bytes, 0x00020000);
     struct Staged { u32x4_t k[K_PIECES], v[K_PIECES]; };   // one tile on its way from HBM to LDS
     const uint32_t k_lane_off = (uint32_t)(tid >> 4) * row_bytes + (uint32_t)(tid & 15) * 16u;
-    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
 
     // tile jt wholly inside the context
     auto load_tile_inside = [&](int jt, Staged &st) {
@@ -346,8 +352,8 @@ __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
             }
     };
 
-    // One step of the fast sweep (tile jt needs no causal compare for this wave and tile jt+4 lies
-    // wholly inside the context): scores of tile jt+1, softmax of tile jt, PV of tile jt-1, written
+    // One step of the pipelined sweep (tile jt+4 lies wholly inside the context; `masked` says whether
+    // tile jt needs the causal compare for this wave): scores of tile jt+1, softmax of tile jt, PV of tile jt-1, written
     // as eight slices of four MFMAs and four scores each, LDS operands fetched one slice ahead
     // (ka / va enter with slice 0's operands and leave with those of the next step).
     // On entry tiles jt-1 .. jt+1 are in the LDS rings, `set` carries tile jt+2, s_in the scores of
@@ -356,9 +362,13 @@ __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
     // in step j-2 or earlier (K of tile j-2 in step j-3, V^T of tile j-6 in step j-5 at the latest),
     // and every wave passed the barrier of step j-1 after that read and before this write; tile j+2
     // is first read in step j+1, after this step's barrier.
-    auto fast_step = [&](int jt, const floatx16 (&s_in)[NB], floatx16 (&s_out)[NB],
+    int key_lim[NB];   // a key of the tile is visible to the lane's query nb iff its (half-wave-relative) index <= this
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) key_lim[nb] = pos[nb] - 8 * hf;
+    auto fast_step = [&](auto masked, int jt, const floatx16 (&s_in)[NB], floatx16 (&s_out)[NB],
                          const u32x4_t (&p_in)[NB][2], u32x4_t (&p_out)[NB][2], Staged &set,
                          u32x4_t &ka, u32x4_t &va) {
+        constexpr bool MASKED = decltype(masked)::value;
         const uint16_t *ks = k_ring + ((jt + 1) & (K_RING - 1)) * K_TILE + k_read_off;
         const uint16_t *vs = v_ring + ((jt - 1) & (V_RING - 1)) * V_TILE + v_read_off;
         const uint16_t *ks_next = k_ring + ((jt + 2) & (K_RING - 1)) * K_TILE + k_read_off;
@@ -378,10 +388,17 @@ __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
             const int nbs = i >> 2, r0 = 4 * (i & 3), a = i >> 2, db = i & 3;
             KVS_SCHED_FENCE();
             s_out[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(ka), qreg[0][i], i == 0 ? zero : s_out[0], 0, 0, 0);
-            const float x0 = fmaf(acc_read(s_in[nbs][r0 + 0]), scale_log2, -m_ref[nbs]);
-            const float x1 = fmaf(acc_read(s_in[nbs][r0 + 1]), scale_log2, -m_ref[nbs]);
-            const float x2 = fmaf(acc_read(s_in[nbs][r0 + 2]), scale_log2, -m_ref[nbs]);
-            const float x3 = fmaf(acc_read(s_in[nbs][r0 + 3]), scale_log2, -m_ref[nbs]);
+            float x0 = fmaf(acc_read(s_in[nbs][r0 + 0]), scale_log2, -m_ref[nbs]);
+            float x1 = fmaf(acc_read(s_in[nbs][r0 + 1]), scale_log2, -m_ref[nbs]);
+            float x2 = fmaf(acc_read(s_in[nbs][r0 + 2]), scale_log2, -m_ref[nbs]);
+            float x3 = fmaf(acc_read(s_in[nbs][r0 + 3]), scale_log2, -m_ref[nbs]);
+            if (MASKED) {   // entry r of the lane is key jt*BN + 16*(r>>3) + 8*hf + (r&7)
+                const int k0 = jt * BN + 16 * (r0 >> 3) + (r0 & 7);
+                x0 = k0 + 0 > key_lim[nbs] ? -INFINITY : x0;
+                x1 = k0 + 1 > key_lim[nbs] ? -INFINITY : x1;
+                x2 = k0 + 2 > key_lim[nbs] ? -INFINITY : x2;
+                x3 = k0 + 3 > key_lim[nbs] ? -INFINITY : x3;
+            }
             KVS_SCHED_FENCE();
             s_out[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(ka), qreg[1][i], i == 0 ? zero : s_out[1], 0, 0, 0);
             const float e0 = __builtin_amdgcn_exp2f(x0);
@@ -427,7 +444,7 @@ __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
             // exact row maxima: one tile at a time through the first ring stages
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb) m_ref[nb] = -INFINITY;
-            for (int jt = 0; jt < n_kv_tiles; ++jt) {
+            for (int jt = t_lo; jt < t_hi; ++jt) {
                 Staged st;
                 load_tile(jt, st);
                 store_tile(0, st);
@@ -440,20 +457,21 @@ __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
                 __syncthreads();
             }
         }
-        // tiles 0 and 1 into the rings, tiles 2 and 3 on their way, scores of tile 0
+        // the first two tiles into the rings, the next two on their way, scores of the first tile
         Staged held, next;
-        load_tile(0, held);
-        store_tile(0, held);
-        if (n_kv_tiles > 1) { load_tile(1, held); store_tile(1, held); }
-        if (n_kv_tiles > 2) load_tile(2, held);
-        if (n_kv_tiles > 3) load_tile(3, next);
+        if (t_lo < t_hi) { load_tile(t_lo, held); store_tile(t_lo, held); }
+        if (t_lo + 1 < t_hi) { load_tile(t_lo + 1, held); store_tile(t_lo + 1, held); }
+        if (t_lo + 2 < t_hi) load_tile(t_lo + 2, held);
+        if (t_lo + 3 < t_hi) load_tile(t_lo + 3, next);
         __syncthreads();
         floatx16 s_cur[NB], s_nxt[NB];
-        qk(0, s_cur);
+        qk(t_lo, s_cur);
         if (pass == 0) {
-            mask_tile(0, s_cur);
+            mask_tile(t_lo, s_cur);
+            // a row whose keys all lie before this piece sees nothing here: a finite reference keeps
+            // its weights at exp2(-inf) = 0 instead of NaN (the merge drops pieces with zero sum)
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb) m_ref[nb] = row_max(s_cur[nb]);
+            for (int nb = 0; nb < NB; ++nb) m_ref[nb] = fmaxf(row_max(s_cur[nb]), -1.0e30f);
         }
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) { l_run[nb] = 0.f; l_exact[nb] = 0.f; }
@@ -462,7 +480,7 @@ __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb) o_acc[db][nb] = zero;
 
-        int jt = 0;
+        int jt = t_lo;
         // Fast sweep over the tiles that need no causal compare for any row of this wave and whose
         // look-ahead tiles lie wholly inside the context.  Each wave leaves it at its own point and
         // finishes in the general loop below: both write the same tile into the rings at the start
@@ -470,33 +488,39 @@ __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
         // different loops.  Tiles past the last one may get staged here; nothing reads them.
         const int j_unmasked = (pmin + 1) / BN;     // tiles 0 .. j_unmasked-1: every key <= pmin
         const int j_inside = ctx_len / BN;          // tiles 0 .. j_inside-1 need no row clamp
-        if (j_unmasked >= 3 && j_inside >= 7) {
-            // step 0 has no earlier tile to multiply: scores of tile 1, softmax of tile 0
+        if (t_lo + 3 <= min(j_unmasked, t_hi) && t_lo + 7 <= j_inside) {
+            // the first step has no earlier tile to multiply: scores of the second tile, softmax of the first
             u32x4_t p_a[NB][2], p_b[NB][2];
-            store_tile(2, held);
-            load_tile_inside(4, held);
-            qk(1, s_nxt);
-            softmax(0, s_cur, p_a);
+            store_tile(t_lo + 2, held);
+            load_tile_inside(t_lo + 4, held);
+            qk(t_lo + 1, s_nxt);
+            softmax(t_lo, s_cur, p_a);
             __syncthreads();
-            u32x4_t ka = *reinterpret_cast<const u32x4_t *>(k_ring + 2 * K_TILE + k_read_off);   // K of tile 2, V^T of tile 0
-            u32x4_t va = read_vt(v_ring + v_read_off, 0, 0);
+            // K of the third tile, V of the first
+            u32x4_t ka = *reinterpret_cast<const u32x4_t *>(k_ring + ((t_lo + 2) & (K_RING - 1)) * K_TILE + k_read_off);
+            u32x4_t va = read_vt(v_ring + (t_lo & (V_RING - 1)) * V_TILE + v_read_off, 0, 0);
             // two steps per trip so that the score, weight and staging buffers swap roles without copies
-            for (jt = 1; jt + 1 < j_unmasked && jt + 5 < j_inside; jt += 2) {
-                fast_step(jt, s_nxt, s_cur, p_a, p_b, next, ka, va);
-                fast_step(jt + 1, s_cur, s_nxt, p_b, p_a, held, ka, va);
+            for (jt = t_lo + 1; jt + 1 < min(j_unmasked, t_hi) && jt + 5 < j_inside; jt += 2) {
+                fast_step(std::false_type{}, jt, s_nxt, s_cur, p_a, p_b, next, ka, va);
+                fast_step(std::false_type{}, jt + 1, s_cur, s_nxt, p_b, p_a, held, ka, va);
+            }
+            // the tiles around the wave's own positions, same pipeline with the causal compare
+            for (; jt + 1 < t_hi && jt + 5 < j_inside; jt += 2) {
+                fast_step(std::true_type{}, jt, s_nxt, s_cur, p_a, p_b, next, ka, va);
+                fast_step(std::true_type{}, jt + 1, s_cur, s_nxt, p_b, p_a, held, ka, va);
             }
             pv_product(jt - 1, p_a);
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb) s_cur[nb] = s_nxt[nb];
-            const Staged t = held;   // jt is odd here: tile jt+2 sits in `next`
+            const Staged t = held;   // an odd number of steps so far: tile jt+2 sits in `next`
             held = next;
             next = t;
         }
         // general loop; invariant at the top: s_cur = scores of tile jt, `held` carries tile jt+2 and
         // `next` tile jt+3 (where those exist)
-        for (; jt < n_kv_tiles; ++jt) {
-            if (jt + 2 < n_kv_tiles) store_tile(jt + 2, held);
-            if (jt + 4 < n_kv_tiles) load_tile(jt + 4, held);
+        for (; jt < t_hi; ++jt) {
+            if (jt + 2 < t_hi) store_tile(jt + 2, held);
+            if (jt + 4 < t_hi) load_tile(jt + 4, held);
             // scores of the next tile first (past the last tile the slot holds stale data and the
             // result is discarded)
             qk(jt + 1, s_nxt);
@@ -538,6 +562,22 @@ __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
     for (int nb = 0; nb < NB; ++nb) {
         const float inv = 1.0f / l_tot[nb];
         const float l_exact_tot = WANT_LSE ? l_exact[nb] + __shfl_xor(l_exact[nb], 32) : 0.f;
+        if (SPLIT) {
+            if (row_ok[nb]) {
+                const int64_t slot = row_idx[nb] * (int64_t)n_splits + split;
+                float *prow = part_o + slot * D;
+#pragma unroll
+                for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+                    for (int r4 = 0; r4 < 4; ++r4) {
+                        const int d0 = 32 * db + 8 * r4 + 4 * hf;
+                        *reinterpret_cast<float4 *>(prow + d0) = make_float4(o_acc[db][nb][4 * r4 + 0], o_acc[db][nb][4 * r4 + 1],
+                                                                             o_acc[db][nb][4 * r4 + 2], o_acc[db][nb][4 * r4 + 3]);
+                    }
+                if (hf == 0) part_ml[slot] = make_float4(m_ref[nb], l_tot[nb], WANT_LSE ? l_exact_tot : l_tot[nb], 0.f);
+            }
+            continue;
+        }
         if (row_ok[nb]) {
             uint16_t *orow = out + row_idx[nb] * D;
 #pragma unroll
@@ -558,36 +598,80 @@ __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
 
 } // namespace
 
+namespace {
+template <bool WANT_LSE, bool SPLIT>
+kvs_status launch_one(const dim3 grid, size_t lds_bytes, hipStream_t st, const AttnTiles &td, const kvs_shape *shape,
+                      int tiles, const void *q_sel, const int32_t *sel_pos, const void *k_cache, const void *v_cache,
+                      float scale_log2, void *out, float *lse_out, int n_splits, float *part_o, float4 *part_ml)
+{
+    static bool attr_set = false;   // idempotent; a race only repeats the same call
+    if (!attr_set) {
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_mfma2_kernel<WANT_LSE, SPLIT>),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+        if (e != hipSuccess) return fail(KVS_EHIP, "kvs_partial_attention: hipFuncSetAttribute: %s", hipGetErrorString(e));
+        attr_set = true;
+    }
+    hipLaunchKernelGGL((attn_mfma2_kernel<WANT_LSE, SPLIT>), grid, dim3(NT), lds_bytes, st, td, shape->n_q_heads,
+                       shape->n_kv_heads, tiles, (const uint16_t *)q_sel, sel_pos, (const uint16_t *)k_cache,
+                       (const uint16_t *)v_cache, scale_log2, (uint16_t *)out, lse_out, n_splits, part_o, part_ml);
+    return check_launch("kvs_partial_attention(mfma2)");
+}
+} // namespace
+
+int attention_mfma2_splits(const kvs_shape *shape, const AttnBatch &bd, size_t workspace_bytes)
+{
+    const int grp = shape->n_q_heads / shape->n_kv_heads;
+    int64_t tiles = 0, max_ctx = 0;
+    for (int i = 0; i < bd.n_req; ++i) {
+        tiles += ((bd.cu_sel[i + 1] - bd.cu_sel[i]) * grp + ROWS - 1) / ROWS;
+        max_ctx = bd.ctx_len[i] > max_ctx ? bd.ctx_len[i] : max_ctx;
+    }
+    const int64_t wgs = tiles * shape->n_kv_heads;
+    if (wgs <= 0 || wgs >= kAttnSplitBelowWgs) return 1;
+    int64_t s = (kAttnSplitTargetWgs + wgs - 1) / wgs;
+    if (s > kAttnSplitMax) s = kAttnSplitMax;
+    const int64_t by_len = max_ctx / (16 * BN);                      // at least 16 key tiles per piece
+    if (s > by_len) s = by_len;
+    const int64_t n_rows_total = (bd.cu_sel[bd.n_req] - bd.cu_sel[0]) * shape->n_q_heads;
+    const int64_t by_ws = (int64_t)(workspace_bytes / (kAttnPartBytesPerSlot * (size_t)(n_rows_total > 0 ? n_rows_total : 1)));
+    if (s > by_ws) s = by_ws;
+    return s >= 2 ? (int)s : 1;
+}
+
 kvs_status launch_attention_mfma2(const kvs_shape *shape, const AttnBatch &bd, const void *q_sel,
                                   const int32_t *sel_pos, const void *k_cache, const void *v_cache,
-                                  float scale, void *out, float *lse_out, hipStream_t st)
+                                  float scale, void *out, float *lse_out, void *workspace, int n_splits,
+                                  hipStream_t st)
 {
     AttnTiles td;
     const int64_t tiles = build_attn_tiles(shape, bd, ROWS, td);
     if (tiles < 0) return fail(KVS_EINVAL, "kvs_partial_attention: too many row tiles");
     if (tiles == 0) return KVS_OK;
     const size_t lds_bytes = LDS_ELEMS * sizeof(uint16_t);
-    static bool attr_set = false;   // idempotent; a race only repeats the same call
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_mfma2_kernel<false>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_mfma2_kernel<true>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
-        if (e != hipSuccess) return fail(KVS_EHIP, "kvs_partial_attention: hipFuncSetAttribute: %s", hipGetErrorString(e));
-        attr_set = true;
-    }
     const float scale_log2 = scale * 1.4426950408889634f;
-    const dim3 grid((unsigned)(tiles * shape->n_kv_heads)), block(NT);
-    if (lse_out)
-        hipLaunchKernelGGL(attn_mfma2_kernel<true>, grid, block, lds_bytes, st, td, shape->n_q_heads, shape->n_kv_heads,
-                           (int)tiles, (const uint16_t *)q_sel, sel_pos, (const uint16_t *)k_cache,
-                           (const uint16_t *)v_cache, scale_log2, (uint16_t *)out, lse_out);
-    else
-        hipLaunchKernelGGL(attn_mfma2_kernel<false>, grid, block, lds_bytes, st, td, shape->n_q_heads, shape->n_kv_heads,
-                           (int)tiles, (const uint16_t *)q_sel, sel_pos, (const uint16_t *)k_cache,
-                           (const uint16_t *)v_cache, scale_log2, (uint16_t *)out, lse_out);
-    return check_launch("kvs_partial_attention(mfma2)");
+    if (n_splits <= 1 || !workspace) {
+        const dim3 grid((unsigned)(tiles * shape->n_kv_heads));
+        return lse_out ? launch_one<true, false>(grid, lds_bytes, st, td, shape, (int)tiles, q_sel, sel_pos, k_cache, v_cache,
+                                                 scale_log2, out, lse_out, 1, nullptr, nullptr)
+                       : launch_one<false, false>(grid, lds_bytes, st, td, shape, (int)tiles, q_sel, sel_pos, k_cache, v_cache,
+                                                  scale_log2, out, lse_out, 1, nullptr, nullptr);
+    }
+    // pieces are indexed by the row's position in the whole call's output, so offset the tables by
+    // the first row of this launch
+    const int64_t n_rows_total = (bd.cu_sel[bd.n_req] - bd.cu_sel[0]) * shape->n_q_heads;
+    const int64_t row0 = bd.cu_sel[0] * shape->n_q_heads;
+    float *part_o = (float *)workspace - row0 * n_splits * D;
+    float4 *ml_base = (float4 *)((char *)workspace + (size_t)n_rows_total * n_splits * D * sizeof(float));
+    float4 *part_ml = ml_base - row0 * n_splits;
+    const dim3 grid((unsigned)(tiles * shape->n_kv_heads * n_splits));
+    const kvs_status stt =
+        lse_out ? launch_one<true, true>(grid, lds_bytes, st, td, shape, (int)tiles, q_sel, sel_pos, k_cache, v_cache,
+                                         scale_log2, out, lse_out, n_splits, part_o, part_ml)
+                : launch_one<false, true>(grid, lds_bytes, st, td, shape, (int)tiles, q_sel, sel_pos, k_cache, v_cache,
+                                          scale_log2, out, lse_out, n_splits, part_o, part_ml);
+    if (stt != KVS_OK) return stt;
+    return launch_attention_merge(n_rows_total, n_splits, (const float *)workspace, ml_base,
+                                  (uint16_t *)out + row0 * D, lse_out ? lse_out + row0 : nullptr, st);
 }
 
 } // namespace kvs
