@@ -3,35 +3,32 @@
 //
 // Why this shape.  Feeding every v_mfma_f32_32x32x16_bf16 with a fresh 16-byte-per-lane operand
 // from LDS saturates the LDS read pipe (measured: the MFMA rate drops to ~75 % with nothing else
-// going on).  Here each K row block / V^T row block read from LDS is used by two MFMAs (two
-// blocks of 32 queries), which halves the LDS traffic per flop.  Two query blocks per wave need
-// the whole register file (output accumulators 128, Q operands 64, two score tiles 64, ...), so
-// one wave per SIMD is resident and the overlap of matrix and vector work has to come from within
-// the wave: the score product of tile j+1 is issued before the softmax of tile j, whose vector
-// instructions then run in the shadow of those MFMAs; the PV product of tile j follows.  The
-// softmax uses a per-row exponent reference that is fixed for the whole sweep (taken from the
-// row's first tile, with an exact-maximum fallback sweep if that ever overflows), so the output
-// accumulators are only ever touched by MFMAs and stay in the accumulation registers.
+// going on).  Here each K / V operand read from LDS is used by two MFMAs (two blocks of 32
+// queries), which halves the LDS traffic per flop.  Two query blocks per wave need the whole
+// register file (output accumulators 128, Q operands 64, two score tiles 64, ...), so one wave per
+// SIMD is resident and the overlap of matrix, vector and memory work has to come from within the
+// wave.  The softmax uses a per-row exponent reference that is fixed for the whole sweep (taken
+// from the row's first tile, with an exact-maximum fallback sweep if that ever overflows), so the
+// output accumulators are only ever touched by MFMAs and stay in the accumulation registers.
 //
-// Everything else follows the 32-rows-per-wave kernel: rows are flattened (selected token,
-// head-in-group), transposed products S^T = K Q^T and O^T += V^T P^T so that P stays in registers
-// as the B operand, K rows fed in a bit-swapped order so that a lane's 8 P values per k-step are 8
-// consecutive keys, V transposed on its way into LDS, exp2 with the scale folded in, causal compare
-// only on tiles that can straddle a row position of the wave, heaviest row tiles first, KV head =
-// blockIdx % n_kv_heads.
+// As in the 32-rows-per-wave kernel, rows are flattened (selected token, head-in-group), the
+// products are transposed (S^T = K Q^T, O^T += V^T P^T) so that P stays in registers as the B
+// operand, K rows are fed in a bit-swapped order so that a lane's 8 P values per k-step are 8
+// consecutive keys, exp2 carries the scale, the heaviest row tiles come first and the KV head is
+// blockIdx % n_kv_heads.  Unlike there, V stays row-major in LDS and the V^T operand is produced
+// by the transposing LDS read, so K and V are staged by the same plain 16-byte copies.
 //
-// Software pipeline (fast sweep).  Step j issues, for one wave, three independent strands:
+// Software pipeline.  Step j issues, for one wave, three independent strands:
 //   * the score MFMAs of tile j+1        (K tile j+1 from LDS, Q from registers),
-//   * the PV MFMAs of tile j-1           (V^T tile j-1 from LDS, P of tile j-1 from registers),
+//   * the PV MFMAs of tile j-1           (V tile j-1 from LDS, P of tile j-1 from registers),
 //   * the softmax of tile j              (vector instructions only),
-// so every MFMA of the step has vector work to run beside it; the source interleaves them in the
-// ratio the hardware sustains (an MFMA holds the issue port for roughly half of its 32 cycles, the
-// other half takes about four vector instructions) and scheduling barriers keep that order.
+// so every MFMA of the step has vector work that can run beside it, and the staging of tile j+2
+// (registers -> LDS) and tile j+4 (global -> registers) is spread over the step one instruction at
+// a time: a burst of LDS writes or global loads holds up the MFMAs behind it.  Tiles that need the
+// causal compare go through the same pipeline with two more vector instructions per score.
 //
-// LDS: K ring of four tiles, V^T ring of eight.  Step j first writes tile j+2 (loaded two steps
-// earlier) into the rings and sends out the global loads of tile j+4, then reads K of tile j+1 and
-// V^T of tile j-1 (the general loop: V^T of tile j).  One barrier per step, placed in the middle of
-// the step: the rings are deep enough that a slot is rewritten only two barriers after its last
+// LDS: K ring of four tiles, V ring of eight.  One barrier per step, placed in the middle of the
+// step: the rings are deep enough that a slot is rewritten only two barriers after its last
 // reader, so no wave ever waits at a step boundary and the LDS operands of a step's first MFMAs are
 // fetched at the end of the step before.  Global loads use buffer instructions with scalar tile
 // offsets, so the loop carries no per-lane address arithmetic.
@@ -61,15 +58,6 @@ constexpr int K_RING = 4;   // >= 3, see the barrier argument at fast_step
 constexpr int V_RING = 8;   // >= 5
 constexpr int LDS_ELEMS = K_RING * K_TILE + V_RING * V_TILE;
 constexpr int K_PIECES = BN * (D / 8) / NT;   // 2
-#ifndef KVS_ATTN_PIN_SCHEDULE
-#define KVS_ATTN_PIN_SCHEDULE 1
-#endif
-#if KVS_ATTN_PIN_SCHEDULE
-#define KVS_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)   // nothing is scheduled across this point
-#else
-#define KVS_SCHED_FENCE() do {} while (0)
-#endif
-
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4_t v) { return __builtin_bit_cast(bf16x8, v); }
 
 __device__ __forceinline__ uint32_t pack2(float lo, float hi)
@@ -85,16 +73,6 @@ __device__ __forceinline__ uint32_t pack2(float lo, float hi)
 // and denominator then carry the same rounding, so a row dominated by a single key still returns
 // that key's V exactly (with a fixed exponent reference the dominant weight is not 1.0 and its
 // bf16 rounding error, up to 2^-9, would otherwise pass straight into the output).
-// One accumulation register into a vector register, at this point of the program.  The scores of a
-// tile are produced by MFMAs into accumulation registers and consumed a step later by the softmax;
-// left to itself the compiler copies all of them out right behind the last MFMA, which stalls on
-// that MFMA.  The caller keeps at least 11 instructions between the MFMA and this read.
-__device__ __forceinline__ float acc_read(float acc)
-{
-    float v;
-    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(v) : "a"(acc));
-    return v;
-}
 __device__ __forceinline__ float add_rounded_pair(uint32_t w, float acc)   // acc + lo(w) + hi(w), one instruction
 {
     typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
@@ -375,8 +353,10 @@ __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
         const uint16_t *vs_next = v_ring + (jt & (V_RING - 1)) * V_TILE + v_read_off;
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            // issue order of the slice (kept by the scheduling barriers): next slice's LDS operands,
-            // then one MFMA at a time, each followed by the vector work that runs beside it
+            // source order of the slice: next slice's LDS operands, then one MFMA at a time, each
+            // followed by vector work that can run beside it.  The compiler's scheduler is left free
+            // to reorder within the step: pinning this order with scheduling barriers measured 4-6 %
+            // slower than its own choice.
             u32x4_t ka_n, va_n;
             if (i < 7) {
                 ka_n = *reinterpret_cast<const u32x4_t *>(ks + 16 * (i + 1));
@@ -386,12 +366,11 @@ __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
                 va_n = read_vt(vs_next, 0, 0);
             }
             const int nbs = i >> 2, r0 = 4 * (i & 3), a = i >> 2, db = i & 3;
-            KVS_SCHED_FENCE();
             s_out[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(ka), qreg[0][i], i == 0 ? zero : s_out[0], 0, 0, 0);
-            float x0 = fmaf(acc_read(s_in[nbs][r0 + 0]), scale_log2, -m_ref[nbs]);
-            float x1 = fmaf(acc_read(s_in[nbs][r0 + 1]), scale_log2, -m_ref[nbs]);
-            float x2 = fmaf(acc_read(s_in[nbs][r0 + 2]), scale_log2, -m_ref[nbs]);
-            float x3 = fmaf(acc_read(s_in[nbs][r0 + 3]), scale_log2, -m_ref[nbs]);
+            float x0 = fmaf(s_in[nbs][r0 + 0], scale_log2, -m_ref[nbs]);
+            float x1 = fmaf(s_in[nbs][r0 + 1], scale_log2, -m_ref[nbs]);
+            float x2 = fmaf(s_in[nbs][r0 + 2], scale_log2, -m_ref[nbs]);
+            float x3 = fmaf(s_in[nbs][r0 + 3], scale_log2, -m_ref[nbs]);
             if (MASKED) {   // entry r of the lane is key jt*BN + 16*(r>>3) + 8*hf + (r&7)
                 const int k0 = jt * BN + 16 * (r0 >> 3) + (r0 & 7);
                 x0 = k0 + 0 > key_lim[nbs] ? -INFINITY : x0;
@@ -399,20 +378,17 @@ __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
                 x2 = k0 + 2 > key_lim[nbs] ? -INFINITY : x2;
                 x3 = k0 + 3 > key_lim[nbs] ? -INFINITY : x3;
             }
-            KVS_SCHED_FENCE();
             s_out[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(ka), qreg[1][i], i == 0 ? zero : s_out[1], 0, 0, 0);
             const float e0 = __builtin_amdgcn_exp2f(x0);
             const float e1 = __builtin_amdgcn_exp2f(x1);
             const float e2 = __builtin_amdgcn_exp2f(x2);
             const float e3 = __builtin_amdgcn_exp2f(x3);
-            KVS_SCHED_FENCE();
             o_acc[db][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(va), as_bf16x8(p_in[0][a]), o_acc[db][0], 0, 0, 0);
             const uint32_t w0 = pack2(e0, e1), w1 = pack2(e2, e3);
             p_out[nbs][r0 >> 3][(r0 & 7) >> 1] = w0;
             p_out[nbs][r0 >> 3][((r0 & 7) >> 1) + 1] = w1;
             l_run[nbs] = add_rounded_pair(w1, add_rounded_pair(w0, l_run[nbs]));
             if (WANT_LSE) l_exact[nbs] += (e0 + e1) + (e2 + e3);
-            KVS_SCHED_FENCE();
             o_acc[db][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(va), as_bf16x8(p_in[1][a]), o_acc[db][1], 0, 0, 0);
             // staging, a piece per slice so that no burst of LDS writes or global loads holds up the
             // MFMAs: tile jt+2 goes from `set` to LDS before the barrier, the loads of tile jt+4 refill
@@ -423,7 +399,6 @@ __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
             if (i == 3) store_v_piece(jt + 2, set, 1);
             if (i == 4) load_v_piece(jt + 4, set, 0);
             if (i == 5) load_v_piece(jt + 4, set, 1);
-            KVS_SCHED_FENCE();
             ka = ka_n;
             va = va_n;
             if (i == 3) __syncthreads();
