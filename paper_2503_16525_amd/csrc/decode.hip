@@ -195,33 +195,44 @@ __global__ __launch_bounds__(kThreads) void decode_stats_kernel(
 }
 
 // ---- 3. scores ---------------------------------------------------------------------------------
+// One workgroup per kTok-token tile: lane = token, wave w takes KV heads w, w+4, ...; the waves'
+// partial sums are added in a fixed order.
 __global__ __launch_bounds__(kThreads) void decode_score_kernel(
     const DecodeBatch bd, int n_q_heads, int n_kv_heads, int64_t n_rows,
     const float *__restrict__ logits, const float2 *__restrict__ stats,
     const float *__restrict__ dev_v, const uint8_t *__restrict__ reused, float *__restrict__ score)
 {
+    static_assert(kTok == 64, "one token per lane");
+    constexpr int NW = kThreads / 64;
+    __shared__ float part[NW][kTok];
     int b = 0;
     while (b + 1 < bd.n_req && (int)blockIdx.x >= bd.tile_begin[b + 1]) ++b;
-    // this kernel is launched with kThreads-token tiles: tile_begin was built for kTok tokens, so
-    // the launcher passes a table built for kThreads instead (see launch code)
     const int tile = blockIdx.x - bd.tile_begin[b];
-    const int i = tile * kThreads + threadIdx.x;
-    if (i >= bd.ctx_len[b]) return;
-    const int64_t row = bd.ctx_off[b] + i;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int i = tile * kTok + lane;
+    const bool live = i < bd.ctx_len[b];
+    const int64_t row = bd.ctx_off[b] + min(i, bd.ctx_len[b] - 1);
     const int grp = n_q_heads / n_kv_heads;
     const float2 *st = stats + (int64_t)(bd.req0 + b) * n_q_heads;
     float s = 0.f;
-    for (int g = 0; g < n_kv_heads; ++g) {
+    for (int g = wave; g < n_kv_heads; g += NW) {
         float mass = 0.f;
         for (int hh = 0; hh < grp; ++hh) {
             const int h = g * grp + hh;
             const float2 ms = st[h];
-            mass += expf(logits[(int64_t)h * n_rows + row] - ms.x) / ms.y;
+            mass += __builtin_amdgcn_exp2f((logits[(int64_t)h * n_rows + row] - ms.x) * 1.4426950408889634f) * (1.0f / ms.y);
         }
         s += mass * dev_v[(int64_t)g * n_rows + row];
     }
-    const bool cand = reused ? reused[row] != 0 : true;
-    score[row] = cand ? s : -INFINITY;
+    part[wave][lane] = s;
+    __syncthreads();
+    if (wave == 0 && live) {
+        float t = part[0][lane];
+#pragma unroll
+        for (int w = 1; w < NW; ++w) t += part[w][lane];
+        const bool cand = reused ? reused[row] != 0 : true;
+        score[row] = cand ? t : -INFINITY;
+    }
 }
 
 // ---- 5. optional decode attention output -------------------------------------------------------
@@ -338,23 +349,20 @@ extern "C" kvs_status kvs_decode_check(const kvs_shape *shape, int32_t batch, in
 
     for (int32_t b0 = 0; b0 < batch; b0 += kMaxReq) {
         const int nr = (batch - b0) < kMaxReq ? (batch - b0) : kMaxReq;
-        DecodeBatch bd_tok, bd_thr;   // tile tables for kTok-token and kThreads-token tiles
-        int64_t tiles_tok = 0, tiles_thr = 0;
+        DecodeBatch bd_tok;   // tile table for kTok-token tiles
+        int64_t tiles_tok = 0;
         for (int i = 0; i < kMaxReq; ++i) {
             const bool live = i < nr;
             const int64_t len = live ? ctx_len[b0 + i] : 0;
-            bd_tok.ctx_off[i] = bd_thr.ctx_off[i] = live ? ctx_off[b0 + i] : 0;
-            bd_tok.ctx_len[i] = bd_thr.ctx_len[i] = (int32_t)len;
+            bd_tok.ctx_off[i] = live ? ctx_off[b0 + i] : 0;
+            bd_tok.ctx_len[i] = (int32_t)len;
             bd_tok.tile_begin[i] = (int32_t)tiles_tok;
-            bd_thr.tile_begin[i] = (int32_t)tiles_thr;
             tiles_tok += (len + kTok - 1) / kTok;
-            tiles_thr += (len + kThreads - 1) / kThreads;
             if (tiles_tok > 0x7fffffffLL) return fail(KVS_EINVAL, "kvs_decode_check: too many tokens in one launch");
         }
         bd_tok.tile_begin[kMaxReq] = (int32_t)tiles_tok;
-        bd_thr.tile_begin[kMaxReq] = (int32_t)tiles_thr;
-        bd_tok.req0 = bd_thr.req0 = b0;
-        bd_tok.n_req = bd_thr.n_req = nr;
+        bd_tok.req0 = b0;
+        bd_tok.n_req = nr;
         if (tiles_tok == 0) continue;
         const int grp = hq / hk;
         const bool regq = (kThreads / lph) % hk == 0;   // every lane group keeps one kv head
@@ -383,7 +391,7 @@ extern "C" kvs_status kvs_decode_check(const kvs_shape *shape, int32_t batch, in
         if ((st = check_launch("kvs_decode_check(logits)")) != KVS_OK) return st;
         hipLaunchKernelGGL(decode_stats_kernel, dim3((unsigned)(nr * hq)), block, 0, hs, bd_tok, hq, part_l, stats);
         if ((st = check_launch("kvs_decode_check(stats)")) != KVS_OK) return st;
-        hipLaunchKernelGGL(decode_score_kernel, dim3((unsigned)tiles_thr), block, 0, hs, bd_thr, hq, hk, n_rows,
+        hipLaunchKernelGGL(decode_score_kernel, dim3((unsigned)tiles_tok), block, 0, hs, bd_tok, hq, hk, n_rows,
                            logits, stats, dev_v, reused, score);
         if ((st = check_launch("kvs_decode_check(score)")) != KVS_OK) return st;
         if (attn_out) {

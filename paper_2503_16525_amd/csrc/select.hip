@@ -274,6 +274,7 @@ kvs_status launch_select(const float *scores, int32_t n_rows, const int64_t *beg
         else if (max_len <= 8 * kSelThreads) hipLaunchKernelGGL(select_kernel<8>, grid, block, 0, hs, scores, idx_out, rows);
         else if (max_len <= 16 * kSelThreads) hipLaunchKernelGGL(select_kernel<16>, grid, block, 0, hs, scores, idx_out, rows);
         else if (max_len <= 32 * kSelThreads) hipLaunchKernelGGL(select_kernel<32>, grid, block, 0, hs, scores, idx_out, rows);
+        else if (max_len <= 36 * kSelThreads) hipLaunchKernelGGL(select_kernel<36>, grid, block, 0, hs, scores, idx_out, rows);
         else if (max_len <= 48 * kSelThreads) hipLaunchKernelGGL(select_kernel<48>, grid, block, 0, hs, scores, idx_out, rows);
         else hipLaunchKernelGGL(select_kernel<0>, grid, block, 0, hs, scores, idx_out, rows);
         kvs_status st = check_launch("kvs_select_topk");
