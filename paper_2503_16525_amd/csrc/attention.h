@@ -36,6 +36,7 @@ int64_t build_attn_tiles(const kvs_shape *shape, const AttnBatch &bd, int rows_p
 // weights, unused) per row; slot = row * n_splits + piece.
 constexpr size_t kAttnPartBytesPerSlot = 128 * sizeof(float) + 4 * sizeof(float);
 constexpr int kAttnSplitMax = 16;
+constexpr int kAttnSplitCus = 256;         // compute units a round of pieces is spread over
 constexpr int kAttnSplitBelowWgs = 384;    // launches with fewer workgroups than this get split ...
 #ifndef KVS_ATTN_SPLIT_TARGET
 #define KVS_ATTN_SPLIT_TARGET 768
@@ -47,12 +48,13 @@ kvs_status launch_attention_merge(int64_t n_rows, int n_splits, const float *par
                                   uint16_t *out, float *lse_out, hipStream_t st);
 
 // 64 query rows per wave (two MFMAs per LDS operand), one wave per SIMD, 256-row tiles.  n_splits > 1
-// (from attention_mfma2_splits, which needs the workspace size) cuts every row tile's key range.
-int attention_mfma2_splits(const kvs_shape *shape, const AttnBatch &bd, size_t workspace_bytes);
+// (from attention_mfma2_splits, which needs the workspace size) cuts the key range into pieces of
+// split_chunk key tiles.
+int attention_mfma2_splits(const kvs_shape *shape, const AttnBatch &bd, size_t workspace_bytes, int *split_chunk);
 kvs_status launch_attention_mfma2(const kvs_shape *shape, const AttnBatch &bd, const void *q_sel,
                                   const int32_t *sel_pos, const void *k_cache, const void *v_cache,
                                   float scale, void *out, float *lse_out, void *workspace, int n_splits,
-                                  hipStream_t st);
+                                  int split_chunk, hipStream_t st);
 
 kvs_status launch_attention_valu(const kvs_shape *shape, const AttnBatch &bd, int64_t n_sel,
                                  const void *q_sel, const int32_t *sel_pos, const void *k_cache,

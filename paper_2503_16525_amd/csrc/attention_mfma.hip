@@ -362,10 +362,10 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(int64_t n_rows, int n_s
     float4 p[kAttnSplitMax];
 #pragma unroll
     for (int s = 0; s < kAttnSplitMax; ++s)
-        if (s < n_splits) {
-            p[s] = ml[s];
-            v[s] = *reinterpret_cast<const float4 *>(po + s * D);
-        }
+        if (s < n_splits) p[s] = ml[s];
+#pragma unroll
+    for (int s = 0; s < kAttnSplitMax; ++s)
+        if (s < n_splits && p[s].y > 0.f) v[s] = *reinterpret_cast<const float4 *>(po + s * D);
     float m = -1.0e30f;
 #pragma unroll
     for (int s = 0; s < kAttnSplitMax; ++s)
@@ -516,14 +516,15 @@ kvs_status launch_attention_mfma(const kvs_shape *shape, const AttnBatch &bd, in
     }
     // with fewer 256-row tiles than compute units the large kernel still wins if the caller's
     // workspace lets it cut the key ranges and its tiles are not mostly padding
-    const int splits2 = workspace ? attention_mfma2_splits(shape, bd, workspace_bytes) : 1;
+    int chunk2 = 0;
+    const int splits2 = workspace ? attention_mfma2_splits(shape, bd, workspace_bytes, &chunk2) : 1;
     const bool fills = big_tiles * shape->n_kv_heads >= kAttnBigTileMinGrid;
     const bool dense_tiles = rows * 10 >= big_tiles * 256 * 6;
     // (below ~160 such tiles the per-workgroup start-up of the large kernel costs more than it gains)
     const bool big = forced ? forced == 2 : fills || (splits2 >= 2 && dense_tiles && big_tiles * shape->n_kv_heads >= 160);
     if (big)
         return launch_attention_mfma2(shape, bd, q_sel, sel_pos, k_cache, v_cache, scale, out, lse_out, workspace,
-                                      fills && !forced ? 1 : splits2, st);
+                                      fills && !forced ? 1 : splits2, chunk2, st);
     return launch_mfma_variant<KVS_ATTN_NWAVES>(shape, bd, q_sel, sel_pos, k_cache, v_cache, scale, out, lse_out,
                                                 workspace, workspace_bytes, st);
 }

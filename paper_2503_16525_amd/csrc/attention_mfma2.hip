@@ -84,17 +84,19 @@ __device__ long long kvs_diag_clk[4096];
 
 
 // WANT_LSE: additionally keep the unrounded sum of weights, from which the log-sum-exp is reported.
-// SPLIT: the key range of a row tile is cut into n_splits contiguous pieces handled by different
-// workgroups (launches with few row tiles over long contexts would otherwise leave most of the chip
-// idle); every piece writes its unnormalised accumulators and (reference, sum) to the workspace and
-// the merge kernel combines them.
+// SPLIT: the key range is cut into pieces of split_chunk key tiles (at most n_splits per row tile)
+// handled by different workgroups (launches with few row tiles over long contexts would otherwise
+// leave most of the chip idle); every piece writes its unnormalised accumulators and (reference,
+// sums) to the workspace and the merge kernel combines them.  The pieces are absolute key ranges,
+// the same for every row tile, and the grid runs through them piece by piece: the workgroups that
+// are resident together read the same stretch of K and V, which then stays in L2.
 template <bool WANT_LSE, bool SPLIT>
 __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
     const AttnTiles td, int n_q_heads, int n_kv_heads, int total_tiles,
     const uint16_t *__restrict__ q_sel, const int32_t *__restrict__ sel_pos,
     const uint16_t *__restrict__ k_cache, const uint16_t *__restrict__ v_cache,
     float scale_log2, uint16_t *__restrict__ out, float *__restrict__ lse_out,
-    int n_splits, float *__restrict__ part_o, float4 *__restrict__ part_ml)
+    int n_splits, int split_chunk, float *__restrict__ part_o, float4 *__restrict__ part_ml)
 {
     extern __shared__ __attribute__((aligned(16))) uint16_t lds[];   // K ring, then V^T ring
     __shared__ int wg_max_pos[NWAVES];
@@ -108,8 +110,8 @@ __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
     // ---- which (request, kv head, row tile) -----------------------------------------------------
     const int g = blockIdx.x % n_kv_heads;
     const int rest = (int)(blockIdx.x / n_kv_heads);
-    const int split = SPLIT ? rest % n_splits : 0;
-    const int tile_lin = total_tiles - 1 - (SPLIT ? rest / n_splits : rest);
+    const int split = SPLIT ? rest / total_tiles : 0;
+    const int tile_lin = total_tiles - 1 - (SPLIT ? rest % total_tiles : rest);
     int b = 0;
     while (b + 1 < td.n_req && tile_lin >= td.tile_begin[b + 1]) ++b;
     const int tile = tile_lin - td.tile_begin[b];
@@ -166,9 +168,14 @@ __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
     for (int w = 1; w < NWAVES; ++w) wg_pmax = max(wg_pmax, wg_max_pos[w]);
     const int n_kv_tiles = wg_pmax / BN + 1;
     // this workgroup's share of the key tiles: [t_lo, t_hi)
-    const int t_chunk = SPLIT ? (n_kv_tiles + n_splits - 1) / n_splits : n_kv_tiles;
-    const int t_lo = SPLIT ? min(n_kv_tiles, split * t_chunk) : 0;
-    const int t_hi = SPLIT ? min(n_kv_tiles, t_lo + t_chunk) : n_kv_tiles;
+    const int t_lo = SPLIT ? min(n_kv_tiles, split * split_chunk) : 0;
+    const int t_hi = SPLIT ? min(n_kv_tiles, t_lo + split_chunk) : n_kv_tiles;
+    if (SPLIT && t_lo >= t_hi) {   // nothing of this tile in this key range: mark the piece empty
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+            if (row_ok[nb] && hf == 0) part_ml[row_idx[nb] * (int64_t)n_splits + split] = make_float4(-1.0e30f, 0.f, 0.f, 0.f);
+        return;
+    }
 
     // ---- global -> register -> LDS staging of one K/V tile ------------------------------------------
     // Buffer loads: the tile's position goes into the scalar offset, the per-lane part is constant.
@@ -463,7 +470,7 @@ __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
         // different loops.  Tiles past the last one may get staged here; nothing reads them.
         const int j_unmasked = (pmin + 1) / BN;     // tiles 0 .. j_unmasked-1: every key <= pmin
         const int j_inside = ctx_len / BN;          // tiles 0 .. j_inside-1 need no row clamp
-        if (t_lo + 3 <= min(j_unmasked, t_hi) && t_lo + 7 <= j_inside) {
+        if (t_lo + 3 <= t_hi && t_lo + 7 <= j_inside) {
             // the first step has no earlier tile to multiply: scores of the second tile, softmax of the first
             u32x4_t p_a[NB][2], p_b[NB][2];
             store_tile(t_lo + 2, held);
@@ -577,7 +584,8 @@ namespace {
 template <bool WANT_LSE, bool SPLIT>
 kvs_status launch_one(const dim3 grid, size_t lds_bytes, hipStream_t st, const AttnTiles &td, const kvs_shape *shape,
                       int tiles, const void *q_sel, const int32_t *sel_pos, const void *k_cache, const void *v_cache,
-                      float scale_log2, void *out, float *lse_out, int n_splits, float *part_o, float4 *part_ml)
+                      float scale_log2, void *out, float *lse_out, int n_splits, int split_chunk, float *part_o,
+                      float4 *part_ml)
 {
     static bool attr_set = false;   // idempotent; a race only repeats the same call
     if (!attr_set) {
@@ -588,12 +596,12 @@ kvs_status launch_one(const dim3 grid, size_t lds_bytes, hipStream_t st, const A
     }
     hipLaunchKernelGGL((attn_mfma2_kernel<WANT_LSE, SPLIT>), grid, dim3(NT), lds_bytes, st, td, shape->n_q_heads,
                        shape->n_kv_heads, tiles, (const uint16_t *)q_sel, sel_pos, (const uint16_t *)k_cache,
-                       (const uint16_t *)v_cache, scale_log2, (uint16_t *)out, lse_out, n_splits, part_o, part_ml);
+                       (const uint16_t *)v_cache, scale_log2, (uint16_t *)out, lse_out, n_splits, split_chunk, part_o, part_ml);
     return check_launch("kvs_partial_attention(mfma2)");
 }
 } // namespace
 
-int attention_mfma2_splits(const kvs_shape *shape, const AttnBatch &bd, size_t workspace_bytes)
+int attention_mfma2_splits(const kvs_shape *shape, const AttnBatch &bd, size_t workspace_bytes, int *split_chunk)
 {
     const int grp = shape->n_q_heads / shape->n_kv_heads;
     int64_t tiles = 0, max_ctx = 0;
@@ -601,22 +609,46 @@ int attention_mfma2_splits(const kvs_shape *shape, const AttnBatch &bd, size_t w
         tiles += ((bd.cu_sel[i + 1] - bd.cu_sel[i]) * grp + ROWS - 1) / ROWS;
         max_ctx = bd.ctx_len[i] > max_ctx ? bd.ctx_len[i] : max_ctx;
     }
+    *split_chunk = 0;
     const int64_t wgs = tiles * shape->n_kv_heads;
     if (wgs <= 0 || wgs >= kAttnSplitBelowWgs) return 1;
-    int64_t s = (kAttnSplitTargetWgs + wgs - 1) / wgs;
-    if (s > kAttnSplitMax) s = kAttnSplitMax;
-    const int64_t by_len = max_ctx / (16 * BN);                      // at least 16 key tiles per piece
-    if (s > by_len) s = by_len;
+    const int64_t ctx_tiles = (max_ctx + BN - 1) / BN;
     const int64_t n_rows_total = (bd.cu_sel[bd.n_req] - bd.cu_sel[0]) * shape->n_q_heads;
+    int64_t s_max = kAttnSplitMax;
+    const int64_t by_len = ctx_tiles / 16;                           // at least 16 key tiles per piece
+    if (s_max > by_len) s_max = by_len;
     const int64_t by_ws = (int64_t)(workspace_bytes / (kAttnPartBytesPerSlot * (size_t)(n_rows_total > 0 ? n_rows_total : 1)));
-    if (s > by_ws) s = by_ws;
-    return s >= 2 ? (int)s : 1;
+    if (s_max > by_ws) s_max = by_ws;
+    if (s_max < 2) return 1;
+    // Pieces run in rounds of one per compute unit and every piece costs about its chunk length, so
+    // the chunk decides how many pieces exist and how full the last round is.  The positions are on
+    // the device; assume they are spread evenly over each context (row tile t of T reaches
+    // (t+1)/T of it) and take the chunk with the shortest predicted time.  A wrong guess costs speed
+    // only.
+    const int64_t c_min = (ctx_tiles + s_max - 1) / s_max;
+    int64_t best_c = c_min;
+    double best_t = 1e300;
+    for (int64_t c = c_min; c <= ctx_tiles; c += (c < 64 ? 4 : 8)) {
+        int64_t pieces = 0;
+        for (int i = 0; i < bd.n_req; ++i) {
+            const int64_t T = ((bd.cu_sel[i + 1] - bd.cu_sel[i]) * grp + ROWS - 1) / ROWS;
+            const int64_t L = (bd.ctx_len[i] + BN - 1) / BN;
+            for (int64_t t = 0; t < T; ++t) pieces += (L * (t + 1) / T + c - 1) / c;
+        }
+        pieces *= shape->n_kv_heads;
+        const int64_t rounds = (pieces + kAttnSplitCus - 1) / kAttnSplitCus;
+        const double time = (double)rounds * ((double)c + 3.0);     // ~3 steps' worth of start-up per piece
+        if (time < best_t) { best_t = time; best_c = c; }
+    }
+    *split_chunk = (int)best_c;
+    const int n = (int)((ctx_tiles + best_c - 1) / best_c);
+    return n >= 2 ? n : 1;
 }
 
 kvs_status launch_attention_mfma2(const kvs_shape *shape, const AttnBatch &bd, const void *q_sel,
                                   const int32_t *sel_pos, const void *k_cache, const void *v_cache,
                                   float scale, void *out, float *lse_out, void *workspace, int n_splits,
-                                  hipStream_t st)
+                                  int split_chunk, hipStream_t st)
 {
     AttnTiles td;
     const int64_t tiles = build_attn_tiles(shape, bd, ROWS, td);
@@ -627,9 +659,9 @@ kvs_status launch_attention_mfma2(const kvs_shape *shape, const AttnBatch &bd, c
     if (n_splits <= 1 || !workspace) {
         const dim3 grid((unsigned)(tiles * shape->n_kv_heads));
         return lse_out ? launch_one<true, false>(grid, lds_bytes, st, td, shape, (int)tiles, q_sel, sel_pos, k_cache, v_cache,
-                                                 scale_log2, out, lse_out, 1, nullptr, nullptr)
+                                                 scale_log2, out, lse_out, 1, 0, nullptr, nullptr)
                        : launch_one<false, false>(grid, lds_bytes, st, td, shape, (int)tiles, q_sel, sel_pos, k_cache, v_cache,
-                                                  scale_log2, out, lse_out, 1, nullptr, nullptr);
+                                                  scale_log2, out, lse_out, 1, 0, nullptr, nullptr);
     }
     // pieces are indexed by the row's position in the whole call's output, so offset the tables by
     // the first row of this launch
@@ -641,9 +673,9 @@ kvs_status launch_attention_mfma2(const kvs_shape *shape, const AttnBatch &bd, c
     const dim3 grid((unsigned)(tiles * shape->n_kv_heads * n_splits));
     const kvs_status stt =
         lse_out ? launch_one<true, true>(grid, lds_bytes, st, td, shape, (int)tiles, q_sel, sel_pos, k_cache, v_cache,
-                                         scale_log2, out, lse_out, n_splits, part_o, part_ml)
+                                         scale_log2, out, lse_out, n_splits, split_chunk, part_o, part_ml)
                 : launch_one<false, true>(grid, lds_bytes, st, td, shape, (int)tiles, q_sel, sel_pos, k_cache, v_cache,
-                                          scale_log2, out, lse_out, n_splits, part_o, part_ml);
+                                          scale_log2, out, lse_out, n_splits, split_chunk, part_o, part_ml);
     if (stt != KVS_OK) return stt;
     return launch_attention_merge(n_rows_total, n_splits, (const float *)workspace, ml_base,
                                   (uint16_t *)out + row0 * D, lse_out ? lse_out + row0 : nullptr, st);
