@@ -50,14 +50,11 @@ constexpr int NB = 2;              // 32-row query blocks per wave
 constexpr int NT = NWAVES * 64;
 constexpr int WROWS = 32 * NB;
 constexpr int ROWS = NWAVES * WROWS;   // 256 rows per workgroup
-constexpr int K_LD = D + 8;        // K tile row pitch in bf16 (272 B)
-constexpr int V_LD = D + 16;        // V tile row pitch in bf16 (288 B): 4 consecutive rows x 32 B hit 32 distinct banks
-constexpr int K_TILE = BN * K_LD;
-constexpr int V_TILE = BN * V_LD;
-constexpr int K_RING = 4;   // >= 3, see the barrier argument at fast_step
-constexpr int V_RING = 8;   // >= 5
-constexpr int LDS_ELEMS = K_RING * K_TILE + V_RING * V_TILE;
-constexpr int K_PIECES = BN * (D / 8) / NT;   // 2
+constexpr int ROW_B = D * 2;            // bytes of one K or V row of one head
+constexpr int TILE_B = BN * ROW_B;      // a K or V tile in LDS: 32 rows of 256 B, 16-byte pieces XOR-swizzled
+constexpr int K_RING = 4;   // tiles; see the slot argument at stage_tile
+constexpr int V_RING = 8;
+constexpr int LDS_BYTES = (K_RING + V_RING) * TILE_B;
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4_t v) { return __builtin_bit_cast(bf16x8, v); }
 
 __device__ __forceinline__ uint32_t pack2(float lo, float hi)
@@ -177,100 +174,131 @@ __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
         return;
     }
 
-    // ---- global -> register -> LDS staging of one K/V tile ------------------------------------------
-    // Buffer loads: the tile's position goes into the scalar offset, the per-lane part is constant.
+    // ---- global -> LDS staging of one K/V tile ---------------------------------------------------------
+    // Buffer loads that write straight into LDS: no registers, no LDS store instructions, and the
+    // data does not pass through the vector register file.  One instruction moves 64 x 16 bytes to
+    // 1 KiB of consecutive LDS (lane l -> bytes 16 l), i.e. four 256-byte rows; a wave stages rows
+    // 4w .. 4w+3 of each half of the tile, K and V, four instructions per tile.  A tile in LDS is 32
+    // rows of 256 B without padding; the 16-byte piece p of row r sits at position p ^ f(r), which
+    // the load realises by letting lane (row, position) fetch piece position ^ f(row).  f is chosen
+    // per tile kind so that the operand reads below are free of bank conflicts:
+    //   K: f(r) = r & 15           (8 lanes read 8 different rows at the same piece index),
+    //   V: f(r) = 2 (r & 7)        (a transposing read covers 4 consecutive rows x 2 pieces).
     // Every address is kept inside the request's rows by construction (tiles wholly inside the
     // context, or per-row clamping); the buffer's record count is a second guard only.
     const uint32_t row_bytes = (uint32_t)n_kv_heads * D * 2u;          // bytes between tokens
     const uint32_t head_bytes = ((uint32_t)ctx_len - 1u) * row_bytes + D * 2u;   // this head's span of the request
-    const __amdgpu_buffer_rsrc_t krs = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<uint16_t *>(k_cache + (ctx_off * n_kv_heads + g) * (int64_t)D), 0, head_bytes, 0x00020000);
-    const __amdgpu_buffer_rsrc_t vrs = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<uint16_t *>(v_cache + (ctx_off * n_kv_heads + g) * (int64_t)D), 0, head_bytes, 0x00020000);
-    struct Staged { u32x4_t k[K_PIECES], v[K_PIECES]; };   // one tile on its way from HBM to LDS
-    const uint32_t k_lane_off = (uint32_t)(tid >> 4) * row_bytes + (uint32_t)(tid & 15) * 16u;
-
-    // tile jt wholly inside the context
-    auto load_tile_inside = [&](int jt, Staged &st) {
-        const uint32_t kt = (uint32_t)jt * BN * row_bytes;
-#pragma unroll
-        for (int i = 0; i < K_PIECES; ++i) {
-            st.k[i] = __builtin_amdgcn_raw_buffer_load_b128(krs, k_lane_off, kt + (uint32_t)(i * (NT / 16)) * row_bytes, 0);
-            st.v[i] = __builtin_amdgcn_raw_buffer_load_b128(vrs, k_lane_off, kt + (uint32_t)(i * (NT / 16)) * row_bytes, 0);
-        }
+    // buffer resource: base address, 48 bits; stride 0; size in bytes; dword 3 as for untyped access
+    auto make_rsrc = [&](const uint16_t *base) -> u32x4_t {
+        const uint64_t a = reinterpret_cast<uint64_t>(base);
+        u32x4_t r = {(uint32_t)a, (uint32_t)(a >> 32) & 0xffffu, head_bytes, 0x00020000u};
+        r.x = __builtin_amdgcn_readfirstlane(r.x);
+        r.y = __builtin_amdgcn_readfirstlane(r.y);
+        r.z = __builtin_amdgcn_readfirstlane(r.z);
+        return r;
     };
-    auto load_tile = [&](int jt, Staged &st) {      // any tile: rows past the context are clamped
-        const int kv0 = jt * BN;
-        if (kv0 + BN <= ctx_len) {
-            load_tile_inside(jt, st);
+    const u32x4_t krs = make_rsrc(k_cache + (ctx_off * n_kv_heads + g) * (int64_t)D);
+    const u32x4_t vrs = make_rsrc(v_cache + (ctx_off * n_kv_heads + g) * (int64_t)D);
+    char *const lds_b = reinterpret_cast<char *>(lds);
+    // byte offset of the dynamic LDS array inside the workgroup's allocation (what M0 has to carry)
+    const uint32_t lds_base = __builtin_amdgcn_readfirstlane(
+        (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)lds_b);
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    const int st_row = 4 * wave_u + (lane >> 4);       // row inside a 16-row half of the tile, 0..15
+    const int st_pos = lane & 15;                      // piece position inside the row
+    const uint32_t st_k_piece = (uint32_t)(st_pos ^ st_row) * 16u;
+    const uint32_t st_v_piece = (uint32_t)(st_pos ^ (2 * (st_row & 7))) * 16u;
+    const uint32_t st_k_voff = (uint32_t)(lane >> 4) * row_bytes + st_k_piece;
+    const uint32_t st_v_voff = (uint32_t)(lane >> 4) * row_bytes + st_v_piece;
+    // Slots.  Tile t goes to K slot t & 3 and V slot t & 7.  stage_part(t, .) is issued in the second
+    // half of step t-4, after that step's barrier.  K slot t & 3 held tile t-4, last read in step t-5,
+    // V slot t & 7 held tile t-8, last read in step t-7 (the general loop: t-8): every wave has passed
+    // the barrier of step t-4 since.  The tile must have landed by the barrier of step t-2 (its K is
+    // first read at the end of step t-2): each wave waits for its own parts there, allowing only the
+    // four instructions of tile t+1 to be still in flight.
+    // The instruction is written out by hand: issued through the compiler's builtin it makes the
+    // compiler wait for all outstanding loads before every later LDS read it cannot prove disjoint,
+    // which would serialise the sweep on global-memory latency.  Here the waiting is done once per
+    // step, at the barrier (KVS_ATTN_BARRIER).  M0 holds the LDS destination of lane 0; the nop covers
+    // the wait state an M0 write needs before such a load.
+    auto stage_1k = [&](const u32x4_t &rs, uint32_t lds_dst, uint32_t voff, uint32_t soff) {
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                     :: "s"(lds_dst), "v"(voff), "s"(rs), "s"(soff));
+    };
+    auto stage_part = [&](int t, int part) {           // part 0,1: K rows 0-15 / 16-31; 2,3: V likewise
+        const int q = part & 1;
+        const uint32_t soff = __builtin_amdgcn_readfirstlane(((uint32_t)t * BN + (uint32_t)(16 * q + 4 * wave_u)) * row_bytes);
+        const uint32_t dst = lds_base + (uint32_t)(16 * q + 4 * wave_u) * ROW_B;
+        if (part < 2)
+            stage_1k(krs, __builtin_amdgcn_readfirstlane(dst + (uint32_t)((t & (K_RING - 1)) * TILE_B)), st_k_voff, soff);
+        else
+            stage_1k(vrs, __builtin_amdgcn_readfirstlane(dst + (uint32_t)((K_RING + (t & (V_RING - 1))) * TILE_B)), st_v_voff, soff);
+    };
+    auto stage_tile_inside = [&](int t) {              // tile wholly inside the context
+#pragma unroll
+        for (int part = 0; part < 4; ++part) stage_part(t, part);
+    };
+    auto stage_tile = [&](int t) {                     // any tile: rows past the context are clamped
+        if ((t + 1) * BN <= ctx_len) {
+            stage_tile_inside(t);
         } else {
 #pragma unroll
-            for (int i = 0; i < K_PIECES; ++i) {
-                const int key = min(kv0 + i * (NT / 16) + (tid >> 4), ctx_len - 1);
-                st.k[i] = __builtin_amdgcn_raw_buffer_load_b128(krs, (uint32_t)key * row_bytes + (uint32_t)(tid & 15) * 16u, 0, 0);
-                st.v[i] = __builtin_amdgcn_raw_buffer_load_b128(vrs, (uint32_t)key * row_bytes + (uint32_t)(tid & 15) * 16u, 0, 0);
+            for (int q = 0; q < 2; ++q) {
+                const int key = min(t * BN + 16 * q + st_row, ctx_len - 1);
+                const uint32_t dst = lds_base + (uint32_t)(16 * q + 4 * wave_u) * ROW_B;
+                stage_1k(krs, __builtin_amdgcn_readfirstlane(dst + (uint32_t)((t & (K_RING - 1)) * TILE_B)),
+                         (uint32_t)key * row_bytes + st_k_piece, 0u);
+                stage_1k(vrs, __builtin_amdgcn_readfirstlane(dst + (uint32_t)((K_RING + (t & (V_RING - 1))) * TILE_B)),
+                         (uint32_t)key * row_bytes + st_v_piece, 0u);
             }
         }
     };
-    uint16_t *const k_ring = lds;
-    uint16_t *const v_ring = lds + K_RING * K_TILE;
-    auto store_tile = [&](int jt, const Staged &st) {
-        uint16_t *ks = k_ring + (jt & (K_RING - 1)) * K_TILE;
-        uint16_t *vs = v_ring + (jt & (V_RING - 1)) * V_TILE;
-#pragma unroll
-        for (int i = 0; i < K_PIECES; ++i) {
-            const int id = i * NT + tid;
-            *reinterpret_cast<u32x4_t *>(ks + (id >> 4) * K_LD + (id & 15) * 8) = st.k[i];
-            *reinterpret_cast<u32x4_t *>(vs + (id >> 4) * V_LD + (id & 15) * 8) = st.v[i];
-        }
-    };
-    // the same staging in pieces, for the pipelined sweep (tile wholly inside the context)
-    auto load_k_piece = [&](int jt, Staged &st, int i) {
-        st.k[i] = __builtin_amdgcn_raw_buffer_load_b128(krs, k_lane_off, ((uint32_t)jt * BN + (uint32_t)(i * (NT / 16))) * row_bytes, 0);
-    };
-    auto load_v_piece = [&](int jt, Staged &st, int i) {
-        st.v[i] = __builtin_amdgcn_raw_buffer_load_b128(vrs, k_lane_off, ((uint32_t)jt * BN + (uint32_t)(i * (NT / 16))) * row_bytes, 0);
-    };
-    auto store_k_piece = [&](int jt, const Staged &st, int i) {
-        const int id = i * NT + tid;
-        *reinterpret_cast<u32x4_t *>(k_ring + (jt & (K_RING - 1)) * K_TILE + (id >> 4) * K_LD + (id & 15) * 8) = st.k[i];
-    };
-    auto store_v_piece = [&](int jt, const Staged &st, int i) {
-        const int id = i * NT + tid;
-        *reinterpret_cast<u32x4_t *>(v_ring + (jt & (V_RING - 1)) * V_TILE + (id >> 4) * V_LD + (id & 15) * 8) = st.v[i];
-    };
+    // Barriers of the sweep.  The staged data arrives asynchronously (the vector-memory counter
+    // tracks it, oldest first); nothing else of the workgroup's LDS traffic needs ordering here: a
+    // slot is only overwritten long after its last reader (above).  `in_flight` = staging
+    // instructions of younger tiles that may still be outstanding.
+#define KVS_ATTN_BARRIER(in_flight) asm volatile("s_waitcnt vmcnt(" #in_flight ")\n\ts_barrier" ::: "memory")
 
     // ---- the three pieces of one tile's work ----------------------------------------------------------
     // K row fed to MFMA row ln: bits 2 and 3 swapped, so that accumulator entry r of a lane is key
-    // 16*(r>>3) + 8*hf + (r&7) of the tile
+    // 16*(r>>3) + 8*hf + (r&7) of the tile.  The lane reads piece 2*ks + hf of that row, which sits
+    // at position (2*ks + hf) ^ (row & 15): byte offset = lane constant ^ 32*ks.
     const int krow = (ln & ~12) | ((ln & 4) << 1) | ((ln & 8) >> 1);
-    const uint32_t k_read_off = (uint32_t)(krow * K_LD + 8 * hf);      // + 16*ks
+    const uint32_t k_read_off = (uint32_t)(krow * ROW_B + ((hf ^ (krow & 15)) * 16));
     // V stays row-major [key][channel] in LDS; the A operand of the PV product (channel = MFMA row,
     // 8 consecutive keys per lane) comes out of two transposing LDS reads.  In each group of 16
     // lanes, lane s points at 8 bytes (4 channels) and lane i receives, as element j, element i%4 of
     // the lane i/4 + 4j: with lane s on key k0 + s/4, channels d0 + 4*(s%4) .. +3, lane i ends up
     // with channel d0 + i of keys k0 .. k0+3.  Groups 0/1 are channels 0-15 / 16-31 of the block,
-    // groups 2/3 the same for the half-wave's second set of 8 keys.
+    // groups 2/3 the same for the half-wave's second set of 8 keys.  The 8 bytes are half (s & 1) of
+    // piece 4*db + 2*(group & 1) + (s % 4) / 2 of their row: byte offset = lane constant ^ 64*db.
     const int tr_s = lane & 15, tr_g = lane >> 4;
-    const uint32_t v_read_off = (uint32_t)((8 * (tr_g >> 1) + (tr_s >> 2)) * V_LD + 16 * (tr_g & 1) + 4 * (tr_s & 3));
-    // + 16*kstep*V_LD + 32*db for keys 0-3 of the lane's 8, + 4*V_LD more for keys 4-7
-    auto read_vt = [&](const uint16_t *vs, int kstep, int db) -> u32x4_t {
+    const int tr_key = 8 * (tr_g >> 1) + (tr_s >> 2);                  // keys 0-3 of the lane's 8; +4 for keys 4-7
+    const int tr_c = 2 * (tr_g & 1) + ((tr_s & 3) >> 1);
+    const uint32_t v_read_lo = (uint32_t)(tr_key * ROW_B + ((tr_c ^ (2 * (tr_key & 7))) * 16) + 8 * (tr_s & 1));
+    const uint32_t v_read_hi = (uint32_t)((tr_key + 4) * ROW_B + ((tr_c ^ (2 * ((tr_key + 4) & 7))) * 16) + 8 * (tr_s & 1));
+    auto read_k = [&](uint32_t slot_off, int ks) -> u32x4_t {          // slot_off: byte offset of the K tile in LDS
+        return *reinterpret_cast<const u32x4_t *>(lds_b + ((k_read_off ^ (uint32_t)(32 * ks)) + slot_off));
+    };
+    auto read_vt = [&](uint32_t slot_off, int kstep, int db) -> u32x4_t {
         typedef short v4i16 __attribute__((ext_vector_type(4)));
         typedef __attribute__((address_space(3))) v4i16 lds_v4i16;
-        const uint16_t *p = vs + 16 * kstep * V_LD + 32 * db;
-        const v4i16 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16 *)(p));
-        const v4i16 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16 *)(p + 4 * V_LD));
+        const uint32_t base = slot_off + (uint32_t)(16 * kstep * ROW_B);
+        const v4i16 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16 *)(lds_b + ((v_read_lo ^ (uint32_t)(64 * db)) + base)));
+        const v4i16 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16 *)(lds_b + ((v_read_hi ^ (uint32_t)(64 * db)) + base)));
         const uint2 l2 = __builtin_bit_cast(uint2, lo), h2 = __builtin_bit_cast(uint2, hi);
         u32x4_t r = {l2.x, l2.y, h2.x, h2.y};
         return r;
     };
+    auto k_slot = [&](int t) -> uint32_t { return (uint32_t)((t & (K_RING - 1)) * TILE_B); };
+    auto v_slot = [&](int t) -> uint32_t { return (uint32_t)((K_RING + (t & (V_RING - 1))) * TILE_B); };
     const floatx16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
     auto qk = [&](int jt, floatx16 (&s)[NB]) {
-        const uint16_t *ks = k_ring + (jt & (K_RING - 1)) * K_TILE + k_read_off;
+        const uint32_t ks = k_slot(jt);
 #pragma unroll
         for (int ksx = 0; ksx < D / 16; ++ksx) {
-            const u32x4_t a = *reinterpret_cast<const u32x4_t *>(ks + 16 * ksx);
+            const u32x4_t a = read_k(ks, ksx);
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb)
                 s[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a), qreg[nb][ksx], ksx == 0 ? zero : s[nb], 0, 0, 0);
@@ -325,7 +353,7 @@ __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
             for (int r0 = 0; r0 < 16; r0 += 4) softmax4(s[nb], nb, r0, pop[nb]);
     };
     auto pv_product = [&](int jt, const u32x4_t (&pop)[NB][2]) {
-        const uint16_t *vs = v_ring + (jt & (V_RING - 1)) * V_TILE + v_read_off;
+        const uint32_t vs = v_slot(jt);
 #pragma unroll
         for (int a = 0; a < 2; ++a)
 #pragma unroll
@@ -338,26 +366,20 @@ __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
     };
 
     // One step of the pipelined sweep (tile jt+4 lies wholly inside the context; `masked` says whether
-    // tile jt needs the causal compare for this wave): scores of tile jt+1, softmax of tile jt, PV of tile jt-1, written
-    // as eight slices of four MFMAs and four scores each, LDS operands fetched one slice ahead
-    // (ka / va enter with slice 0's operands and leave with those of the next step).
-    // On entry tiles jt-1 .. jt+1 are in the LDS rings, `set` carries tile jt+2, s_in the scores of
-    // tile jt and p_in the weights of tile jt-1.
-    // Ring safety with the barrier in mid-step: a slot written at the start of step j was last read
-    // in step j-2 or earlier (K of tile j-2 in step j-3, V^T of tile j-6 in step j-5 at the latest),
-    // and every wave passed the barrier of step j-1 after that read and before this write; tile j+2
-    // is first read in step j+1, after this step's barrier.
+    // tile jt needs the causal compare for this wave): scores of tile jt+1, softmax of tile jt, PV of
+    // tile jt-1, written as eight slices of four MFMAs and four scores each, LDS operands fetched one
+    // slice ahead (ka / va enter with slice 0's operands and leave with those of the next step).
+    // On entry tiles jt-1 .. jt+1 are in the LDS rings and tiles jt+2, jt+3 on their way, s_in holds
+    // the scores of tile jt and p_in the weights of tile jt-1.  The barrier in mid-step makes tile
+    // jt+2 visible; the second half sends out the loads of tile jt+4, one instruction per slice.
     int key_lim[NB];   // a key of the tile is visible to the lane's query nb iff its (half-wave-relative) index <= this
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) key_lim[nb] = pos[nb] - 8 * hf;
     auto fast_step = [&](auto masked, int jt, const floatx16 (&s_in)[NB], floatx16 (&s_out)[NB],
-                         const u32x4_t (&p_in)[NB][2], u32x4_t (&p_out)[NB][2], Staged &set,
+                         const u32x4_t (&p_in)[NB][2], u32x4_t (&p_out)[NB][2],
                          u32x4_t &ka, u32x4_t &va) {
         constexpr bool MASKED = decltype(masked)::value;
-        const uint16_t *ks = k_ring + ((jt + 1) & (K_RING - 1)) * K_TILE + k_read_off;
-        const uint16_t *vs = v_ring + ((jt - 1) & (V_RING - 1)) * V_TILE + v_read_off;
-        const uint16_t *ks_next = k_ring + ((jt + 2) & (K_RING - 1)) * K_TILE + k_read_off;
-        const uint16_t *vs_next = v_ring + (jt & (V_RING - 1)) * V_TILE + v_read_off;
+        const uint32_t ks = k_slot(jt + 1), vs = v_slot(jt - 1), ks_next = k_slot(jt + 2), vs_next = v_slot(jt);
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             // source order of the slice: next slice's LDS operands, then one MFMA at a time, each
@@ -366,10 +388,10 @@ __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
             // slower than its own choice.
             u32x4_t ka_n, va_n;
             if (i < 7) {
-                ka_n = *reinterpret_cast<const u32x4_t *>(ks + 16 * (i + 1));
+                ka_n = read_k(ks, i + 1);
                 va_n = read_vt(vs, (i + 1) >> 2, (i + 1) & 3);
             } else {
-                ka_n = *reinterpret_cast<const u32x4_t *>(ks_next);
+                ka_n = read_k(ks_next, 0);
                 va_n = read_vt(vs_next, 0, 0);
             }
             const int nbs = i >> 2, r0 = 4 * (i & 3), a = i >> 2, db = i & 3;
@@ -397,18 +419,10 @@ __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
             l_run[nbs] = add_rounded_pair(w1, add_rounded_pair(w0, l_run[nbs]));
             if (WANT_LSE) l_exact[nbs] += (e0 + e1) + (e2 + e3);
             o_acc[db][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(va), as_bf16x8(p_in[1][a]), o_acc[db][1], 0, 0, 0);
-            // staging, a piece per slice so that no burst of LDS writes or global loads holds up the
-            // MFMAs: tile jt+2 goes from `set` to LDS before the barrier, the loads of tile jt+4 refill
-            // each register right after it was written out
-            if (i == 0) store_k_piece(jt + 2, set, 0);
-            if (i == 1) { store_k_piece(jt + 2, set, 1); load_k_piece(jt + 4, set, 0); }
-            if (i == 2) { store_v_piece(jt + 2, set, 0); load_k_piece(jt + 4, set, 1); }
-            if (i == 3) store_v_piece(jt + 2, set, 1);
-            if (i == 4) load_v_piece(jt + 4, set, 0);
-            if (i == 5) load_v_piece(jt + 4, set, 1);
             ka = ka_n;
             va = va_n;
-            if (i == 3) __syncthreads();
+            if (i == 3) KVS_ATTN_BARRIER(4);              // tile jt+2 has landed; tile jt+3 may be in flight
+            if (i >= 4) stage_part(jt + 4, i - 4);
         }
     };
 
@@ -423,29 +437,28 @@ __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
     float l_tot[NB];
     for (int pass = 0; pass < 2; ++pass) {
         if (pass == 1) {
-            // exact row maxima: one tile at a time through the first ring stages
+            // exact row maxima: one tile at a time through the K ring
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb) m_ref[nb] = -INFINITY;
             for (int jt = t_lo; jt < t_hi; ++jt) {
-                Staged st;
-                load_tile(jt, st);
-                store_tile(0, st);
-                __syncthreads();
+                stage_tile(jt);
+                KVS_ATTN_BARRIER(0);
                 floatx16 s[NB];
-                qk(0, s);
+                qk(jt, s);
                 mask_tile(jt, s);
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb) m_ref[nb] = fmaxf(m_ref[nb], row_max(s[nb]));
-                __syncthreads();
             }
+            __syncthreads();   // every wave is done with the ring before the sweep refills it
         }
-        // the first two tiles into the rings, the next two on their way, scores of the first tile
-        Staged held, next;
-        if (t_lo < t_hi) { load_tile(t_lo, held); store_tile(t_lo, held); }
-        if (t_lo + 1 < t_hi) { load_tile(t_lo + 1, held); store_tile(t_lo + 1, held); }
-        if (t_lo + 2 < t_hi) load_tile(t_lo + 2, held);
-        if (t_lo + 3 < t_hi) load_tile(t_lo + 3, next);
-        __syncthreads();
+        // Invariant at the top of step j, in either loop: the loads of tiles j .. j+3 have been sent
+        // (where those tiles exist; the pipelined loop also sends tiles past the piece, which nothing
+        // reads), tiles j and j+1 are visible to every wave, and the barrier of step j makes tile j+2
+        // visible.  The loads of tile j+4 go out after that barrier.
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            if (t_lo + k < t_hi) stage_tile(t_lo + k);
+        KVS_ATTN_BARRIER(0);
         floatx16 s_cur[NB], s_nxt[NB];
         qk(t_lo, s_cur);
         if (pass == 0) {
@@ -463,59 +476,51 @@ __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
             for (int nb = 0; nb < NB; ++nb) o_acc[db][nb] = zero;
 
         int jt = t_lo;
-        // Fast sweep over the tiles that need no causal compare for any row of this wave and whose
-        // look-ahead tiles lie wholly inside the context.  Each wave leaves it at its own point and
-        // finishes in the general loop below: both write the same tile into the rings at the start
-        // of the same step and hit one barrier per step, so the waves of a workgroup may sit in
-        // different loops.  Tiles past the last one may get staged here; nothing reads them.
+        // Pipelined sweep over the tiles whose look-ahead tiles lie wholly inside the context.  Each
+        // wave leaves it at its own point and finishes in the general loop below: both send the same
+        // tile's loads in the same step and hit one barrier per step, so the waves of a workgroup
+        // may sit in different loops.
         const int j_unmasked = (pmin + 1) / BN;     // tiles 0 .. j_unmasked-1: every key <= pmin
         const int j_inside = ctx_len / BN;          // tiles 0 .. j_inside-1 need no row clamp
         if (t_lo + 3 <= t_hi && t_lo + 7 <= j_inside) {
             // the first step has no earlier tile to multiply: scores of the second tile, softmax of the first
             u32x4_t p_a[NB][2], p_b[NB][2];
-            store_tile(t_lo + 2, held);
-            load_tile_inside(t_lo + 4, held);
             qk(t_lo + 1, s_nxt);
             softmax(t_lo, s_cur, p_a);
-            __syncthreads();
+            KVS_ATTN_BARRIER(4);
+            stage_tile_inside(t_lo + 4);
             // K of the third tile, V of the first
-            u32x4_t ka = *reinterpret_cast<const u32x4_t *>(k_ring + ((t_lo + 2) & (K_RING - 1)) * K_TILE + k_read_off);
-            u32x4_t va = read_vt(v_ring + (t_lo & (V_RING - 1)) * V_TILE + v_read_off, 0, 0);
-            // two steps per trip so that the score, weight and staging buffers swap roles without copies
+            u32x4_t ka = read_k(k_slot(t_lo + 2), 0);
+            u32x4_t va = read_vt(v_slot(t_lo), 0, 0);
+            // two steps per trip so that the score and weight buffers swap roles without copies
             for (jt = t_lo + 1; jt + 1 < min(j_unmasked, t_hi) && jt + 5 < j_inside; jt += 2) {
-                fast_step(std::false_type{}, jt, s_nxt, s_cur, p_a, p_b, next, ka, va);
-                fast_step(std::false_type{}, jt + 1, s_cur, s_nxt, p_b, p_a, held, ka, va);
+                fast_step(std::false_type{}, jt, s_nxt, s_cur, p_a, p_b, ka, va);
+                fast_step(std::false_type{}, jt + 1, s_cur, s_nxt, p_b, p_a, ka, va);
             }
             // the tiles around the wave's own positions, same pipeline with the causal compare
             for (; jt + 1 < t_hi && jt + 5 < j_inside; jt += 2) {
-                fast_step(std::true_type{}, jt, s_nxt, s_cur, p_a, p_b, next, ka, va);
-                fast_step(std::true_type{}, jt + 1, s_cur, s_nxt, p_b, p_a, held, ka, va);
+                fast_step(std::true_type{}, jt, s_nxt, s_cur, p_a, p_b, ka, va);
+                fast_step(std::true_type{}, jt + 1, s_cur, s_nxt, p_b, p_a, ka, va);
             }
             pv_product(jt - 1, p_a);
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb) s_cur[nb] = s_nxt[nb];
-            const Staged t = held;   // an odd number of steps so far: tile jt+2 sits in `next`
-            held = next;
-            next = t;
         }
-        // general loop; invariant at the top: s_cur = scores of tile jt, `held` carries tile jt+2 and
-        // `next` tile jt+3 (where those exist)
+        // general loop; s_cur = scores of tile jt
         for (; jt < t_hi; ++jt) {
-            if (jt + 2 < t_hi) store_tile(jt + 2, held);
-            if (jt + 4 < t_hi) load_tile(jt + 4, held);
             // scores of the next tile first (past the last tile the slot holds stale data and the
             // result is discarded)
             qk(jt + 1, s_nxt);
             u32x4_t pop[NB][2];
             softmax(jt, s_cur, pop);
             pv_product(jt, pop);
-            __syncthreads();
+            KVS_ATTN_BARRIER(0);
+            if (jt + 4 < t_hi) stage_tile(jt + 4);
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb) s_cur[nb] = s_nxt[nb];
-            const Staged t = held;
-            held = next;
-            next = t;
         }
+        // nothing may still be on its way into LDS when the rings are reused or the workgroup ends
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
         bool bad = false;
 #pragma unroll
@@ -654,7 +659,7 @@ kvs_status launch_attention_mfma2(const kvs_shape *shape, const AttnBatch &bd, c
     const int64_t tiles = build_attn_tiles(shape, bd, ROWS, td);
     if (tiles < 0) return fail(KVS_EINVAL, "kvs_partial_attention: too many row tiles");
     if (tiles == 0) return KVS_OK;
-    const size_t lds_bytes = LDS_ELEMS * sizeof(uint16_t);
+    const size_t lds_bytes = LDS_BYTES;
     const float scale_log2 = scale * 1.4426950408889634f;
     if (n_splits <= 1 || !workspace) {
         const dim3 grid((unsigned)(tiles * shape->n_kv_heads));
