@@ -22,16 +22,19 @@
 //   * the score MFMAs of tile j+1        (K tile j+1 from LDS, Q from registers),
 //   * the PV MFMAs of tile j-1           (V tile j-1 from LDS, P of tile j-1 from registers),
 //   * the softmax of tile j              (vector instructions only),
-// so every MFMA of the step has vector work that can run beside it, and the staging of tile j+2
-// (registers -> LDS) and tile j+4 (global -> registers) is spread over the step one instruction at
-// a time: a burst of LDS writes or global loads holds up the MFMAs behind it.  Tiles that need the
-// causal compare go through the same pipeline with two more vector instructions per score.
+// so every MFMA of the step has vector work that can run beside it.  Tiles that need the causal
+// compare go through the same pipeline with two more vector instructions per score.
 //
-// LDS: K ring of four tiles, V ring of eight.  One barrier per step, placed in the middle of the
-// step: the rings are deep enough that a slot is rewritten only two barriers after its last
-// reader, so no wave ever waits at a step boundary and the LDS operands of a step's first MFMAs are
-// fetched at the end of the step before.  Global loads use buffer instructions with scalar tile
-// offsets, so the loop carries no per-lane address arithmetic.
+// Staging.  K and V tiles go from global memory straight into LDS (buffer loads with the LDS
+// flag): no staging registers, no LDS store instructions, nothing passing through the vector
+// register file.  Measured on a replica of the step, register staging (4 loads + 4 LDS stores per
+// wave and step) cost 28 % on top of the step without any staging; the direct loads cost nothing
+// measurable.  LDS holds a K ring of four tiles and a V ring of eight, unpadded and XOR-swizzled
+// per 16-byte piece.  The loads of tile j+4 go out in the second half of step j, one instruction
+// per slice; the one barrier per step sits in the middle of the step and is also where each wave
+// waits for its own loads of tile j+2.  The rings are deep enough that a slot is refilled only
+// after every wave has passed a barrier since its last reader, so no wave waits at a step boundary
+// and the LDS operands of a step's first MFMAs are fetched at the end of the step before.
 #include "attention.h"
 
 #include <math.h>
@@ -52,8 +55,17 @@ constexpr int WROWS = 32 * NB;
 constexpr int ROWS = NWAVES * WROWS;   // 256 rows per workgroup
 constexpr int ROW_B = D * 2;            // bytes of one K or V row of one head
 constexpr int TILE_B = BN * ROW_B;      // a K or V tile in LDS: 32 rows of 256 B, 16-byte pieces XOR-swizzled
-constexpr int K_RING = 4;   // tiles; see the slot argument at stage_tile
-constexpr int V_RING = 8;
+// Tiles are requested AHEAD steps before their softmax; the barrier of a step lets the
+// 4 * (AHEAD - 3) staging instructions of the younger tiles stay in flight.
+#ifndef KVS_ATTN_AHEAD
+#define KVS_ATTN_AHEAD 4
+#define KVS_ATTN_IN_FLIGHT 4
+#endif
+constexpr int AHEAD = KVS_ATTN_AHEAD;
+static_assert(KVS_ATTN_IN_FLIGHT == 4 * (AHEAD - 3), "staging instructions per tile and wave: 4");
+constexpr int K_RING = AHEAD <= 4 ? 4 : 8;   // tiles, >= AHEAD; see the slot argument at stage_part
+constexpr int V_RING = 8;                    // >= AHEAD + 2
+static_assert(K_RING >= AHEAD && V_RING >= AHEAD + 2, "ring depth");
 constexpr int LDS_BYTES = (K_RING + V_RING) * TILE_B;
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4_t v) { return __builtin_bit_cast(bf16x8, v); }
 
@@ -210,12 +222,13 @@ __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
     const uint32_t st_v_piece = (uint32_t)(st_pos ^ (2 * (st_row & 7))) * 16u;
     const uint32_t st_k_voff = (uint32_t)(lane >> 4) * row_bytes + st_k_piece;
     const uint32_t st_v_voff = (uint32_t)(lane >> 4) * row_bytes + st_v_piece;
-    // Slots.  Tile t goes to K slot t & 3 and V slot t & 7.  stage_part(t, .) is issued in the second
-    // half of step t-4, after that step's barrier.  K slot t & 3 held tile t-4, last read in step t-5,
-    // V slot t & 7 held tile t-8, last read in step t-7 (the general loop: t-8): every wave has passed
-    // the barrier of step t-4 since.  The tile must have landed by the barrier of step t-2 (its K is
-    // first read at the end of step t-2): each wave waits for its own parts there, allowing only the
-    // four instructions of tile t+1 to be still in flight.
+    // Slots.  Tile t goes to K slot t % K_RING and V slot t % V_RING.  stage_part(t, .) is issued in
+    // the second half of step t-AHEAD, after that step's barrier.  The K slot held tile t-K_RING, last
+    // read in step t-K_RING-1, the V slot tile t-V_RING, last read in step t-V_RING+1 (the general
+    // loop: t-V_RING): with K_RING >= AHEAD and V_RING >= AHEAD+2 every wave has passed a barrier
+    // since.  The tile must have landed by the barrier of step t-2 (its K is first read at the end of
+    // step t-2): each wave waits for its own parts there, allowing only the instructions of tiles
+    // t+1 .. t+AHEAD-3 to be still in flight.
     // The instruction is written out by hand: issued through the compiler's builtin it makes the
     // compiler wait for all outstanding loads before every later LDS read it cannot prove disjoint,
     // which would serialise the sweep on global-memory latency.  Here the waiting is done once per
@@ -257,7 +270,8 @@ __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
     // tracks it, oldest first); nothing else of the workgroup's LDS traffic needs ordering here: a
     // slot is only overwritten long after its last reader (above).  `in_flight` = staging
     // instructions of younger tiles that may still be outstanding.
-#define KVS_ATTN_BARRIER(in_flight) asm volatile("s_waitcnt vmcnt(" #in_flight ")\n\ts_barrier" ::: "memory")
+#define KVS_ATTN_BARRIER_(in_flight) asm volatile("s_waitcnt vmcnt(" #in_flight ")\n\ts_barrier" ::: "memory")
+#define KVS_ATTN_BARRIER(in_flight) KVS_ATTN_BARRIER_(in_flight)
 
     // ---- the three pieces of one tile's work ----------------------------------------------------------
     // K row fed to MFMA row ln: bits 2 and 3 swapped, so that accumulator entry r of a lane is key
@@ -365,13 +379,13 @@ __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
             }
     };
 
-    // One step of the pipelined sweep (tile jt+4 lies wholly inside the context; `masked` says whether
+    // One step of the pipelined sweep (tile jt+AHEAD lies wholly inside the context; `masked` says whether
     // tile jt needs the causal compare for this wave): scores of tile jt+1, softmax of tile jt, PV of
     // tile jt-1, written as eight slices of four MFMAs and four scores each, LDS operands fetched one
     // slice ahead (ka / va enter with slice 0's operands and leave with those of the next step).
-    // On entry tiles jt-1 .. jt+1 are in the LDS rings and tiles jt+2, jt+3 on their way, s_in holds
+    // On entry tiles jt-1 .. jt+1 are in the LDS rings and tiles jt+2 .. jt+AHEAD-1 on their way, s_in holds
     // the scores of tile jt and p_in the weights of tile jt-1.  The barrier in mid-step makes tile
-    // jt+2 visible; the second half sends out the loads of tile jt+4, one instruction per slice.
+    // jt+2 visible; the second half sends out the loads of tile jt+AHEAD, one instruction per slice.
     int key_lim[NB];   // a key of the tile is visible to the lane's query nb iff its (half-wave-relative) index <= this
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) key_lim[nb] = pos[nb] - 8 * hf;
@@ -421,8 +435,8 @@ __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
             o_acc[db][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(va), as_bf16x8(p_in[1][a]), o_acc[db][1], 0, 0, 0);
             ka = ka_n;
             va = va_n;
-            if (i == 3) KVS_ATTN_BARRIER(4);              // tile jt+2 has landed; tile jt+3 may be in flight
-            if (i >= 4) stage_part(jt + 4, i - 4);
+            if (i == 3) KVS_ATTN_BARRIER(KVS_ATTN_IN_FLIGHT);   // tile jt+2 has landed; younger ones may be in flight
+            if (i >= 4) stage_part(jt + AHEAD, i - 4);
         }
     };
 
@@ -451,12 +465,12 @@ __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
             }
             __syncthreads();   // every wave is done with the ring before the sweep refills it
         }
-        // Invariant at the top of step j, in either loop: the loads of tiles j .. j+3 have been sent
+        // Invariant at the top of step j, in either loop: the loads of tiles j .. j+AHEAD-1 have been sent
         // (where those tiles exist; the pipelined loop also sends tiles past the piece, which nothing
         // reads), tiles j and j+1 are visible to every wave, and the barrier of step j makes tile j+2
-        // visible.  The loads of tile j+4 go out after that barrier.
+        // visible.  The loads of tile j+AHEAD go out after that barrier.
 #pragma unroll
-        for (int k = 0; k < 4; ++k)
+        for (int k = 0; k < AHEAD; ++k)
             if (t_lo + k < t_hi) stage_tile(t_lo + k);
         KVS_ATTN_BARRIER(0);
         floatx16 s_cur[NB], s_nxt[NB];
@@ -482,23 +496,23 @@ __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
         // may sit in different loops.
         const int j_unmasked = (pmin + 1) / BN;     // tiles 0 .. j_unmasked-1: every key <= pmin
         const int j_inside = ctx_len / BN;          // tiles 0 .. j_inside-1 need no row clamp
-        if (t_lo + 3 <= t_hi && t_lo + 7 <= j_inside) {
+        if (t_lo + 3 <= t_hi && t_lo + AHEAD + 3 <= j_inside) {
             // the first step has no earlier tile to multiply: scores of the second tile, softmax of the first
             u32x4_t p_a[NB][2], p_b[NB][2];
             qk(t_lo + 1, s_nxt);
             softmax(t_lo, s_cur, p_a);
-            KVS_ATTN_BARRIER(4);
-            stage_tile_inside(t_lo + 4);
+            KVS_ATTN_BARRIER(KVS_ATTN_IN_FLIGHT);
+            stage_tile_inside(t_lo + AHEAD);
             // K of the third tile, V of the first
             u32x4_t ka = read_k(k_slot(t_lo + 2), 0);
             u32x4_t va = read_vt(v_slot(t_lo), 0, 0);
             // two steps per trip so that the score and weight buffers swap roles without copies
-            for (jt = t_lo + 1; jt + 1 < min(j_unmasked, t_hi) && jt + 5 < j_inside; jt += 2) {
+            for (jt = t_lo + 1; jt + 1 < min(j_unmasked, t_hi) && jt + AHEAD + 1 < j_inside; jt += 2) {
                 fast_step(std::false_type{}, jt, s_nxt, s_cur, p_a, p_b, ka, va);
                 fast_step(std::false_type{}, jt + 1, s_cur, s_nxt, p_b, p_a, ka, va);
             }
             // the tiles around the wave's own positions, same pipeline with the causal compare
-            for (; jt + 1 < t_hi && jt + 5 < j_inside; jt += 2) {
+            for (; jt + 1 < t_hi && jt + AHEAD + 1 < j_inside; jt += 2) {
                 fast_step(std::true_type{}, jt, s_nxt, s_cur, p_a, p_b, ka, va);
                 fast_step(std::true_type{}, jt + 1, s_cur, s_nxt, p_b, p_a, ka, va);
             }
@@ -515,7 +529,7 @@ __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
             softmax(jt, s_cur, pop);
             pv_product(jt, pop);
             KVS_ATTN_BARRIER(0);
-            if (jt + 4 < t_hi) stage_tile(jt + 4);
+            if (jt + AHEAD < t_hi) stage_tile(jt + AHEAD);
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb) s_cur[nb] = s_nxt[nb];
         }
