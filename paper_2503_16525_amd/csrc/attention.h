@@ -37,11 +37,7 @@ int64_t build_attn_tiles(const kvs_shape *shape, const AttnBatch &bd, int rows_p
 constexpr size_t kAttnPartBytesPerSlot = 128 * sizeof(float) + 4 * sizeof(float);
 constexpr int kAttnSplitMax = 16;
 constexpr int kAttnSplitCus = 256;         // compute units a round of pieces is spread over
-constexpr int kAttnSplitBelowWgs = 384;    // launches with fewer workgroups than this get split ...
-#ifndef KVS_ATTN_SPLIT_TARGET
-#define KVS_ATTN_SPLIT_TARGET 768
-#endif
-constexpr int kAttnSplitTargetWgs = KVS_ATTN_SPLIT_TARGET;   // ... into about this many workgroup-pieces
+constexpr int kAttnSplitBelowWgs = 384;    // launches with fewer workgroups than this get split
 // out = sum_s w_s O_s / sum_s w_s l_s with w_s = 2^(m_s - max m); pieces with l = 0 drop out;
 // the log-sum-exp comes from the unrounded sums
 kvs_status launch_attention_merge(int64_t n_rows, int n_splits, const float *part_o, const float4 *part_ml,

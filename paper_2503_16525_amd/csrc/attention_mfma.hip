@@ -520,8 +520,8 @@ kvs_status launch_attention_mfma(const kvs_shape *shape, const AttnBatch &bd, in
     const int splits2 = workspace ? attention_mfma2_splits(shape, bd, workspace_bytes, &chunk2) : 1;
     const bool fills = big_tiles * shape->n_kv_heads >= kAttnBigTileMinGrid;
     const bool dense_tiles = rows * 10 >= big_tiles * 256 * 6;
-    // (below ~160 such tiles the per-workgroup start-up of the large kernel costs more than it gains)
-    const bool big = forced ? forced == 2 : fills || (splits2 >= 2 && dense_tiles && big_tiles * shape->n_kv_heads >= 160);
+    // (below ~100 such tiles the per-workgroup start-up of the large kernel costs more than it gains)
+    const bool big = forced ? forced == 2 : fills || (splits2 >= 2 && dense_tiles && big_tiles * shape->n_kv_heads >= 96);
     if (big)
         return launch_attention_mfma2(shape, bd, q_sel, sel_pos, k_cache, v_cache, scale, out, lse_out, workspace,
                                       fills && !forced ? 1 : splits2, chunk2, st);
@@ -535,7 +535,7 @@ size_t attention_workspace_bytes(const kvs_shape *shape, int32_t batch, int64_t 
     // kSplitMaxWgs workgroup-pieces of 32*KVS_ATTN_NWAVES rows each exist
     const int64_t rows = n_sel_total * shape->n_q_heads;
     int64_t slots = rows * kSplitMax;
-    // (the 256-row kernel: at most kAttnSplitTargetWgs + kAttnSplitBelowWgs pieces of 256 rows)
+    // (the 256-row kernel: fewer than kAttnSplitBelowWgs tiles of 256 rows, up to kSplitMax pieces each)
     const int64_t cap = (int64_t)(kSplitMaxWgs + kSplitBelowWgs) * 256 + (int64_t)batch * 256 * kSplitMax;
     if (slots > cap) slots = cap;
     return (size_t)slots * kPartBytesPerSlot + 256;
