@@ -24,6 +24,14 @@ FLAGS = [
 ]
 
 
+# per-file additions: the 256-row attention kernel wants its score tiles in vector registers (the
+# softmax reads them there); by default the compiler puts every MFMA result into accumulation
+# registers and copies the scores out one by one
+EXTRA_FLAGS = {
+    "attention_mfma2.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
+}
+
+
 def sources():
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
 
@@ -33,7 +41,7 @@ def _compile(src: str, force: bool) -> str:
     deps = [src] + glob.glob(os.path.join(CSRC, "*.h")) + glob.glob(os.path.join(INCLUDE, "*.h"))
     if not force and os.path.exists(obj) and all(os.path.getmtime(obj) >= os.path.getmtime(d) for d in deps):
         return obj
-    cmd = [HIPCC] + FLAGS + ["-c", src, "-o", obj]
+    cmd = [HIPCC] + FLAGS + EXTRA_FLAGS.get(os.path.basename(src), []) + ["-c", src, "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     msgs = "\n".join(l for l in (r.stdout + r.stderr).splitlines()
                      if "is not a recognized feature for this target" not in l)
