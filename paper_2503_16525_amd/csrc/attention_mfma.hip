@@ -520,8 +520,8 @@ kvs_status launch_attention_mfma(const kvs_shape *shape, const AttnBatch &bd, in
     const int splits2 = workspace ? attention_mfma2_splits(shape, bd, workspace_bytes, &chunk2) : 1;
     const bool fills = big_tiles * shape->n_kv_heads >= kAttnBigTileMinGrid;
     const bool dense_tiles = rows * 10 >= big_tiles * 256 * 6;
-    // (below ~100 such tiles the per-workgroup start-up of the large kernel costs more than it gains)
-    const bool big = forced ? forced == 2 : fills || (splits2 >= 2 && dense_tiles && big_tiles * shape->n_kv_heads >= 96);
+    // (below ~50 such tiles the per-workgroup start-up of the large kernel costs more than it gains)
+    const bool big = forced ? forced == 2 : fills || (splits2 >= 2 && dense_tiles && big_tiles * shape->n_kv_heads >= 48);
     if (big)
         return launch_attention_mfma2(shape, bd, q_sel, sel_pos, k_cache, v_cache, scale, out, lse_out, workspace,
                                       fills && !forced ? 1 : splits2, chunk2, st);

@@ -641,8 +641,8 @@ int attention_mfma2_splits(const kvs_shape *shape, const AttnBatch &bd, size_t w
     if (s_max < 2) return 1;
     // Pieces run in rounds of one per compute unit and every piece costs about its chunk length, so
     // the chunk decides how many pieces exist and how full the last round is.  The positions are on
-    // the device; assume they are spread evenly over each context (row tile t of T reaches
-    // (t+1)/T of it) and take the chunk with the shortest predicted time.  A wrong guess costs speed
+    // the device; assume they are spread evenly over each context (the last of n rows
+    // of a tile that ends at row r reaches r/n of it) and take the chunk with the shortest predicted time.  A wrong guess costs speed
     // only.
     const int64_t c_min = (ctx_tiles + s_max - 1) / s_max;
     int64_t best_c = c_min;
@@ -650,11 +650,17 @@ int attention_mfma2_splits(const kvs_shape *shape, const AttnBatch &bd, size_t w
     for (int64_t c = c_min; c <= ctx_tiles; c += (c < 64 ? 4 : 8)) {
         int64_t pieces = 0;
         for (int i = 0; i < bd.n_req; ++i) {
-            const int64_t T = ((bd.cu_sel[i + 1] - bd.cu_sel[i]) * grp + ROWS - 1) / ROWS;
+            const int64_t n_rows = (bd.cu_sel[i + 1] - bd.cu_sel[i]) * grp;
+            const int64_t T = (n_rows + ROWS - 1) / ROWS;
             const int64_t L = (bd.ctx_len[i] + BN - 1) / BN;
-            for (int64_t t = 0; t < T; ++t) pieces += (L * (t + 1) / T + c - 1) / c;
+            for (int64_t t = 0; t < T; ++t) {
+                const int64_t last_row = (t + 1) * ROWS < n_rows ? (t + 1) * ROWS : n_rows;   // the tile's last row
+                pieces += (L * last_row / n_rows + c - 1) / c;
+            }
         }
-        pieces *= shape->n_kv_heads;
+        // real selections are not spread that evenly: leave 8 % of head-room, or a round that looked
+        // exactly full spills a few pieces into one more
+        pieces = (pieces * shape->n_kv_heads * 27 + 24) / 25 + shape->n_kv_heads;
         const int64_t rounds = (pieces + kAttnSplitCus - 1) / kAttnSplitCus;
         const double time = (double)rounds * ((double)c + 3.0);     // ~3 steps' worth of start-up per piece
         if (time < best_t) { best_t = time; best_c = c; }
