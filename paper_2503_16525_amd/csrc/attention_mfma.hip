@@ -510,18 +510,21 @@ kvs_status launch_attention_mfma(const kvs_shape *shape, const AttnBatch &bd, in
     }();
     const int grp = shape->n_q_heads / shape->n_kv_heads;
     int64_t big_tiles = 0, rows = 0;
+    // the large kernel addresses a request's keys with 32-bit byte offsets from its first token
+    bool fits32 = true;
     for (int i = 0; i < bd.n_req; ++i) {
         big_tiles += ((bd.cu_sel[i + 1] - bd.cu_sel[i]) * grp + 255) / 256;
         rows += (bd.cu_sel[i + 1] - bd.cu_sel[i]) * grp;
+        fits32 = fits32 && bd.ctx_len[i] * (int64_t)shape->n_kv_heads * D * 2 < (int64_t)1 << 32;
     }
     // with fewer 256-row tiles than compute units the large kernel still wins if the caller's
     // workspace lets it cut the key ranges and its tiles are not mostly padding
     int chunk2 = 0;
-    const int splits2 = workspace ? attention_mfma2_splits(shape, bd, workspace_bytes, &chunk2) : 1;
+    const int splits2 = workspace && fits32 ? attention_mfma2_splits(shape, bd, workspace_bytes, &chunk2) : 1;
     const bool fills = big_tiles * shape->n_kv_heads >= kAttnBigTileMinGrid;
     const bool dense_tiles = rows * 10 >= big_tiles * 256 * 6;
     // (below ~50 such tiles the per-workgroup start-up of the large kernel costs more than it gains)
-    const bool big = forced ? forced == 2 : fills || (splits2 >= 2 && dense_tiles && big_tiles * shape->n_kv_heads >= 48);
+    const bool big = fits32 && (forced ? forced == 2 : fills || (splits2 >= 2 && dense_tiles && big_tiles * shape->n_kv_heads >= 48));
     if (big)
         return launch_attention_mfma2(shape, bd, q_sel, sel_pos, k_cache, v_cache, scale, out, lse_out, workspace,
                                       fills && !forced ? 1 : splits2, chunk2, st);

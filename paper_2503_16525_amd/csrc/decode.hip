@@ -67,7 +67,10 @@ __global__ __launch_bounds__(kThreads) void decode_logits_kernel(
 {
     constexpr int EPL = DTYPE == KVS_BF16 ? 8 : 4;
     constexpr int D = LPH * EPL;
-    constexpr int UNROLL = 4;
+#ifndef KVS_DEC_UNROLL
+#define KVS_DEC_UNROLL 8
+#endif
+    constexpr int UNROLL = KVS_DEC_UNROLL;
     extern __shared__ float lds[];
     float *lg_s = lds;                             // [n_q_heads][kTok]
     float *q_s = lds + n_q_heads * kTok;           // [n_q_heads][D], pre-multiplied by scale (GRP == 0 only)
