@@ -38,19 +38,36 @@ constexpr size_t kAttnPartBytesPerSlot = 128 * sizeof(float) + 4 * sizeof(float)
 constexpr int kAttnSplitMax = 16;
 constexpr int kAttnSplitCus = 256;         // compute units a round of pieces is spread over
 constexpr int kAttnSplitBelowWgs = 384;    // launches with fewer workgroups than this get split
+constexpr int kAttnSmallChunk = 32;        // key tiles per small piece at the bottom of the context
+constexpr int kAttnSmallPieces = 2;        // how many of them
+constexpr double kAttnPieceOverhead = 30.0;   // start-up, write-out and merge share of a piece, in key tiles
+constexpr double kAttnRoundFill = 0.92;       // pieces per round / compute units the plan aims for
 // out = sum_s w_s O_s / sum_s w_s l_s with w_s = 2^(m_s - max m); pieces with l = 0 drop out;
 // the log-sum-exp comes from the unrounded sums
 kvs_status launch_attention_merge(int64_t n_rows, int n_splits, const float *part_o, const float4 *part_ml,
                                   uint16_t *out, float *lse_out, hipStream_t st);
 
-// 64 query rows per wave (two MFMAs per LDS operand), one wave per SIMD, 256-row tiles.  n_splits > 1
-// (from attention_mfma2_splits, which needs the workspace size) cuts the key range into pieces of
-// split_chunk key tiles.
-int attention_mfma2_splits(const kvs_shape *shape, const AttnBatch &bd, size_t workspace_bytes, int *split_chunk);
+// What the host fixes for a split launch of the 256-row kernel: piece slots per row tile (1: no
+// cutting, nothing else is read), the longest context in key tiles, and the small pieces at the
+// bottom of the context (n_small of small_chunk key tiles).  The size of the large pieces above
+// them is chosen on the device, from the positions; pieces are started from the top of the context
+// down, so the short ones at the bottom come last and level out the finish times.
+struct AttnSplitPlan {
+    int n_splits;
+    int ctx_tiles;
+    int small_chunk;
+    int n_small;
+};
+// the device-side plan and the list of piece ids (16 bits each, kAttnSplitMax per row tile, fewer
+// than kAttnSplitBelowWgs row tiles), after the pieces in the workspace
+constexpr size_t kAttnPlanBytes = 16 + 2 * (size_t)kAttnSplitMax * kAttnSplitBelowWgs;
+// 64 query rows per wave (two MFMAs per LDS operand), one wave per SIMD, 256-row tiles.  The plan
+// comes from attention_mfma2_plan, which needs the workspace size.
+AttnSplitPlan attention_mfma2_plan(const kvs_shape *shape, const AttnBatch &bd, size_t workspace_bytes);
 kvs_status launch_attention_mfma2(const kvs_shape *shape, const AttnBatch &bd, const void *q_sel,
                                   const int32_t *sel_pos, const void *k_cache, const void *v_cache,
-                                  float scale, void *out, float *lse_out, void *workspace, int n_splits,
-                                  int split_chunk, hipStream_t st);
+                                  float scale, void *out, float *lse_out, void *workspace,
+                                  const AttnSplitPlan &plan, hipStream_t st);
 
 kvs_status launch_attention_valu(const kvs_shape *shape, const AttnBatch &bd, int64_t n_sel,
                                  const void *q_sel, const int32_t *sel_pos, const void *k_cache,

@@ -519,15 +519,17 @@ kvs_status launch_attention_mfma(const kvs_shape *shape, const AttnBatch &bd, in
     }
     // with fewer 256-row tiles than compute units the large kernel still wins if the caller's
     // workspace lets it cut the key ranges and its tiles are not mostly padding
-    int chunk2 = 0;
-    const int splits2 = workspace && fits32 ? attention_mfma2_splits(shape, bd, workspace_bytes, &chunk2) : 1;
+    AttnSplitPlan plan2 = {1, 0, 0, 0};
+    if (workspace && fits32) plan2 = attention_mfma2_plan(shape, bd, workspace_bytes);
+    const int splits2 = plan2.n_splits;
     const bool fills = big_tiles * shape->n_kv_heads >= kAttnBigTileMinGrid;
     const bool dense_tiles = rows * 10 >= big_tiles * 256 * 6;
     // (below ~50 such tiles the per-workgroup start-up of the large kernel costs more than it gains)
     const bool big = fits32 && (forced ? forced == 2 : fills || (splits2 >= 2 && dense_tiles && big_tiles * shape->n_kv_heads >= 48));
-    if (big)
-        return launch_attention_mfma2(shape, bd, q_sel, sel_pos, k_cache, v_cache, scale, out, lse_out, workspace,
-                                      fills && !forced ? 1 : splits2, chunk2, st);
+    if (big) {
+        if (fills && !forced) plan2 = {1, 0, 0, 0};
+        return launch_attention_mfma2(shape, bd, q_sel, sel_pos, k_cache, v_cache, scale, out, lse_out, workspace, plan2, st);
+    }
     return launch_mfma_variant<KVS_ATTN_NWAVES>(shape, bd, q_sel, sel_pos, k_cache, v_cache, scale, out, lse_out,
                                                 workspace, workspace_bytes, st);
 }
@@ -541,7 +543,7 @@ size_t attention_workspace_bytes(const kvs_shape *shape, int32_t batch, int64_t 
     // (the 256-row kernel: fewer than kAttnSplitBelowWgs tiles of 256 rows, up to kSplitMax pieces each)
     const int64_t cap = (int64_t)(kSplitMaxWgs + kSplitBelowWgs) * 256 + (int64_t)batch * 256 * kSplitMax;
     if (slots > cap) slots = cap;
-    return (size_t)slots * kPartBytesPerSlot + 256;
+    return (size_t)slots * kPartBytesPerSlot + kAttnPlanBytes + 256;
 }
 
 } // namespace kvs

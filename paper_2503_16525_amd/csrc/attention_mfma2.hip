@@ -93,19 +93,21 @@ __device__ long long kvs_diag_clk[4096];
 
 
 // WANT_LSE: additionally keep the unrounded sum of weights, from which the log-sum-exp is reported.
-// SPLIT: the key range is cut into pieces of split_chunk key tiles (at most n_splits per row tile)
-// handled by different workgroups (launches with few row tiles over long contexts would otherwise
-// leave most of the chip idle); every piece writes its unnormalised accumulators and (reference,
-// sums) to the workspace and the merge kernel combines them.  The pieces are absolute key ranges,
-// the same for every row tile, and the grid runs through them piece by piece: the workgroups that
-// are resident together read the same stretch of K and V, which then stays in L2.
+// SPLIT: the key range is cut into pieces handled by different workgroups (launches with few row
+// tiles over long contexts would otherwise leave most of the chip idle); at most n_splits slots
+// per row tile, the sizes and the order of the pieces come from what attn_plan_kernel leaves in
+// device memory.  Every piece writes its unnormalised accumulators and (reference, sums) to the
+// workspace and the merge kernel combines them.  The pieces are absolute key ranges, the same for
+// every row tile, and the list runs through them range by range: the workgroups that are resident
+// together read the same stretch of K and V, which then stays in L2.
 template <bool WANT_LSE, bool SPLIT>
 __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
     const AttnTiles td, int n_q_heads, int n_kv_heads, int total_tiles,
     const uint16_t *__restrict__ q_sel, const int32_t *__restrict__ sel_pos,
     const uint16_t *__restrict__ k_cache, const uint16_t *__restrict__ v_cache,
     float scale_log2, uint16_t *__restrict__ out, float *__restrict__ lse_out,
-    int n_splits, int split_chunk, float *__restrict__ part_o, float4 *__restrict__ part_ml)
+    int n_splits, const int4 *__restrict__ split_plan, const uint16_t *__restrict__ piece_list,
+    float *__restrict__ part_o, float4 *__restrict__ part_ml)
 {
     extern __shared__ __attribute__((aligned(16))) uint16_t lds[];   // K ring, then V^T ring
     __shared__ int wg_max_pos[NWAVES];
@@ -119,8 +121,11 @@ __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
     // ---- which (request, kv head, row tile) -----------------------------------------------------
     const int g = blockIdx.x % n_kv_heads;
     const int rest = (int)(blockIdx.x / n_kv_heads);
-    const int split = SPLIT ? rest / total_tiles : 0;
-    const int tile_lin = total_tiles - 1 - (SPLIT ? rest % total_tiles : rest);
+    // split launches walk the list of pieces the plan kernel wrote: the pieces that have keys first,
+    // from the top of the context down, then the empty ones (which only mark their slot)
+    const int piece = SPLIT ? piece_list[rest] : rest;
+    const int split = SPLIT ? piece / total_tiles : 0;
+    const int tile_lin = total_tiles - 1 - (SPLIT ? piece % total_tiles : rest);
     int b = 0;
     while (b + 1 < td.n_req && tile_lin >= td.tile_begin[b + 1]) ++b;
     const int tile = tile_lin - td.tile_begin[b];
@@ -129,6 +134,22 @@ __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
     const int n_rows = (int)(td.cu_sel[b + 1] - sel0) * grp;
     const int ctx_len = td.ctx_len[b];
     const int64_t ctx_off = td.ctx_off[b];
+
+    // the plan: (pieces per row tile in use, key tiles per large piece, per small piece, small pieces)
+    int4 plan = make_int4(1, 0, 0, 0);
+    if (SPLIT) {
+        plan = *split_plan;
+        if (split >= plan.x) {   // a piece slot the plan does not use: mark it empty for the merge
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+                const int rq = tile * ROWS + wave * WROWS + nb * 32 + ln;
+                const int t_sel = rq / grp, hh = rq - t_sel * grp;
+                if (rq < n_rows && hf == 0)
+                    part_ml[((sel0 + t_sel) * n_q_heads + g * grp + hh) * (int64_t)n_splits + split] = make_float4(-1.0e30f, 0.f, 0.f, 0.f);
+            }
+            return;
+        }
+    }
 
     // this lane's query rows, one per 32-row block (both half-waves hold the same queries)
     bool row_ok[NB];
@@ -177,8 +198,15 @@ __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
     for (int w = 1; w < NWAVES; ++w) wg_pmax = max(wg_pmax, wg_max_pos[w]);
     const int n_kv_tiles = wg_pmax / BN + 1;
     // this workgroup's share of the key tiles: [t_lo, t_hi)
-    const int t_lo = SPLIT ? min(n_kv_tiles, split * split_chunk) : 0;
-    const int t_hi = SPLIT ? min(n_kv_tiles, t_lo + split_chunk) : n_kv_tiles;
+    int t_lo = 0, t_hi = n_kv_tiles;
+    if (SPLIT) {
+        // piece 0 is the top of the context; counted from the bottom, the first plan.w pieces are
+        // plan.z key tiles long and the others plan.y
+        const int j = plan.x - 1 - split;
+        const int lo = j < plan.w ? j * plan.z : plan.w * plan.z + (j - plan.w) * plan.y;
+        t_lo = min(n_kv_tiles, lo);
+        t_hi = min(n_kv_tiles, lo + (j < plan.w ? plan.z : plan.y));
+    }
     if (SPLIT && t_lo >= t_hi) {   // nothing of this tile in this key range: mark the piece empty
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb)
@@ -449,7 +477,13 @@ __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
     // overflow.  Real attention logits do not do that, so pass 1 is a correctness net.
     __shared__ int redo_flag;
     float l_tot[NB];
+#ifdef KVS_DIAG_CLOCK
+    int diag_pass = 0;
+#endif
     for (int pass = 0; pass < 2; ++pass) {
+#ifdef KVS_DIAG_CLOCK
+        diag_pass = pass;
+#endif
         if (pass == 1) {
             // exact row maxima: one tile at a time through the K ring
 #pragma unroll
@@ -554,7 +588,7 @@ __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
     if (tid == 0 && blockIdx.x < 1024) {
         kvs_diag_clk[4 * blockIdx.x] = clock64() - diag_t0;
         kvs_diag_clk[4 * blockIdx.x + 1] = wall_clock64() - diag_w0;
-        kvs_diag_clk[4 * blockIdx.x + 2] = n_kv_tiles;
+        kvs_diag_clk[4 * blockIdx.x + 2] = (t_hi - t_lo) + 4096 * max(0, t_hi - max(t_lo, (pmin + 1) / BN)) + 4096 * 4096 * (long long)diag_pass;
         kvs_diag_clk[4 * blockIdx.x + 3] = diag_w0;
     }
 #endif
@@ -600,11 +634,123 @@ __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
 } // namespace
 
 namespace {
+
+// Plans a split launch on the device, where the positions are: the size of the large pieces and
+// the order in which the workgroups take the pieces.
+//
+// Size.  The large pieces run in rounds of one per compute unit, each round as long as the chunk,
+// and a piece costs about piece_overhead key tiles on top of its own: so for 1, 2, ... rounds the
+// best chunk is the smallest one whose pieces just fit, and the round count with the shortest
+// predicted time wins (fewer, longer rounds win ties through the overhead).  round_fill < 1 leaves
+// head-room.  Thread i tries chunk c_min + i * step over the lengths of all row tiles (taken from
+// each tile's last row, i.e. exact for positions in ascending order; any other order costs speed
+// only: the attention kernel finds its own key range).
+//
+// Order.  piece id = split * total_tiles + (row tiles from the last one down).  A workgroup that
+// finds its piece empty still holds a compute unit for a few microseconds, and the dispatcher
+// hands out workgroups strictly in order, so empty pieces in between starve the pieces behind
+// them: the list names the pieces with keys first and all empty slots after them.
+constexpr int PLAN_NT = 256;
+constexpr int PLAN_MAX_TILES = kAttnSplitBelowWgs;   // a split launch has fewer row tiles than this
+constexpr int PLAN_MAX_ROUNDS = 4;
+__global__ __launch_bounds__(PLAN_NT) void attn_plan_kernel(
+    const AttnTiles td, int grp, int n_kv_heads, int total_tiles, const int32_t *__restrict__ sel_pos,
+    int s_max, int ctx_tiles, int small_chunk, int n_small, float round_fill, float piece_overhead,
+    int forced_chunk, int4 *__restrict__ plan, uint16_t *__restrict__ piece_list)
+{
+    __shared__ int len[PLAN_MAX_TILES];       // key tiles of each row tile
+    __shared__ int first_fit[PLAN_MAX_ROUNDS];
+    __shared__ int4 chosen;
+    __shared__ int wave_total[PLAN_NT / 64];
+    const int tid = threadIdx.x;
+    const int bottom = n_small * small_chunk;
+    for (int t = tid; t < total_tiles; t += PLAN_NT) {
+        int b = 0;
+        while (b + 1 < td.n_req && t >= td.tile_begin[b + 1]) ++b;
+        const int tile = t - td.tile_begin[b];
+        const int n_rows = (int)(td.cu_sel[b + 1] - td.cu_sel[b]) * grp;
+        const int last_row = min((tile + 1) * ROWS, n_rows) - 1;
+        int p = sel_pos[td.cu_sel[b] + last_row / grp];
+        p = min(max(p, 0), td.ctx_len[b] - 1);
+        len[t] = p / BN + 1;
+    }
+    if (tid < PLAN_MAX_ROUNDS) first_fit[tid] = 0x7fffffff;
+    __syncthreads();
+    const int c_min = max(1, (ctx_tiles - bottom + (s_max - n_small) - 1) / (s_max - n_small));
+    const int c_max = max(c_min, ctx_tiles - bottom);
+    const int step = (c_max - c_min + PLAN_NT - 1) / PLAN_NT;
+    const int c = c_min + tid * step;
+    const bool tries = c <= c_max && (step > 0 || tid == 0);
+    int pieces = 0x7fffffff;
+    if (tries) {
+        const float rc = 1.0f / (float)c;
+        pieces = 0;
+        for (int t = 0; t < total_tiles; ++t) pieces += (int)ceilf((float)max(0, len[t] - bottom) * rc - 1.0e-4f);
+        pieces *= n_kv_heads;
+    }
+    // the piece count falls as the chunk grows, so per round count the first thread that fits is
+    // the answer: one LDS atomic per wave instead of one per thread
+    for (int r = 0; r < PLAN_MAX_ROUNDS; ++r) {
+        const bool fits = tries && (float)pieces <= round_fill * (float)(kAttnSplitCus * (r + 1));
+        const unsigned long long m = __ballot(fits);
+        if (m != 0 && (tid & 63) == __ffsll((long long)m) - 1) atomicMin(&first_fit[r], c);
+    }
+    __syncthreads();
+    if (tid == 0) {
+        int best_c = c_max;                 // one large piece per row tile always "fits"
+        float best_t = 3.0e38f;
+        for (int r = 0; r < PLAN_MAX_ROUNDS; ++r) {
+            if (first_fit[r] == 0x7fffffff) continue;
+            const float time = (float)(r + 1) * ((float)first_fit[r] + piece_overhead);
+            if (time < best_t) { best_t = time; best_c = first_fit[r]; }
+        }
+        if (forced_chunk > 0) best_c = min(max(forced_chunk, c_min), c_max);
+        chosen = make_int4(n_small + (ctx_tiles - bottom + best_c - 1) / best_c, best_c, small_chunk, n_small);
+        *plan = chosen;
+    }
+    __syncthreads();
+    // the list: a stable partition of the piece ids into those with keys and the rest
+    const int4 pl = chosen;
+    const int n_ids = s_max * total_tiles;
+    const int per = (n_ids + PLAN_NT - 1) / PLAN_NT;
+    const int e0 = min(n_ids, tid * per), e1 = min(n_ids, e0 + per);
+    auto has_keys = [&](int e) {
+        const int split = e / total_tiles, tile_lin = total_tiles - 1 - e % total_tiles;
+        if (split >= pl.x) return false;
+        const int j = pl.x - 1 - split;
+        const int lo = j < pl.w ? j * pl.z : pl.w * pl.z + (j - pl.w) * pl.y;
+        return len[tile_lin] > lo;
+    };
+    int mine = 0;
+    for (int e = e0; e < e1; ++e) mine += has_keys(e) ? 1 : 0;
+    // exclusive prefix sum over the threads: within each wave by shuffles, across the waves through LDS
+    const int lane = tid & 63, wave = tid >> 6;
+    int incl = mine;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const int v = __shfl_up(incl, o);
+        if (lane >= o) incl += v;
+    }
+    if (lane == 63) wave_total[wave] = incl;
+    __syncthreads();
+    int before = incl - mine, total = 0;
+#pragma unroll
+    for (int w = 0; w < PLAN_NT / 64; ++w) {
+        before += w < wave ? wave_total[w] : 0;
+        total += wave_total[w];
+    }
+    int full = before, empty = total + (e0 - before);
+    for (int e = e0; e < e1; ++e) {
+        if (has_keys(e)) piece_list[full++] = (uint16_t)e;
+        else piece_list[empty++] = (uint16_t)e;
+    }
+}
+
 template <bool WANT_LSE, bool SPLIT>
 kvs_status launch_one(const dim3 grid, size_t lds_bytes, hipStream_t st, const AttnTiles &td, const kvs_shape *shape,
                       int tiles, const void *q_sel, const int32_t *sel_pos, const void *k_cache, const void *v_cache,
-                      float scale_log2, void *out, float *lse_out, int n_splits, int split_chunk, float *part_o,
-                      float4 *part_ml)
+                      float scale_log2, void *out, float *lse_out, int n_splits, const int4 *split_plan,
+                      const uint16_t *piece_list, float *part_o, float4 *part_ml)
 {
     static bool attr_set = false;   // idempotent; a race only repeats the same call
     if (!attr_set) {
@@ -615,65 +761,43 @@ kvs_status launch_one(const dim3 grid, size_t lds_bytes, hipStream_t st, const A
     }
     hipLaunchKernelGGL((attn_mfma2_kernel<WANT_LSE, SPLIT>), grid, dim3(NT), lds_bytes, st, td, shape->n_q_heads,
                        shape->n_kv_heads, tiles, (const uint16_t *)q_sel, sel_pos, (const uint16_t *)k_cache,
-                       (const uint16_t *)v_cache, scale_log2, (uint16_t *)out, lse_out, n_splits, split_chunk, part_o, part_ml);
+                       (const uint16_t *)v_cache, scale_log2, (uint16_t *)out, lse_out, n_splits, split_plan, piece_list,
+                       part_o, part_ml);
     return check_launch("kvs_partial_attention(mfma2)");
 }
 } // namespace
 
-int attention_mfma2_splits(const kvs_shape *shape, const AttnBatch &bd, size_t workspace_bytes, int *split_chunk)
+AttnSplitPlan attention_mfma2_plan(const kvs_shape *shape, const AttnBatch &bd, size_t workspace_bytes)
 {
+    const AttnSplitPlan whole = {1, 0, 0, 0};
     const int grp = shape->n_q_heads / shape->n_kv_heads;
     int64_t tiles = 0, max_ctx = 0;
     for (int i = 0; i < bd.n_req; ++i) {
         tiles += ((bd.cu_sel[i + 1] - bd.cu_sel[i]) * grp + ROWS - 1) / ROWS;
         max_ctx = bd.ctx_len[i] > max_ctx ? bd.ctx_len[i] : max_ctx;
     }
-    *split_chunk = 0;
     const int64_t wgs = tiles * shape->n_kv_heads;
-    if (wgs <= 0 || wgs >= kAttnSplitBelowWgs) return 1;
+    if (wgs <= 0 || wgs >= kAttnSplitBelowWgs) return whole;
     const int64_t ctx_tiles = (max_ctx + BN - 1) / BN;
     const int64_t n_rows_total = (bd.cu_sel[bd.n_req] - bd.cu_sel[0]) * shape->n_q_heads;
     int64_t s_max = kAttnSplitMax;
     const int64_t by_len = ctx_tiles / 16;                           // at least 16 key tiles per piece
     if (s_max > by_len) s_max = by_len;
-    const int64_t by_ws = (int64_t)(workspace_bytes / (kAttnPartBytesPerSlot * (size_t)(n_rows_total > 0 ? n_rows_total : 1)));
+    if (workspace_bytes < kAttnPlanBytes) return whole;
+    const int64_t by_ws = (int64_t)((workspace_bytes - kAttnPlanBytes) / (kAttnPartBytesPerSlot * (size_t)(n_rows_total > 0 ? n_rows_total : 1)));
     if (s_max > by_ws) s_max = by_ws;
-    if (s_max < 2) return 1;
-    // Pieces run in rounds of one per compute unit and every piece costs about its chunk length, so
-    // the chunk decides how many pieces exist and how full the last round is.  The positions are on
-    // the device; assume they are spread evenly over each context (the last of n rows
-    // of a tile that ends at row r reaches r/n of it) and take the chunk with the shortest predicted time.  A wrong guess costs speed
-    // only.
-    const int64_t c_min = (ctx_tiles + s_max - 1) / s_max;
-    int64_t best_c = c_min;
-    double best_t = 1e300;
-    for (int64_t c = c_min; c <= ctx_tiles; c += (c < 64 ? 4 : 8)) {
-        int64_t pieces = 0;
-        for (int i = 0; i < bd.n_req; ++i) {
-            const int64_t n_rows = (bd.cu_sel[i + 1] - bd.cu_sel[i]) * grp;
-            const int64_t T = (n_rows + ROWS - 1) / ROWS;
-            const int64_t L = (bd.ctx_len[i] + BN - 1) / BN;
-            for (int64_t t = 0; t < T; ++t) {
-                const int64_t last_row = (t + 1) * ROWS < n_rows ? (t + 1) * ROWS : n_rows;   // the tile's last row
-                pieces += (L * last_row / n_rows + c - 1) / c;
-            }
-        }
-        // real selections are not spread that evenly: leave 8 % of head-room, or a round that looked
-        // exactly full spills a few pieces into one more
-        pieces = (pieces * shape->n_kv_heads * 27 + 24) / 25 + shape->n_kv_heads;
-        const int64_t rounds = (pieces + kAttnSplitCus - 1) / kAttnSplitCus;
-        const double time = (double)rounds * ((double)c + 3.0);     // ~3 steps' worth of start-up per piece
-        if (time < best_t) { best_t = time; best_c = c; }
-    }
-    *split_chunk = (int)best_c;
-    const int n = (int)((ctx_tiles + best_c - 1) / best_c);
-    return n >= 2 ? n : 1;
+    if (s_max < 2) return whole;
+    // Small pieces at the bottom of the context (every row tile has them, and they start last)
+    // fill the gaps the large ones leave; they pay off once the large pieces can be several times
+    // their size.
+    const bool taper = s_max >= 6 && ctx_tiles >= 8 * kAttnSmallChunk;
+    return AttnSplitPlan{(int)s_max, (int)ctx_tiles, kAttnSmallChunk, taper ? kAttnSmallPieces : 0};
 }
 
 kvs_status launch_attention_mfma2(const kvs_shape *shape, const AttnBatch &bd, const void *q_sel,
                                   const int32_t *sel_pos, const void *k_cache, const void *v_cache,
-                                  float scale, void *out, float *lse_out, void *workspace, int n_splits,
-                                  int split_chunk, hipStream_t st)
+                                  float scale, void *out, float *lse_out, void *workspace,
+                                  const AttnSplitPlan &plan, hipStream_t st)
 {
     AttnTiles td;
     const int64_t tiles = build_attn_tiles(shape, bd, ROWS, td);
@@ -681,26 +805,45 @@ kvs_status launch_attention_mfma2(const kvs_shape *shape, const AttnBatch &bd, c
     if (tiles == 0) return KVS_OK;
     const size_t lds_bytes = LDS_BYTES;
     const float scale_log2 = scale * 1.4426950408889634f;
+    const int n_splits = plan.n_splits;
     if (n_splits <= 1 || !workspace) {
         const dim3 grid((unsigned)(tiles * shape->n_kv_heads));
         return lse_out ? launch_one<true, false>(grid, lds_bytes, st, td, shape, (int)tiles, q_sel, sel_pos, k_cache, v_cache,
-                                                 scale_log2, out, lse_out, 1, 0, nullptr, nullptr)
+                                                 scale_log2, out, lse_out, 1, nullptr, nullptr, nullptr, nullptr)
                        : launch_one<false, false>(grid, lds_bytes, st, td, shape, (int)tiles, q_sel, sel_pos, k_cache, v_cache,
-                                                  scale_log2, out, lse_out, 1, 0, nullptr, nullptr);
+                                                  scale_log2, out, lse_out, 1, nullptr, nullptr, nullptr, nullptr);
     }
-    // pieces are indexed by the row's position in the whole call's output, so offset the tables by
-    // the first row of this launch
+    if (tiles > PLAN_MAX_TILES) return fail(KVS_EINVAL, "kvs_partial_attention: split launch with %lld row tiles", (long long)tiles);
+    // workspace: the pieces' accumulators, their (reference, sums) records, the plan, the piece list.  Pieces are
+    // indexed by the row's position in the whole call's output, so offset the tables by the first
+    // row of this launch.
     const int64_t n_rows_total = (bd.cu_sel[bd.n_req] - bd.cu_sel[0]) * shape->n_q_heads;
     const int64_t row0 = bd.cu_sel[0] * shape->n_q_heads;
     float *part_o = (float *)workspace - row0 * n_splits * D;
     float4 *ml_base = (float4 *)((char *)workspace + (size_t)n_rows_total * n_splits * D * sizeof(float));
     float4 *part_ml = ml_base - row0 * n_splits;
+    int4 *split_plan = (int4 *)(ml_base + n_rows_total * n_splits);
+    uint16_t *piece_list = (uint16_t *)(split_plan + 1);
+    float round_fill = kAttnRoundFill, piece_overhead = kAttnPieceOverhead;
+    int forced_chunk = 0, small_chunk = plan.small_chunk, n_small = plan.n_small;
+#ifdef KVS_DIAG_CHUNK
+    if (const char *e = getenv("KVS_ATTN_SMALL")) small_chunk = atoi(e);
+    if (const char *e = getenv("KVS_ATTN_NSMALL")) n_small = atoi(e);
+    if (const char *e = getenv("KVS_ATTN_FILL")) round_fill = (float)atof(e);
+    if (const char *e = getenv("KVS_ATTN_OVH")) piece_overhead = (float)atof(e);
+    if (const char *e = getenv("KVS_ATTN_CHUNK")) forced_chunk = atoi(e);
+    if (n_small * small_chunk * 2 > plan.ctx_tiles || n_small + 2 > n_splits) n_small = 0;
+#endif
+    hipLaunchKernelGGL(attn_plan_kernel, dim3(1), dim3(PLAN_NT), 0, st, td, shape->n_q_heads / shape->n_kv_heads,
+                       shape->n_kv_heads, (int)tiles, sel_pos, n_splits, plan.ctx_tiles, small_chunk, n_small, round_fill,
+                       piece_overhead, forced_chunk, split_plan, piece_list);
+    kvs_status stt = check_launch("kvs_partial_attention(plan)");
+    if (stt != KVS_OK) return stt;
     const dim3 grid((unsigned)(tiles * shape->n_kv_heads * n_splits));
-    const kvs_status stt =
-        lse_out ? launch_one<true, true>(grid, lds_bytes, st, td, shape, (int)tiles, q_sel, sel_pos, k_cache, v_cache,
-                                         scale_log2, out, lse_out, n_splits, split_chunk, part_o, part_ml)
-                : launch_one<false, true>(grid, lds_bytes, st, td, shape, (int)tiles, q_sel, sel_pos, k_cache, v_cache,
-                                          scale_log2, out, lse_out, n_splits, split_chunk, part_o, part_ml);
+    stt = lse_out ? launch_one<true, true>(grid, lds_bytes, st, td, shape, (int)tiles, q_sel, sel_pos, k_cache, v_cache,
+                                           scale_log2, out, lse_out, n_splits, split_plan, piece_list, part_o, part_ml)
+                  : launch_one<false, true>(grid, lds_bytes, st, td, shape, (int)tiles, q_sel, sel_pos, k_cache, v_cache,
+                                            scale_log2, out, lse_out, n_splits, split_plan, piece_list, part_o, part_ml);
     if (stt != KVS_OK) return stt;
     return launch_attention_merge(n_rows_total, n_splits, (const float *)workspace, ml_base,
                                   (uint16_t *)out + row0 * D, lse_out ? lse_out + row0 : nullptr, st);

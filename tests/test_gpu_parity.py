@@ -321,6 +321,37 @@ def test_partial_attention_few_rows_long_context_splits_keys():
     np.testing.assert_allclose(lse, ref_lse, atol=2e-3)
 
 
+def test_partial_attention_split_plan_two_requests_unsorted_and_clustered():
+    # two requests, a few hundred selected tokens each over 6k and 9k contexts: enough 256-row
+    # tiles for the large kernel but too few to fill the chip, so the launch is planned on the
+    # device.  The plan reads each row tile's last position and assumes ascending order; request 0
+    # gives its positions shuffled and request 1 has them all at the end of its context, which
+    # may cost speed but never keys.
+    w = synth.scaled(synth.LLAMA, 0)
+    say("attention split plan: two requests, unsorted and clustered positions")
+    lens, pad = [6000, 9000], 3
+    off = np.cumsum([0] + [l + pad for l in lens])[:-1]
+    rows = sum(lens) + pad * len(lens)
+    g = torch.Generator().manual_seed(91)
+    k = torch.randn((rows, w.n_kv_heads, w.head_dim), generator=g).to(torch.bfloat16)
+    v = torch.randn((rows, w.n_kv_heads, w.head_dim), generator=g).to(torch.bfloat16)
+    rng = np.random.default_rng(92)
+    sel = [rng.permutation(rng.choice(lens[0], size=420, replace=False)).astype(np.int32),
+           np.arange(lens[1] - 390, lens[1], dtype=np.int32)]
+    cu = np.cumsum([0] + [len(x) for x in sel])
+    q = (torch.randn((int(cu[-1]), w.n_q_heads, w.head_dim), generator=g) / math.sqrt(w.head_dim)).to(torch.bfloat16)
+    pos = np.concatenate(sel)
+    ref, ref_lse = oracle.partial_attention(q, pos, k, v, 1.0, off, lens, cu)
+    mag = attn_magnitude(q, pos, k, v, 1.0, off, lens, cu)
+    got, lse = run_gpu_attention(w, q, pos, k, v, 1.0, off, lens, cu)
+    assert_attn_close(got, ref, w, mag)
+    np.testing.assert_allclose(lse, ref_lse, atol=2e-3)
+    # the same launch without a workspace (no key pieces) must agree as well
+    got2, lse2 = run_gpu_attention(w, q, pos, k, v, 1.0, off, lens, cu, with_workspace=False)
+    assert_attn_close(got2, ref, w, mag)
+    np.testing.assert_allclose(lse2, ref_lse, atol=2e-3)
+
+
 def test_partial_attention_select_all_is_full_prefill():
     w = synth.scaled(synth.LLAMA, 400, span_mean=32.0)
     say("attention select-all == full prefill")
