@@ -324,6 +324,27 @@ def main() -> int:
     torch.cuda.synchronize()
     del kdst, vdst
 
+    # Beside the timed path: the producer of the prefill alpha (Alg. 1 steps 1-2), which a caller
+    # runs once per check layer before kvs_deviation.  Not part of a step and not in `value`.
+    lay0 = synth.make_layer(w, layer=0, device="cuda")
+    alpha_out = torch.empty((hk, n), device="cuda")
+    ws_cs = torch.empty(B.kvs_workspace_size("attn_colsum", sh, 1, n), dtype=torch.uint8, device="cuda")
+    B.kvs_attn_colsum(sh, n, lay0["q"], lay0["k_fresh"], 1.0, alpha_out, ws_cs)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(3):
+        B.kvs_attn_colsum(sh, n, lay0["q"], lay0["k_fresh"], 1.0, alpha_out, ws_cs)
+    e1.record()
+    torch.cuda.synchronize()
+    t_cs = e0.elapsed_time(e1) / 3
+    flops_cs = 2 * 2.0 * d * hq * (n * (n + 1) / 2)      # two sweeps of the causal score matrix
+    row_sums = alpha_out.double().sum(dim=1) / (n * (hq // hk))
+    result["next_rows"] = {"attn_colsum": {
+        "ms": float(t_cs), "TFLOPs": flops_cs / (t_cs * 1e-3) / 1e12,
+        "frac_mfma": flops_cs / (t_cs * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+        "flops": flops_cs, "check_sum_alpha_over_rows": [float(x) for x in row_sums.cpu()]}}
+    del lay0, alpha_out, ws_cs
+
     if args.cpu_sample > 0:
         cb = cpu_baseline_and_parity(w, args.ratio, sh, alpha_n, args.cpu_sample)
         cb["attention_extrapolated_ms_per_layer"] = flops / (cb["value"] * 1e12) * 1e3

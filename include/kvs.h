@@ -189,8 +189,30 @@ KVS_API kvs_status kvs_decode_check(const kvs_shape *shape, int32_t batch, int64
                             void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * kvs_attn_colsum -- Alg. 1 steps 1-2: the attention column mass of a whole prefill,
+ *     alpha[g, i] = sum over the query heads h of KV head g, and over the rows j >= i, of A_h[j, i],
+ *     A_h = row softmax over the keys i <= j of scale * q[j, h] . k[i, g]      (Eq. (3), causal),
+ * i.e. the alpha that kvs_deviation takes.  Every row of A sums to 1, so sum_i alpha[g, i] =
+ * n_tokens * n_q_heads / n_kv_heads.  The score matrix is never stored: one sweep leaves each
+ * row's log-sum-exp in the workspace, a second one sums exp(score - lse) down the columns.
+ * Cost: two passes of n_tokens^2 / 2 * head_dim * n_q_heads multiply-adds on the matrix cores.
+ *
+ * Built for bf16 with head_dim 128 (KVS_EUNSUPPORTED otherwise, and for scale <= 0 or tensors of
+ * 4 GiB and more).  Q and K as for the other calls: [n_tokens, heads, head_dim], 16-byte aligned.
+ *
+ * q         [dev] [n_tokens, n_q_heads, head_dim]
+ * k         [dev] [n_tokens, n_kv_heads, head_dim] (the fresh keys)
+ * alpha     [dev] fp32[n_kv_heads, n_tokens], written
+ * workspace [dev] kvs_workspace_size("attn_colsum", shape, 1, n_tokens, 0) bytes, 256-byte
+ *           aligned, required; contents on return are unspecified
+ */
+KVS_API kvs_status kvs_attn_colsum(const kvs_shape *shape, int64_t n_tokens, const void *q, const void *k,
+                           float scale, float *alpha,
+                           void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Workspace a call needs, in bytes, for the given problem.  `call` is "select_topk",
- * "partial_attention" or "decode_check" (anything else returns 0).  n_rows_total is the total
+ * "partial_attention", "decode_check" or "attn_colsum" (anything else returns 0).  n_rows_total is the total
  * number of score / cache rows the call will see, n_sel_total the total number of selected
  * tokens (partial_attention only).  The answer is an upper bound valid for any split of the
  * totals over `batch` requests.

@@ -22,7 +22,7 @@ SCORE_V, SCORE_KV = 0, 1
 OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP = 0, 1, 2, 3, 4
 
 EXPORTS = ("kvs_deviation", "kvs_select_topk", "kvs_scatter_kv", "kvs_partial_attention",
-           "kvs_decode_check", "kvs_workspace_size", "kvs_strerror", "kvs_last_error", "kvs_version")
+           "kvs_decode_check", "kvs_attn_colsum", "kvs_workspace_size", "kvs_strerror", "kvs_last_error", "kvs_version")
 
 
 class KvsError(RuntimeError):
@@ -57,8 +57,10 @@ def load(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.kvs_scatter_kv.argtypes = [sp, i64, vp, vp, vp, i64, vp, vp, vp, vp, vp]
     lib.kvs_partial_attention.argtypes = [sp, i32, vp, vp, vp, vp, vp, vp, vp, f32, vp, vp, vp, sz, vp]
     lib.kvs_decode_check.argtypes = [sp, i32, i64, vp, vp, vp, vp, vp, vp, vp, f32, vp, vp, vp, vp, vp, sz, vp]
+    lib.kvs_attn_colsum.argtypes = [sp, i64, vp, vp, f32, vp, vp, sz, vp]
     lib.kvs_workspace_size.argtypes = [ctypes.c_char_p, sp, i32, i64, i64]
-    for n in ("kvs_deviation", "kvs_select_topk", "kvs_scatter_kv", "kvs_partial_attention", "kvs_decode_check"):
+    for n in ("kvs_deviation", "kvs_select_topk", "kvs_scatter_kv", "kvs_partial_attention", "kvs_decode_check",
+              "kvs_attn_colsum"):
         getattr(lib, n).restype = ctypes.c_int
     lib.kvs_workspace_size.restype = sz
     lib.kvs_strerror.argtypes = [ctypes.c_int]
@@ -174,6 +176,13 @@ def kvs_decode_check(shape: Shape, n_rows: int, ctx_off: Sequence[int], ctx_len:
                                  _ptr(score_out, torch.float32), _ptr(attn_out), _ptr(workspace), ws_bytes,
                                  _stream(stream))
     _check(rc, "kvs_decode_check")
+
+
+def kvs_attn_colsum(shape: Shape, n_tokens: int, q, k, scale: float, alpha, workspace, stream=None) -> None:
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    rc = load().kvs_attn_colsum(ctypes.byref(shape), n_tokens, _ptr(q), _ptr(k), scale, _ptr(alpha, torch.float32),
+                                _ptr(workspace), ws_bytes, _stream(stream))
+    _check(rc, "kvs_attn_colsum")
 
 
 def shape_of(workload) -> Shape:

@@ -26,6 +26,7 @@ inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 
 kvs_status launch_select(const float *scores, int32_t n_rows, const int64_t *begin, const int64_t *len,
                          const int32_t *k_row, int32_t *idx_out, hipStream_t stream);
 size_t decode_workspace_bytes(const kvs_shape *shape, int32_t batch, int64_t n_rows);
+size_t colsum_workspace_bytes(const kvs_shape *shape, int64_t n_tokens);
 
 constexpr int kWave = 64;
 

@@ -112,3 +112,24 @@ def test_decode_argument_errors(lib):
     assert call(attn=FAKE) == B.EINVAL                        # attn_out without v_cache
     assert b"v_cache" in lib.kvs_last_error()
     assert B.kvs_workspace_size("nonsense", sh, 1, 10) == 0
+
+
+def test_attn_colsum_argument_errors(lib):
+    sh = _shape()
+    need = B.kvs_workspace_size("attn_colsum", sh, 1, 1000)
+    assert need >= 4 * 32 * 1000
+
+    def call(shape=sh, n=1000, q=FAKE, k=FAKE, scale=1.0, alpha=FAKE, ws=FAKE * 16, ws_bytes=need):
+        return lib.kvs_attn_colsum(ctypes.byref(shape), n, q, k, scale, alpha, ws, ws_bytes, None)
+    assert call(n=-1) == B.EINVAL
+    assert call(n=0, q=None, k=None, alpha=None, ws=None, ws_bytes=0) == B.OK      # empty: no-op
+    assert call(shape=_shape(dt=B.F32, d=64, hq=4, hk=4)) == B.EUNSUPPORTED
+    assert call(scale=0.0) == B.EUNSUPPORTED
+    assert call(scale=float("nan")) == B.EUNSUPPORTED
+    assert call(q=None) == B.EINVAL
+    assert call(k=FAKE + 8) == B.EINVAL
+    assert call(ws=None) == B.EINVAL
+    assert call(ws=FAKE * 16 + 64) == B.EINVAL                # workspace alignment
+    assert call(ws_bytes=need - 1) == B.EWORKSPACE
+    assert call(n=1 << 20) == B.EUNSUPPORTED                  # 8 GiB of queries: past the 32-bit offsets
+    assert b"4 GiB" in lib.kvs_last_error()

@@ -189,3 +189,42 @@ def test_decode_batch_full_size():
         ref, _ = oracle.partial_attention(q_sel[rows_b].cpu(), ix[rows_b], kh, vh, 1.0)
         mag, _ = oracle.partial_attention(q_sel[rows_b].cpu(), ix[rows_b], kh, abs_bf16(vh), 1.0)
         attn_close(out[rows_b].float().cpu().numpy(), ref, mag)
+
+
+def test_attn_colsum_llama_32k_full_size():
+    """The prefill column mass at 32k: the oracle needs every row's log-sum-exp for one column, so
+    the comparison takes the last columns (column i needs the rows j >= i only) and the first
+    column of a truncated context (alpha over the first m tokens is a problem of its own), plus
+    what holds at any size: every softmax row sums to 1, the last column is at most one unit per
+    head and the first at least one."""
+    w = synth.LLAMA
+    say("attention column mass, llama 32k")
+    sh = B.shape_of(w)
+    n, hk, hq, d = w.n_ctx, w.n_kv_heads, w.n_q_heads, w.head_dim
+    grp = hq // hk
+    lay = synth.make_layer(w, device=DEV)
+    alpha = torch.empty((hk, n), device=DEV)
+    ws = torch.empty(B.kvs_workspace_size("attn_colsum", sh, 1, n), dtype=torch.uint8, device=DEV)
+    B.kvs_attn_colsum(sh, n, lay["q"], lay["k_fresh"], 1.0, alpha, ws)
+    torch.cuda.synchronize()
+    a = alpha.double().cpu().numpy()
+    assert np.all(np.isfinite(a)) and np.all(a > 0)
+    np.testing.assert_allclose(a.sum(axis=1), np.full(hk, float(n * grp)), rtol=1e-5)
+    assert np.all(a[:, -1] <= grp) and np.all(a[:, 0] >= grp)
+    # last m columns against the oracle's rows
+    m = 8
+    q_tail, k_all = lay["q"][n - m:].cpu(), lay["k_fresh"].cpu()
+    _, lse = oracle.partial_attention(q_tail, np.arange(n - m, n, dtype=np.int32), k_all, lay["v_fresh"].cpu(), 1.0)
+    qf, kf = q_tail.double().numpy(), k_all[n - m:].double().numpy()
+    ref = np.zeros((hk, m))
+    for j in range(m):
+        for h in range(hq):
+            s = kf[: j + 1, h // grp] @ qf[j, h]
+            ref[h // grp, : j + 1] += np.exp(s - lse[j, h])
+    np.testing.assert_allclose(a[:, n - m:], ref, rtol=1e-4, atol=1e-7)
+    # the same kernel on the first 1500 tokens, in full against the oracle
+    m2 = 1500
+    _, ref2 = oracle.alpha_prefill(lay["q"][:m2].cpu(), k_all[:m2], 1.0)
+    alpha2 = torch.empty((hk, m2), device=DEV)
+    B.kvs_attn_colsum(sh, m2, lay["q"], lay["k_fresh"], 1.0, alpha2, ws)
+    np.testing.assert_allclose(alpha2.double().cpu().numpy(), ref2, rtol=1e-4, atol=1e-7)

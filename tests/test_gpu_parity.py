@@ -421,6 +421,88 @@ def check_topk_band(idx, score_ref, k, rtol=2e-5):
     assert not np.any(chosen[score_ref < thr * (1 - rtol) - 1e-30]), "a clearly worse candidate was taken"
 
 
+# ------------------------------------------------------------------- attention column mass
+
+def run_gpu_colsum(w, q, k, scale):
+    n = q.shape[0]
+    sh = shape_for(w)
+    alpha = torch.full((w.n_kv_heads, max(n, 1)), float("nan"), device=DEV)
+    ws = torch.empty(B.kvs_workspace_size("attn_colsum", sh, 1, n), dtype=torch.uint8, device=DEV)
+    B.kvs_attn_colsum(sh, n, q.to(DEV).contiguous(), k.to(DEV).contiguous(), scale, alpha, ws)
+    torch.cuda.synchronize()
+    return alpha[:, :n].cpu().numpy().astype(np.float64)
+
+
+# fp32 scores from exact bf16 products (error ~1e-6 of the logit), exp2 of the hardware (~1 ulp) and
+# fp32 sums of up to n * grp terms per key: a few 1e-6 relative in all; 1e-4 leaves a wide margin
+COLSUM_RTOL, COLSUM_ATOL = 1e-4, 1e-7
+
+COLSUM_CASES = [
+    ("llama-1201-g4", synth.scaled(synth.LLAMA, 1201, span_mean=64.0)),
+    ("qwen-777-g7", synth.scaled(synth.QWEN, 777, span_mean=64.0)),
+    ("yi-900-g8", synth.scaled(synth.YI, 900, span_mean=64.0, coverage=0.9)),
+    ("g1-515", synth.scaled(synth.LLAMA, 515, n_q_heads=4, n_kv_heads=4, span_mean=32.0)),
+    ("llama-256-exact-tiles", synth.scaled(synth.LLAMA, 256, span_mean=32.0)),
+    ("llama-33", synth.scaled(synth.LLAMA, 33, span_mean=8.0)),
+    ("llama-1", synth.scaled(synth.LLAMA, 1, span_mean=1.0)),
+]
+
+
+@pytest.mark.parametrize("name,w", COLSUM_CASES, ids=[c[0] for c in COLSUM_CASES])
+def test_attn_colsum_parity(name, w):
+    say(f"attention column mass {name}")
+    lay = synth.make_layer(w)
+    q, k = lay["q"], lay["k_fresh"]
+    _, ref = oracle.alpha_prefill(q, k, 1.0)
+    got = run_gpu_colsum(w, q, k, 1.0)
+    np.testing.assert_allclose(got, ref, rtol=COLSUM_RTOL, atol=COLSUM_ATOL)
+    # every row of the softmax sums to 1
+    grp = w.n_q_heads // w.n_kv_heads
+    np.testing.assert_allclose(got.sum(axis=1), np.full(w.n_kv_heads, w.n_ctx * grp), rtol=1e-5)
+    # with an explicit scale on unscaled queries
+    q2 = (q.float() * math.sqrt(w.head_dim)).to(q.dtype)
+    _, ref2 = oracle.alpha_prefill(q2, k, 1.0 / math.sqrt(w.head_dim))
+    got2 = run_gpu_colsum(w, q2, k, 1.0 / math.sqrt(w.head_dim))
+    np.testing.assert_allclose(got2, ref2, rtol=COLSUM_RTOL, atol=COLSUM_ATOL)
+
+
+def test_attn_colsum_feeds_deviation_like_the_oracle_alpha():
+    # Alg. 1 on the GPU end to end: alpha from kvs_attn_colsum into kvs_deviation; the scores agree
+    # with the oracle's (own alpha, own deviation) to the column mass's tolerance
+    w = synth.scaled(synth.LLAMA, 1100, span_mean=64.0)
+    say("attention column mass -> deviation score")
+    lay = synth.make_layer(w)
+    _, alpha_ref = oracle.alpha_prefill(lay["q"], lay["k_fresh"], 1.0)
+    _, _, score_ref = oracle.deviation(lay["v_fresh"], lay["v_cache"], reused=lay["reused"], alpha=alpha_ref.astype(np.float32))
+    alpha = torch.from_numpy(run_gpu_colsum(w, lay["q"], lay["k_fresh"], 1.0).astype(np.float32)).to(DEV)
+    n = w.n_ctx
+    dev_v = torch.empty((w.n_kv_heads, n), device=DEV)
+    score = torch.empty((n,), device=DEV)
+    B.kvs_deviation(shape_for(w), n, None, lay["v_fresh"].to(DEV), None, lay["v_cache"].to(DEV), lay["reused"].to(DEV),
+                    alpha, 0, None, dev_v, score)
+    got = score.cpu().numpy()
+    fin = np.isfinite(score_ref)
+    np.testing.assert_array_equal(np.isfinite(got), fin)
+    np.testing.assert_allclose(got[fin], score_ref[fin], rtol=2e-4, atol=1e-6)
+
+
+def test_attn_colsum_first_tile_reference_fallback():
+    # one key far down the context whose logit towers over everything in the first tile: the row
+    # sums taken against the first tile's reference overflow and the exact-maximum sweep must take over
+    w = synth.scaled(synth.LLAMA, 600, span_mean=32.0)
+    say("attention column mass: exact-maximum fallback")
+    g = torch.Generator().manual_seed(5)
+    q = (torch.randn((w.n_ctx, w.n_q_heads, w.head_dim), generator=g) / math.sqrt(w.head_dim)).to(torch.bfloat16)
+    k = torch.randn((w.n_ctx, w.n_kv_heads, w.head_dim), generator=g).to(torch.bfloat16)
+    k[300] = 0
+    k[300, :, 0] = 64.0
+    q[:, :, 0] = 4.0          # logit 256 on key 300 for every later query: 2^369 against the first tile
+    _, ref = oracle.alpha_prefill(q, k, 1.0)
+    got = run_gpu_colsum(w, q, k, 1.0)
+    np.testing.assert_allclose(got, ref, rtol=COLSUM_RTOL, atol=COLSUM_ATOL)
+    assert got[0, 300] > 4 * 250          # nearly every later row puts all its mass there
+
+
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 def test_decode_check_parity(dtype):
     w = synth.DECODE if dtype == "bf16" else synth.scaled(synth.DECODE, 0, dtype="f32", head_dim=64, n_q_heads=8, n_kv_heads=4)
