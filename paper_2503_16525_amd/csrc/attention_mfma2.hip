@@ -132,6 +132,10 @@ __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
     const int grp = n_q_heads / n_kv_heads;
     const int64_t sel0 = td.cu_sel[b];
     const int n_rows = (int)(td.cu_sel[b + 1] - sel0) * grp;
+    // Row tiles are aligned to the end of the request's rows: the one partly filled tile is then the
+    // first, whose rows sit lowest in the context and see the fewest keys, so the padding lanes of
+    // the launch idle through the shortest sweep instead of the longest.
+    const int row0 = tile * ROWS - ((td.tile_begin[b + 1] - td.tile_begin[b]) * ROWS - n_rows);
     const int ctx_len = td.ctx_len[b];
     const int64_t ctx_off = td.ctx_off[b];
 
@@ -142,9 +146,9 @@ __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
         if (split >= plan.x) {   // a piece slot the plan does not use: mark it empty for the merge
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb) {
-                const int rq = tile * ROWS + wave * WROWS + nb * 32 + ln;
+                const int rq = row0 + wave * WROWS + nb * 32 + ln;
                 const int t_sel = rq / grp, hh = rq - t_sel * grp;
-                if (rq < n_rows && hf == 0)
+                if (rq >= 0 && hf == 0)
                     part_ml[((sel0 + t_sel) * n_q_heads + g * grp + hh) * (int64_t)n_splits + split] = make_float4(-1.0e30f, 0.f, 0.f, 0.f);
             }
             return;
@@ -158,9 +162,9 @@ __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
     int pmin = 0x7fffffff, pmax = 0;
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
-        const int rq = tile * ROWS + wave * WROWS + nb * 32 + ln;
-        row_ok[nb] = rq < n_rows;
-        const int rqc = row_ok[nb] ? rq : n_rows - 1;
+        const int rq = row0 + wave * WROWS + nb * 32 + ln;
+        row_ok[nb] = rq >= 0;
+        const int rqc = max(rq, 0);
         const int t_sel = rqc / grp, hh = rqc - t_sel * grp;
         const int64_t s_glob = sel0 + t_sel;
         int p = sel_pos[s_glob];
@@ -669,7 +673,7 @@ __global__ __launch_bounds__(PLAN_NT) void attn_plan_kernel(
         while (b + 1 < td.n_req && t >= td.tile_begin[b + 1]) ++b;
         const int tile = t - td.tile_begin[b];
         const int n_rows = (int)(td.cu_sel[b + 1] - td.cu_sel[b]) * grp;
-        const int last_row = min((tile + 1) * ROWS, n_rows) - 1;
+        const int last_row = (tile + 1) * ROWS - ((td.tile_begin[b + 1] - td.tile_begin[b]) * ROWS - n_rows) - 1;   // tiles end-aligned
         int p = sel_pos[td.cu_sel[b] + last_row / grp];
         p = min(max(p, 0), td.ctx_len[b] - 1);
         len[t] = p / BN + 1;
