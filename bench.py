@@ -82,6 +82,12 @@ def build_slot(w, layer: int, ratio: float, sh, alpha) -> Slot:
     s.out = torch.empty((s.k, hq, d), dtype=torch.bfloat16, device=dev)
     s.out_dec = torch.empty((s.k_dec, hq, d), dtype=torch.bfloat16, device=dev)
     s.alpha = alpha
+    s.q_full = None
+    if isinstance(alpha, str):          # "gpu": the step computes this layer's alpha itself
+        s.q_full = lay["q"]
+        s.alpha = torch.empty((hk, n), device=dev)
+        B.kvs_attn_colsum(sh, n, s.q_full, s.k_fresh, 1.0, s.alpha, WS_CS)
+        alpha = s.alpha
     # ---- untimed set-up pass: find what the step will select, gather the recomputed rows ----
     q_full = lay["q"]
     k0, v0 = s.k_cache.clone(), s.v_cache.clone()
@@ -118,6 +124,10 @@ def run_step(s: Slot, sh, ev=None) -> None:
     """The timed work: seven C-ABI calls on the current stream, no host synchronisation."""
     n, rows = s.n, s.rows
     if ev:
+        ev[6].record()
+    if s.q_full is not None:
+        B.kvs_attn_colsum(sh, n, s.q_full, s.k_fresh, 1.0, s.alpha, WS_CS)
+    if ev:
         ev[0].record()
     B.kvs_deviation(sh, n, None, s.v_fresh, None, s.v_cache, s.reused, s.alpha, B.SCORE_V, None, s.dev_v, s.score)
     B.kvs_select_topk(s.score, [0, n], [s.k], s.idx)
@@ -141,6 +151,7 @@ def run_step(s: Slot, sh, ev=None) -> None:
 
 WS = None       # decode-check workspace
 WS_ATT = None   # partial-attention workspace (lets the small decode-recompute launch split its key range)
+WS_CS = None    # workspace of kvs_attn_colsum
 
 
 def cpu_baseline_and_parity(w, ratio: float, sh, alpha, n_sample: int) -> dict:
@@ -218,15 +229,16 @@ def read_traffic(kernel: str):
 
 
 def main() -> int:
-    global WS, WS_ATT
+    global WS, WS_ATT, WS_CS
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--ratio", type=float, default=0.15, help="recompute ratio (fraction of reused tokens)")
-    ap.add_argument("--alpha", choices=["none", "synthetic"], default="none",
-                    help="attention column mass fed to kvs_deviation: none = magnitude-only score (alpha = 1), "
-                         "synthetic = a harmonic-tail profile (the exact O(N^2) alpha is not affordable at 32k)")
+    ap.add_argument("--alpha", choices=["none", "synthetic", "gpu"], default="none",
+                    help="attention column mass fed to kvs_deviation: none = magnitude-only score (alpha = 1, the "
+                         "headline workload), synthetic = a fixed harmonic-tail profile, gpu = the exact Alg. 1 alpha, "
+                         "produced by kvs_attn_colsum inside every timed step (adds two sweeps of the N x N score matrix)")
     ap.add_argument("--cpu-sample", type=int, default=256, help="selected queries in the oracle's attention sample (0 = skip the CPU leg)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -242,7 +254,8 @@ def main() -> int:
     n, hk, hq, d = w.n_ctx, w.n_kv_heads, w.n_q_heads, w.head_dim
     WS = torch.empty(B.kvs_workspace_size("decode_check", sh, 1, n + 1), dtype=torch.uint8, device="cuda")
     WS_ATT = torch.empty(B.kvs_workspace_size("partial_attention", sh, 1, n + 1, 1024), dtype=torch.uint8, device="cuda")
-    alpha_n = synth.synthetic_alpha(w, device="cuda") if args.alpha == "synthetic" else None
+    WS_CS = torch.empty(B.kvs_workspace_size("attn_colsum", sh, 1, n), dtype=torch.uint8, device="cuda")
+    alpha_n = synth.synthetic_alpha(w, device="cuda") if args.alpha == "synthetic" else ("gpu" if args.alpha == "gpu" else None)
 
     n_slots = max(1, min(args.warmup + args.steps, MAX_SLOTS))
     t0 = time.perf_counter()
@@ -263,7 +276,7 @@ def main() -> int:
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
-    events = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(args.steps)]
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(7)] for _ in range(args.steps)]
     torch.cuda.synchronize()
     t_start = time.perf_counter()
     for i in range(args.steps):
@@ -274,6 +287,7 @@ def main() -> int:
 
     seg = np.array([[ev[j].elapsed_time(ev[j + 1]) for j in range(5)] for ev in events])  # ms
     t_devsel, t_scat, t_attn, t_dec, t_decrec = seg.mean(0)
+    t_alpha = float(np.mean([ev[6].elapsed_time(ev[0]) for ev in events]))   # ~0 unless --alpha gpu
     used_slots = [slots[(args.warmup + i) % n_slots] for i in range(args.steps)]
     flops = float(np.mean([s.flops for s in used_slots]))
     flops_dec = float(np.mean([s.flops_dec for s in used_slots]))
@@ -312,6 +326,7 @@ def main() -> int:
             "decode_check": {"ms": float(t_dec), "GBps": bytes_dec / (t_dec * 1e-3) / 1e9,
                              "frac_hbm": bytes_dec / (t_dec * 1e-3) / 1e9 / HBM_PEAK_GBS},
             "decode_recompute": {"ms": float(t_decrec), "attention_TFLOP": flops_dec / 1e12},
+            "alpha_in_step": {"ms": t_alpha if args.alpha == "gpu" else 0.0},
         },
     }
     # One untimed launch of known traffic for the profiler: kvs_scatter_kv over every row of a layer
@@ -346,7 +361,8 @@ def main() -> int:
     del lay0, alpha_out, ws_cs
 
     if args.cpu_sample > 0:
-        cb = cpu_baseline_and_parity(w, args.ratio, sh, alpha_n, args.cpu_sample)
+        # (with --alpha gpu the oracle takes the alpha the GPU produced for layer 0: its own is O(N^2 d) on the CPU)
+        cb = cpu_baseline_and_parity(w, args.ratio, sh, slots[0].alpha if args.alpha == "gpu" else alpha_n, args.cpu_sample)
         cb["attention_extrapolated_ms_per_layer"] = flops / (cb["value"] * 1e12) * 1e3
         result["cpu_baseline"] = cb
     else:
