@@ -3,10 +3,11 @@
 //     score_i = sum_g ( sum_{h in g} softmax_i(scale * q_h . K_i) ) * dev_v[g,i]
 //
 // Kernels, all on the caller's stream:
-//   1. logits     streams K once (16-byte pieces, LPH lanes per (token, kv head) cell, the group's
-//                 query slices in registers, DPP reduction as in the deviation kernel), writes
-//                 scale*q.K for every query head to the workspace as fp32 [n_q_heads][n_rows] and
-//                 the (max, sum exp) of each 64-token tile;
+//   1. logits     streams K once and writes scale*q.K for every query head to the workspace as fp32
+//                 [n_q_heads][n_rows], plus the (max, sum exp) of each 64-token tile.  bf16 with
+//                 head_dim 128: on the matrix cores, K loaded straight into LDS (1b below); other
+//                 shapes: 16-byte pieces, LPH lanes per (token, kv head) cell, the group's query
+//                 slices in registers, DPP reduction as in the deviation kernel;
 //   2. stats      per (request, head): merges the tile partials into the softmax max / normaliser;
 //   3. score      per token: normalised weights summed per group, times the stored deviation,
 //                 masked to the candidates;
@@ -163,6 +164,169 @@ __global__ __launch_bounds__(kThreads) void decode_logits_kernel(
     }
 }
 
+// ---- 1b. the same on the matrix cores (bf16, head_dim 128, groups of up to 32 query heads) ----------
+// The vector kernel above spends ~60 instructions per 16 bytes of K and tops out near half of
+// the HBM rate; here q . K is one v_mfma_f32_32x32x16_bf16 chain per 32 tokens of a KV head: A =
+// the group's query heads as rows (the unused rows are zero), B = the K rows as columns, so a
+// lane's column of the result is one token and its first registers are that token's logits for
+// the group's heads - stores of one head are 32 consecutive floats.  Only 1/8 of the matrix work
+// is useful at a group of 4, which is irrelevant: the kernel has to be memory-bound, and is.
+// K goes from global memory straight into LDS (buffer loads with the LDS flag and the
+// non-temporal hint: the cache is read once; 1 KiB = four
+// 256-byte rows per instruction, 16-byte pieces XOR-swizzled by the row so that the operand reads
+// are conflict-free).  A workgroup is still one 64-token tile; wave w takes KV heads w, w+4, ..,
+// each as two units of 32 tokens that it stages and consumes by itself through its own two LDS
+// slots, so there is no barrier anywhere: a wave only waits for its own loads.
+constexpr int kMmaUnitBytes = 32 * 256;            // 32 tokens x 256 bytes
+constexpr int kMmaSlots = 2;
+constexpr int kMmaLds = (kThreads / 64) * kMmaSlots * kMmaUnitBytes;
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 dec_bf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float dec_floatx16;
+
+// max / sum over the 32 lanes of a half-wave (lanes 0-31 or 32-63), result in each of them
+__device__ __forceinline__ float half_max(float v)
+{
+    v = fmaxf(v, dpp_f32<0x128>(v));
+    v = fmaxf(v, dpp_f32<0x124>(v));
+    v = fmaxf(v, dpp_f32<0x122>(v));
+    v = fmaxf(v, dpp_f32<0x121>(v));
+    return fmaxf(v, __shfl_xor(v, 16));
+}
+__device__ __forceinline__ float half_sum(float v)
+{
+    v = row16_sum(v);
+    return v + __shfl_xor(v, 16);
+}
+
+__global__ __launch_bounds__(kThreads) void decode_logits_mfma_kernel(
+    const DecodeBatch bd, int n_q_heads, int n_kv_heads, int64_t n_rows,
+    const uint16_t *__restrict__ q_new, const uint16_t *__restrict__ k_cache, float scale,
+    float *__restrict__ logits, float2 *__restrict__ partial /* [tile][n_q_heads] (max, sum exp) */)
+{
+    constexpr int D = 128, ROW_B = 256;
+    extern __shared__ __attribute__((aligned(16))) char lds_mma[];
+    int b = 0;
+    while (b + 1 < bd.n_req && (int)blockIdx.x >= bd.tile_begin[b + 1]) ++b;
+    const int tile = blockIdx.x - bd.tile_begin[b];
+    const int len = bd.ctx_len[b];
+    const int tok0 = tile * kTok;
+    const int tile_tok = min(kTok, len - tok0);
+    const int64_t row0 = bd.ctx_off[b] + tok0;
+    const int grp = n_q_heads / n_kv_heads;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int hf = lane >> 5, ln = lane & 31;
+    const uint16_t *qb = q_new + (int64_t)(bd.req0 + b) * n_q_heads * D;
+
+    // the whole cache as one buffer (the host checks that it is below 4 GiB)
+    const uint32_t row_bytes = (uint32_t)n_kv_heads * ROW_B;
+    u32x4_t rs;
+    {
+        const uint64_t a = reinterpret_cast<uint64_t>(k_cache);
+        rs.x = __builtin_amdgcn_readfirstlane((uint32_t)a);
+        rs.y = __builtin_amdgcn_readfirstlane((uint32_t)(a >> 32) & 0xffffu);
+        rs.z = __builtin_amdgcn_readfirstlane((uint32_t)n_rows * row_bytes);
+        rs.w = 0x00020000u;
+    }
+    char *const my_lds = lds_mma + wave * (kMmaSlots * kMmaUnitBytes);
+    const uint32_t lds_base = __builtin_amdgcn_readfirstlane(
+        (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)my_lds);
+    // staging: instruction j moves rows 4j .. 4j+3 of the unit; lane = (row in the four, position);
+    // piece p of row r sits at position p ^ (r & 15)
+    const int st_r = lane >> 4, st_p = lane & 15;
+    // This wave's KV heads are wave, wave + 4, ...; they are taken two at a time, and the four units
+    // of a pair go (head A, tokens 0-31), (head B, 0-31), (A, 32-63), (B, 32-63): with two units in
+    // flight per wave the four waves together are then reading all heads of the same 32 token rows,
+    // i.e. one contiguous stretch of the cache, instead of every other 256-byte chunk of it.
+    const int n_heads_w = (n_kv_heads - wave + 3) / 4;
+    const int n_units = 2 * n_heads_w;
+    // unit u of the wave -> (index of the head among the wave's heads, token half)
+    auto unit_head = [&](int u) { const int pair = u >> 2, k = u & 3; return (n_heads_w - 2 * pair >= 2) ? 2 * pair + (k & 1) : 2 * pair; };
+    auto unit_sub = [&](int u) { const int pair = u >> 2, k = u & 3; return (n_heads_w - 2 * pair >= 2) ? (k >> 1) : (k & 1); };
+    auto stage_unit = [&](int u) {
+        const int g = wave + 4 * unit_head(u), sub = unit_sub(u);
+        const uint32_t slot = lds_base + (uint32_t)((u & (kMmaSlots - 1)) * kMmaUnitBytes);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int r = 4 * j + st_r;
+            const int t = min(32 * sub + r, tile_tok - 1);          // rows past the context: its last row
+            const uint32_t voff = (uint32_t)(row0 + t) * row_bytes + (uint32_t)g * ROW_B + (uint32_t)((st_p ^ (r & 15)) * 16);
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen nt lds"
+                         :: "s"(__builtin_amdgcn_readfirstlane(slot + (uint32_t)(j * 1024))), "v"(voff), "s"(rs));
+        }
+    };
+    // B operand: K row ln, pieces 2*ks + hf
+    const uint32_t b_read_off = (uint32_t)(ln * ROW_B + ((hf ^ (ln & 15)) * 16));
+    const dec_floatx16 zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+
+    if (n_units > 0) stage_unit(0);
+    if (n_units > 1) stage_unit(1);
+    for (int pair = 0; 2 * pair < n_heads_w; ++pair) {
+        const int heads_here = min(2, n_heads_w - 2 * pair);
+        // A operands: query head g*grp + ln of each head of the pair (rows past the group are zero)
+        dec_bf16x8 qa[2][D / 16];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int g = wave + 4 * (2 * pair + min(i, heads_here - 1));
+#pragma unroll
+            for (int ks = 0; ks < D / 16; ++ks) {
+                u32x4_t v = {0u, 0u, 0u, 0u};
+                if (ln < grp) v = *reinterpret_cast<const u32x4_t *>(qb + (int64_t)(g * grp + ln) * D + 16 * ks + 8 * hf);
+                qa[i][ks] = __builtin_bit_cast(dec_bf16x8, v);
+            }
+        }
+        dec_floatx16 x[2][2];      // [head of the pair][token half]
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            if (k < 2 * heads_here) {
+                const int u = 4 * pair + k;
+                const int i = heads_here == 2 ? (k & 1) : 0, sub = heads_here == 2 ? (k >> 1) : (k & 1);
+                // this unit's eight loads are older than the next unit's eight
+                if (u + 1 < n_units) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+                else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                const char *slot = my_lds + (u & (kMmaSlots - 1)) * kMmaUnitBytes;
+                dec_floatx16 acc = zero;
+#pragma unroll
+                for (int ks = 0; ks < D / 16; ++ks) {
+                    const u32x4_t kb = *reinterpret_cast<const u32x4_t *>(slot + (b_read_off ^ (uint32_t)(32 * ks)));
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(i == 0 ? qa[0][ks] : qa[1][ks], __builtin_bit_cast(dec_bf16x8, kb), acc, 0, 0, 0);
+                }
+                if (i == 0) { if (sub == 0) x[0][0] = acc; else x[0][1] = acc; }
+                else { if (sub == 0) x[1][0] = acc; else x[1][1] = acc; }
+                // the slot is free once its reads have returned; refill it with the unit after next
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                if (u + kMmaSlots < n_units) stage_unit(u + kMmaSlots);
+            }
+        }
+        // register r of half-wave hf is query head 8*(r/4) + 4*hf + r%4 of the group, column = token
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            if (i < heads_here) {
+                const int g = wave + 4 * (2 * pair + i);
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int hh = 8 * (r >> 2) + 4 * hf + (r & 3);
+                    if (hh < grp) {                                      // uniform per half-wave
+                        const int h = g * grp + hh;
+                        float v[2];
+#pragma unroll
+                        for (int sub = 0; sub < 2; ++sub) {
+                            const int t = 32 * sub + ln;
+                            v[sub] = x[i][sub][r] * scale;
+                            if (t < tile_tok) logits[(int64_t)h * n_rows + row0 + t] = v[sub];
+                            else v[sub] = -INFINITY;
+                        }
+                        const float m = half_max(fmaxf(v[0], v[1]));
+                        const float z = half_sum(__expf(v[0] - m) + __expf(v[1] - m));
+                        if (ln == 0) partial[(int64_t)blockIdx.x * n_q_heads + h] = make_float2(m, z);
+                    }
+                }
+            }
+        }
+    }
+}
+
 // ---- 2. softmax statistics per (request, head): merge the tile partials ------------------------------
 __global__ __launch_bounds__(kThreads) void decode_stats_kernel(
     const DecodeBatch bd, int n_q_heads, const float2 *__restrict__ partial,
@@ -198,43 +362,66 @@ __global__ __launch_bounds__(kThreads) void decode_stats_kernel(
 }
 
 // ---- 3. scores ---------------------------------------------------------------------------------
-// One workgroup per kTok-token tile: lane = token, wave w takes KV heads w, w+4, ...; the waves'
-// partial sums are added in a fixed order.
+// One wave per kTok-token tile, lane = token: every load is 64 consecutive floats, there is no
+// LDS and no barrier, and the sum over the KV heads runs in head order.  GRP > 0: the group size
+// is a compile-time constant, so the loads of two KV heads are in flight together.
+template <int GRP>
 __global__ __launch_bounds__(kThreads) void decode_score_kernel(
-    const DecodeBatch bd, int n_q_heads, int n_kv_heads, int64_t n_rows,
+    const DecodeBatch bd, int n_tiles, int n_q_heads, int n_kv_heads, int64_t n_rows,
     const float *__restrict__ logits, const float2 *__restrict__ stats,
     const float *__restrict__ dev_v, const uint8_t *__restrict__ reused, float *__restrict__ score)
 {
     static_assert(kTok == 64, "one token per lane");
-    constexpr int NW = kThreads / 64;
-    __shared__ float part[NW][kTok];
+    const int lane = threadIdx.x & 63;
+    const int tile_id = __builtin_amdgcn_readfirstlane((int)blockIdx.x * (kThreads / 64) + (int)(threadIdx.x >> 6));
+    if (tile_id >= n_tiles) return;
     int b = 0;
-    while (b + 1 < bd.n_req && (int)blockIdx.x >= bd.tile_begin[b + 1]) ++b;
-    const int tile = blockIdx.x - bd.tile_begin[b];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    while (b + 1 < bd.n_req && tile_id >= bd.tile_begin[b + 1]) ++b;
+    const int tile = tile_id - bd.tile_begin[b];
     const int i = tile * kTok + lane;
     const bool live = i < bd.ctx_len[b];
     const int64_t row = bd.ctx_off[b] + min(i, bd.ctx_len[b] - 1);
-    const int grp = n_q_heads / n_kv_heads;
     const float2 *st = stats + (int64_t)(bd.req0 + b) * n_q_heads;
     float s = 0.f;
-    for (int g = wave; g < n_kv_heads; g += NW) {
-        float mass = 0.f;
-        for (int hh = 0; hh < grp; ++hh) {
-            const int h = g * grp + hh;
-            const float2 ms = st[h];
-            mass += __builtin_amdgcn_exp2f((logits[(int64_t)h * n_rows + row] - ms.x) * 1.4426950408889634f) * (1.0f / ms.y);
-        }
-        s += mass * dev_v[(int64_t)g * n_rows + row];
-    }
-    part[wave][lane] = s;
-    __syncthreads();
-    if (wave == 0 && live) {
-        float t = part[0][lane];
+    if constexpr (GRP > 0) {
+        constexpr int GB = 2;                       // KV heads per batch of loads
+        for (int g0 = 0; g0 < n_kv_heads; g0 += GB) {
+            float lg[GB][GRP], dv[GB];
 #pragma unroll
-        for (int w = 1; w < NW; ++w) t += part[w][lane];
+            for (int j = 0; j < GB; ++j) {
+                const int g = min(g0 + j, n_kv_heads - 1);
+#pragma unroll
+                for (int hh = 0; hh < GRP; ++hh) lg[j][hh] = logits[(int64_t)(g * GRP + hh) * n_rows + row];
+                dv[j] = dev_v[(int64_t)g * n_rows + row];
+            }
+#pragma unroll
+            for (int j = 0; j < GB; ++j) {
+                if (g0 + j < n_kv_heads) {
+                    float mass = 0.f;
+#pragma unroll
+                    for (int hh = 0; hh < GRP; ++hh) {
+                        const float2 ms = st[(g0 + j) * GRP + hh];
+                        mass += __builtin_amdgcn_exp2f((lg[j][hh] - ms.x) * 1.4426950408889634f) * (1.0f / ms.y);
+                    }
+                    s += mass * dv[j];
+                }
+            }
+        }
+    } else {
+        const int grp = n_q_heads / n_kv_heads;
+        for (int g = 0; g < n_kv_heads; ++g) {
+            float mass = 0.f;
+            for (int hh = 0; hh < grp; ++hh) {
+                const int h = g * grp + hh;
+                const float2 ms = st[h];
+                mass += __builtin_amdgcn_exp2f((logits[(int64_t)h * n_rows + row] - ms.x) * 1.4426950408889634f) * (1.0f / ms.y);
+            }
+            s += mass * dev_v[(int64_t)g * n_rows + row];
+        }
+    }
+    if (live) {
         const bool cand = reused ? reused[row] != 0 : true;
-        score[row] = cand ? t : -INFINITY;
+        score[row] = cand ? s : -INFINITY;
     }
 }
 
@@ -384,7 +571,21 @@ extern "C" kvs_status kvs_decode_check(const kvs_shape *shape, int32_t batch, in
         else if (regq && grp == 8) KVS_DEC_LAUNCH(DT, L, 8);                   \
         else KVS_DEC_LAUNCH(DT, L, 0);                                         \
     } while (0)
-        if (shape->dtype == KVS_BF16 && lph == 16) KVS_DEC_CASE(KVS_BF16, 16);
+        // bf16 / head_dim 128: the matrix-core kernel, as long as 32-bit byte offsets reach the whole cache
+        const bool mma = shape->dtype == KVS_BF16 && d == 128 && grp <= 32 && n_rows * (int64_t)hk * 256 < ((int64_t)1 << 32) &&
+                         aligned16(q_new) && aligned16(k_cache);
+        if (mma) {
+            static bool attr_set = false;   // idempotent; a race only repeats the same call
+            if (!attr_set) {
+                const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&decode_logits_mfma_kernel),
+                                                         hipFuncAttributeMaxDynamicSharedMemorySize, kMmaLds);
+                if (e != hipSuccess) return fail(KVS_EHIP, "kvs_decode_check: hipFuncSetAttribute: %s", hipGetErrorString(e));
+                attr_set = true;
+            }
+            hipLaunchKernelGGL(decode_logits_mfma_kernel, dim3((unsigned)tiles_tok), block, kMmaLds, hs, bd_tok, hq, hk, n_rows,
+                               (const uint16_t *)q_new, (const uint16_t *)k_cache, scale, logits, part_l);
+        }
+        else if (shape->dtype == KVS_BF16 && lph == 16) KVS_DEC_CASE(KVS_BF16, 16);
         else if (shape->dtype == KVS_BF16 && lph == 8) KVS_DEC_CASE(KVS_BF16, 8);
         else if (shape->dtype == KVS_F32 && lph == 16) KVS_DEC_CASE(KVS_F32, 16);
         else if (shape->dtype == KVS_F32 && lph == 32) KVS_DEC_CASE(KVS_F32, 32);
@@ -394,8 +595,15 @@ extern "C" kvs_status kvs_decode_check(const kvs_shape *shape, int32_t batch, in
         if ((st = check_launch("kvs_decode_check(logits)")) != KVS_OK) return st;
         hipLaunchKernelGGL(decode_stats_kernel, dim3((unsigned)(nr * hq)), block, 0, hs, bd_tok, hq, part_l, stats);
         if ((st = check_launch("kvs_decode_check(stats)")) != KVS_OK) return st;
-        hipLaunchKernelGGL(decode_score_kernel, dim3((unsigned)tiles_tok), block, 0, hs, bd_tok, hq, hk, n_rows,
-                           logits, stats, dev_v, reused, score);
+        const dim3 sgrid((unsigned)((tiles_tok + kThreads / 64 - 1) / (kThreads / 64)));
+#define KVS_DEC_SCORE(G) hipLaunchKernelGGL(decode_score_kernel<G>, sgrid, block, 0, hs, bd_tok, (int)tiles_tok, hq, hk, n_rows, logits, stats, dev_v, reused, score)
+        if (grp == 1) KVS_DEC_SCORE(1);
+        else if (grp == 2) KVS_DEC_SCORE(2);
+        else if (grp == 4) KVS_DEC_SCORE(4);
+        else if (grp == 7) KVS_DEC_SCORE(7);
+        else if (grp == 8) KVS_DEC_SCORE(8);
+        else KVS_DEC_SCORE(0);
+#undef KVS_DEC_SCORE
         if ((st = check_launch("kvs_decode_check(score)")) != KVS_OK) return st;
         if (attn_out) {
             dim3 grid((unsigned)(nr * hk));
