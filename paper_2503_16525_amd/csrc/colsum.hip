@@ -112,7 +112,13 @@ __global__ __launch_bounds__(NT, 2) void colsum_kernel(int n, int n_q_heads, int
     const int last_fixed = min(fb + FIXED, n_fixed) - 1;
     const int t_begin = SWEEP == 1 ? 0 : (int)(((int64_t)fb * grp) / TS);
     const int t_end = SWEEP == 1 ? (int)div_grp((uint32_t)last_fixed) / TS + 1 : (n_stream + TS - 1) / TS;
-    const int t_last = t_end - 1;
+    const int n_tiles = t_end - t_begin;
+    // Step k of a sweep takes tile t_begin + k in sweep 1 and tile t_end - 1 - k in sweep 2: every
+    // workgroup of a KV head then starts at the same end of the streamed tensor (key 0 / the last
+    // query row) whatever its own range, so the workgroups that run together read the same tiles
+    // at the same time and share them through L2.  (Sweep 2 run forwards, each workgroup from its
+    // own first key, fetched 13 GB from HBM per call at 32k instead of well under 1 GB.)
+    auto tile_of = [&](int k) { k = min(k, n_tiles - 1); return SWEEP == 1 ? t_begin + k : t_end - 1 - k; };
 
     auto make_rsrc = [&](const void *base, uint32_t bytes) -> u32x4_t {
         const uint64_t a = reinterpret_cast<uint64_t>(base);
@@ -144,23 +150,44 @@ __global__ __launch_bounds__(NT, 2) void colsum_kernel(int n, int n_q_heads, int
         asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, 0 offen lds"
                      :: "s"(lds_dst), "v"(voff), "s"(lrs));
     };
-    // Any tile index is accepted and clamped to the sweep's last tile, rows past the tensor to its
+    // Any step index is accepted and clamped to the sweep's last step, rows past the tensor to its
     // last row: the sweep requests tiles past its end (into slots nothing reads) so that every step
     // issues the same number of loads and the waits can count them.
-    auto stage_tile = [&](int t) {
-        const uint32_t slot = lds_base + (uint32_t)((t & (RING - 1)) * SLOT_B);
-        t = min(t, t_last);
+    // Offsets of the lane's two rows inside tile 0, with the swizzled piece: a tile wholly inside the
+    // tensor then only adds its own offset (sweep 2: when the group size divides 32, so that every
+    // tile starts at a token boundary; otherwise the row index is split per tile).
+    uint32_t st_off[2];
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+        const uint32_t r = (uint32_t)(16 * half + st_row);
+        if (SWEEP == 1) {
+            st_off[half] = r * k_row_bytes + st_piece;
+        } else {
+            const uint32_t tok = div_grp(r), hh = r - tok * (uint32_t)grp;
+            st_off[half] = tok * q_row_bytes + hh * ROW_B + st_piece;
+        }
+    }
+    const bool even_tiles = SWEEP == 1 || TS % grp == 0;
+    const uint32_t tile_bytes = SWEEP == 1 ? TS * k_row_bytes : (uint32_t)(TS / grp) * q_row_bytes;
+    auto stage_tile = [&](int k) {                  // step k's tile into slot k % RING
+        const uint32_t slot = lds_base + (uint32_t)((k & (RING - 1)) * SLOT_B);
+        const int t = tile_of(k);
+        const bool inside = even_tiles && (t + 1) * TS <= n_stream;      // uniform
 #pragma unroll
         for (int half = 0; half < 2; ++half) {
-            const int sr = min(t * TS + 16 * half + st_row, n_stream - 1);
             uint32_t off;
-            if (SWEEP == 1) {
-                off = (uint32_t)sr * k_row_bytes;
+            if (inside) {
+                off = st_off[half] + (uint32_t)t * tile_bytes;
             } else {
-                const uint32_t tok = div_grp((uint32_t)sr), hh = (uint32_t)sr - tok * (uint32_t)grp;
-                off = tok * q_row_bytes + hh * ROW_B;
+                const int sr = min(t * TS + 16 * half + st_row, n_stream - 1);
+                if (SWEEP == 1) {
+                    off = (uint32_t)sr * k_row_bytes + st_piece;
+                } else {
+                    const uint32_t tok = div_grp((uint32_t)sr), hh = (uint32_t)sr - tok * (uint32_t)grp;
+                    off = tok * q_row_bytes + hh * ROW_B + st_piece;
+                }
             }
-            stage_16(__builtin_amdgcn_readfirstlane(slot + (uint32_t)(16 * half + 4 * wave) * ROW_B), off + st_piece);
+            stage_16(__builtin_amdgcn_readfirstlane(slot + (uint32_t)(16 * half + 4 * wave) * ROW_B), off);
         }
         if (SWEEP == 2 && wave == 0) {
             if (lane < TS) stage_4(__builtin_amdgcn_readfirstlane(slot + TILE_B), (uint32_t)min(t * TS + lane, n_stream - 1) * 4u);
@@ -173,8 +200,8 @@ __global__ __launch_bounds__(NT, 2) void colsum_kernel(int n, int n_q_heads, int
     };
 
     const floatx16 zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-    auto scores = [&](int t, floatx16 (&s)[NB]) {
-        const uint32_t slot_off = (uint32_t)((t & (RING - 1)) * SLOT_B);
+    auto scores = [&](int k, floatx16 (&s)[NB]) {
+        const uint32_t slot_off = (uint32_t)((k & (RING - 1)) * SLOT_B);
 #pragma unroll
         for (int ks = 0; ks < D / 16; ++ks) {
             const u32x4_t a = read_a(slot_off, ks);
@@ -214,19 +241,21 @@ __global__ __launch_bounds__(NT, 2) void colsum_kernel(int n, int n_q_heads, int
         if (SWEEP == 2 && wave == 0) KVS_CS_BARRIER(6);
         else KVS_CS_BARRIER(4);
     };
-    // One sweep over the streamed tiles; f(t, s) consumes the masked scores of tile t.  At the top
-    // of step t the loads of tiles t .. t+2 have been sent; the barrier makes tile t visible to
-    // every wave and tells that every wave is done with tile t-1, whose slot tile t+3 then takes.
+    // One sweep over the streamed tiles; f(k, t, s) consumes the masked scores of step k = tile t.
+    // At the top of step k the loads of steps k .. k+2 have been sent; the barrier makes step k's
+    // tile visible to every wave and tells that every wave is done with step k-1, whose slot step
+    // k+3 then takes.
     auto sweep = [&](auto f) {
 #pragma unroll
-        for (int i = 0; i < RING - 1; ++i) stage_tile(t_begin + i);
-        for (int t = t_begin; t < t_end; ++t) {
+        for (int i = 0; i < RING - 1; ++i) stage_tile(i);
+        for (int k = 0; k < n_tiles; ++k) {
             step_barrier();
-            stage_tile(t + RING - 1);
+            stage_tile(k + RING - 1);
+            const int t = tile_of(k);
             floatx16 s[NB];
-            scores(t, s);
+            scores(k, s);
             mask_tile(t, s);
-            f(t, s);
+            f(k, t, s);
         }
         // nothing may still be on its way into LDS when the ring is reused or the workgroup ends
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -241,7 +270,7 @@ __global__ __launch_bounds__(NT, 2) void colsum_kernel(int n, int n_q_heads, int
                 // exact row maxima
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb) ref[nb] = -INFINITY;
-                sweep([&](int, floatx16 (&s)[NB]) {
+                sweep([&](int, int, floatx16 (&s)[NB]) {
 #pragma unroll
                     for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
@@ -252,8 +281,8 @@ __global__ __launch_bounds__(NT, 2) void colsum_kernel(int n, int n_q_heads, int
             }
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb) acc[nb] = 0.f;
-            sweep([&](int t, floatx16 (&s)[NB]) {
-                if (pass == 0 && t == t_begin) {
+            sweep([&](int k, int, floatx16 (&s)[NB]) {
+                if (pass == 0 && k == 0) {
                     // the reference: the largest score of the row's first tile (key 0 is never masked)
 #pragma unroll
                     for (int nb = 0; nb < NB; ++nb) {
@@ -288,8 +317,8 @@ __global__ __launch_bounds__(NT, 2) void colsum_kernel(int n, int n_q_heads, int
     } else {
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) acc[nb] = 0.f;
-        sweep([&](int t, floatx16 (&s)[NB]) {
-            const char *lp = lds_b + (t & (RING - 1)) * SLOT_B + TILE_B + 16 * hf;
+        sweep([&](int k, int, floatx16 (&s)[NB]) {
+            const char *lp = lds_b + (k & (RING - 1)) * SLOT_B + TILE_B + 16 * hf;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const float4 l4 = *reinterpret_cast<const float4 *>(lp + 32 * i);   // rows 8i + 4hf .. +3
