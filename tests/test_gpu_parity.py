@@ -352,6 +352,54 @@ def test_partial_attention_split_plan_two_requests_unsorted_and_clustered():
     np.testing.assert_allclose(lse2, ref_lse, atol=2e-3)
 
 
+@pytest.mark.parametrize("seed", [1, 2, 3, 4])
+def test_partial_attention_split_plan_random_batches(seed):
+    # random ragged batches in the range where the large kernel cuts its key range (a few row tiles
+    # per request over contexts of thousands of tokens): positions clustered, spread or shuffled,
+    # 1 to 5 requests, KV-head counts 8 / 4 / 2.  The launch with a workspace (device-planned
+    # pieces + merge) must agree with the launch without one (whole key ranges) and, on sampled
+    # rows, with the oracle.
+    rng = np.random.default_rng(1000 + seed)
+    hk = int(rng.choice([8, 4, 2]))
+    grp = int(rng.choice([4, 8]))
+    w = synth.scaled(synth.LLAMA, 0, n_q_heads=hk * grp, n_kv_heads=hk)
+    n_req = int(rng.integers(1, 6))
+    lens = [int(rng.integers(2000, 12000)) for _ in range(n_req)]
+    pad = 2
+    off = np.cumsum([0] + [l + pad for l in lens])[:-1]
+    rows = sum(lens) + pad * n_req
+    say(f"attention split plan, random batch seed {seed}: {hk} kv heads x {grp}, contexts {lens}")
+    g = torch.Generator().manual_seed(2000 + seed)
+    k = torch.randn((rows, hk, w.head_dim), generator=g).to(torch.bfloat16)
+    v = torch.randn((rows, hk, w.head_dim), generator=g).to(torch.bfloat16)
+    sel = []
+    for l in lens:
+        cnt = int(rng.integers(40, 700))
+        kind = rng.integers(0, 3)
+        if kind == 0:      # clustered at the end
+            p = np.arange(l - cnt, l)
+        elif kind == 1:    # spread
+            p = np.sort(rng.choice(l, size=cnt, replace=False))
+        else:              # spread and shuffled
+            p = rng.permutation(rng.choice(l, size=cnt, replace=False))
+        sel.append(p.astype(np.int32))
+    cu = np.cumsum([0] + [len(x) for x in sel])
+    q = (torch.randn((int(cu[-1]), w.n_q_heads, w.head_dim), generator=g) / math.sqrt(w.head_dim)).to(torch.bfloat16)
+    pos = np.concatenate(sel)
+    got_ws, lse_ws = run_gpu_attention(w, q, pos, k, v, 1.0, off, lens, cu)
+    got_no, lse_no = run_gpu_attention(w, q, pos, k, v, 1.0, off, lens, cu, with_workspace=False)
+    assert np.all(np.isfinite(got_ws)) and np.all(np.isfinite(lse_ws))
+    np.testing.assert_allclose(lse_ws, lse_no, atol=2e-3)
+    # oracle on a sample of rows of every request (each with its own context)
+    for b in range(n_req):
+        pick = np.unique(rng.integers(cu[b], cu[b + 1], size=12))
+        ref, ref_lse = oracle.partial_attention(q[pick], pos[pick], k, v, 1.0, [off[b]], [lens[b]], [0, len(pick)])
+        mag = attn_magnitude(q[pick], pos[pick], k, v, 1.0, [off[b]], [lens[b]], [0, len(pick)])
+        assert_attn_close(got_ws[pick], ref, w, mag)
+        assert_attn_close(got_no[pick], ref, w, mag)
+        np.testing.assert_allclose(lse_ws[pick], ref_lse, atol=2e-3)
+
+
 def test_partial_attention_select_all_is_full_prefill():
     w = synth.scaled(synth.LLAMA, 400, span_mean=32.0)
     say("attention select-all == full prefill")
