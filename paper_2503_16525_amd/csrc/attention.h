@@ -49,18 +49,29 @@ kvs_status launch_attention_merge(int64_t n_rows, int n_splits, const float *par
 
 // What the host fixes for a split launch of the 256-row kernel: piece slots per row tile (1: no
 // cutting, nothing else is read), the longest context in key tiles, and the small pieces at the
-// bottom of the context (n_small of small_chunk key tiles).  The size of the large pieces above
-// them is chosen on the device, from the positions; pieces are started from the top of the context
-// down, so the short ones at the bottom come last and level out the finish times.
+// bottom of the context (n_small of small_chunk key tiles).  Two cases cut the key range:
+//   * launches too small to fill the chip: the size of the large pieces is chosen on the device,
+//     from the positions, so that the pieces just fill whole rounds of the compute units;
+//   * launches whose K and V no longer fit the last-level cache (kAttnRangeMajorBytes; the 131k
+//     context): chunk > 0 fixes the piece size so that one key range of one KV head fits an L2.
+//     Workgroups of a KV head that start at different times otherwise sweep K/V at different
+//     places and every one of them streams from HBM on its own (measured: 16 % of the matrix
+//     peak at 131k against 45 % at 32k, where K and V stay cached).
+// Pieces are started from the top of the context down, range by range.
 struct AttnSplitPlan {
     int n_splits;
     int ctx_tiles;
     int small_chunk;
     int n_small;
+    int chunk;          // 0: chosen on the device
 };
-// the device-side plan and the list of piece ids (16 bits each, kAttnSplitMax per row tile, fewer
-// than kAttnSplitBelowWgs row tiles), after the pieces in the workspace
-constexpr size_t kAttnPlanBytes = 16 + 2 * (size_t)kAttnSplitMax * kAttnSplitBelowWgs;
+constexpr int64_t kAttnRangeMajorBytes = (int64_t)192 << 20;   // K + V of a launch above which key ranges are walked in step
+constexpr int kAttnRangeChunk = 256;       // key tiles per piece then: 8192 keys = 4 MiB of K and V per KV head
+constexpr int kAttnPlanMaxTiles = 2048;    // row tiles a planned launch may have
+// the device-side plan and the list of piece ids (16 bits each, kAttnSplitMax per row tile), after
+// the pieces in the workspace
+constexpr size_t kAttnPlanBytes = 16 + 2 * (size_t)kAttnSplitMax * kAttnPlanMaxTiles;
+static_assert(kAttnSplitMax * kAttnPlanMaxTiles <= 65536, "piece ids are 16 bits");
 // 64 query rows per wave (two MFMAs per LDS operand), one wave per SIMD, 256-row tiles.  The plan
 // comes from attention_mfma2_plan, which needs the workspace size.
 AttnSplitPlan attention_mfma2_plan(const kvs_shape *shape, const AttnBatch &bd, size_t workspace_bytes);
@@ -80,7 +91,7 @@ kvs_status launch_attention_mfma(const kvs_shape *shape, const AttnBatch &bd, in
                                  const void *v_cache, float scale, void *out, float *lse_out,
                                  void *workspace, size_t workspace_bytes, hipStream_t st);
 // workspace that lets small launches split their key range (0 bytes still works, unsplit)
-size_t attention_workspace_bytes(const kvs_shape *shape, int32_t batch, int64_t n_sel_total);
+size_t attention_workspace_bytes(const kvs_shape *shape, int32_t batch, int64_t n_rows_total, int64_t n_sel_total);
 bool attention_mfma_supports(const kvs_shape *shape);
 
 } // namespace kvs

@@ -519,7 +519,7 @@ kvs_status launch_attention_mfma(const kvs_shape *shape, const AttnBatch &bd, in
     }
     // with fewer 256-row tiles than compute units the large kernel still wins if the caller's
     // workspace lets it cut the key ranges and its tiles are not mostly padding
-    AttnSplitPlan plan2 = {1, 0, 0, 0};
+    AttnSplitPlan plan2 = {1, 0, 0, 0, 0};
     if (workspace && fits32) plan2 = attention_mfma2_plan(shape, bd, workspace_bytes);
     const int splits2 = plan2.n_splits;
     const bool fills = big_tiles * shape->n_kv_heads >= kAttnBigTileMinGrid;
@@ -527,22 +527,27 @@ kvs_status launch_attention_mfma(const kvs_shape *shape, const AttnBatch &bd, in
     // (below ~50 such tiles the per-workgroup start-up of the large kernel costs more than it gains)
     const bool big = fits32 && (forced ? forced == 2 : fills || (splits2 >= 2 && dense_tiles && big_tiles * shape->n_kv_heads >= 48));
     if (big) {
-        if (fills && !forced) plan2 = {1, 0, 0, 0};
+        if (fills && !forced && plan2.chunk == 0) plan2 = {1, 0, 0, 0, 0};   // fills the chip and stays cached: whole key ranges
         return launch_attention_mfma2(shape, bd, q_sel, sel_pos, k_cache, v_cache, scale, out, lse_out, workspace, plan2, st);
     }
     return launch_mfma_variant<KVS_ATTN_NWAVES>(shape, bd, q_sel, sel_pos, k_cache, v_cache, scale, out, lse_out,
                                                 workspace, workspace_bytes, st);
 }
 
-size_t attention_workspace_bytes(const kvs_shape *shape, int32_t batch, int64_t n_sel_total)
+size_t attention_workspace_bytes(const kvs_shape *shape, int32_t batch, int64_t n_rows_total, int64_t n_sel_total)
 {
-    // pieces are only used for launches below kSplitBelowWgs workgroups, and then at most
-    // kSplitMaxWgs workgroup-pieces of 32*KVS_ATTN_NWAVES rows each exist
     const int64_t rows = n_sel_total * shape->n_q_heads;
     int64_t slots = rows * kSplitMax;
-    // (the 256-row kernel: fewer than kAttnSplitBelowWgs tiles of 256 rows, up to kSplitMax pieces each)
-    const int64_t cap = (int64_t)(kSplitMaxWgs + kSplitBelowWgs) * 256 + (int64_t)batch * 256 * kSplitMax;
-    if (slots > cap) slots = cap;
+    // Launches that fill the chip keep whole key ranges unless their K and V outgrow the last-level
+    // cache (then every row may have up to kSplitMax pieces).  Otherwise pieces are only used below
+    // kSplitBelowWgs workgroups: at most kSplitMaxWgs workgroup-pieces of 32*KVS_ATTN_NWAVES rows
+    // each (128-row kernel) or fewer than kAttnSplitBelowWgs tiles of 256 rows with up to kSplitMax
+    // pieces each (256-row kernel).
+    const int64_t kv_bytes = n_rows_total * shape->n_kv_heads * (int64_t)D * 2 * 2;
+    if (kv_bytes <= kAttnRangeMajorBytes) {
+        const int64_t cap = (int64_t)(kSplitMaxWgs + kSplitBelowWgs) * 256 + (int64_t)batch * 256 * kSplitMax;
+        if (slots > cap) slots = cap;
+    }
     return (size_t)slots * kPartBytesPerSlot + kAttnPlanBytes + 256;
 }
 

@@ -67,6 +67,7 @@ constexpr int K_RING = AHEAD <= 4 ? 4 : 8;   // tiles, >= AHEAD; see the slot ar
 constexpr int V_RING = 8;                    // >= AHEAD + 2
 static_assert(K_RING >= AHEAD && V_RING >= AHEAD + 2, "ring depth");
 constexpr int LDS_BYTES = (K_RING + V_RING) * TILE_B;
+constexpr float kRefShift = 60.0f;      // base-2 offset of the fixed softmax reference above the first tile's maximum
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4_t v) { return __builtin_bit_cast(bf16x8, v); }
 
 __device__ __forceinline__ uint32_t pack2(float lo, float hi)
@@ -474,11 +475,16 @@ __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
 
     // ---- passes -------------------------------------------------------------------------------------------
     // Pass 0 takes each row's exponent reference from its first tile (every row sees key 0) and
-    // never moves it: softmax(x) is invariant to the reference as long as nothing overflows, and
-    // fp32 / bf16 leave 2^127 of headroom.  If a row's sum ends above 2^100 (or inf / nan) some later
-    // logit was more than ~2^6 above the first tile's max; then the workgroup computes the exact
-    // row maxima in a score-only sweep and repeats the pass with those (pass 1), which cannot
-    // overflow.  Real attention logits do not do that, so pass 1 is a correctness net.
+    // never moves it: softmax(x) is invariant to the reference as long as nothing overflows or
+    // underflows.  The reference is the first tile's largest logit plus kRefShift (in base-2 units),
+    // so weights are computed around 2^-60 instead of around 1: fp32 and bf16 share an 8-bit exponent,
+    // nothing loses precision down there, and the sum only passes 2^100 if a later logit lies more
+    // than 160 (111 in natural units) above the first tile's maximum, while a key has to be 2^-66
+    // of the row's largest weight before it is flushed to zero.  (Unshifted, a logit ~2^6 above
+    // the first tile's maximum already overflowed, which heavy-tailed keys do reach: half the
+    // workgroups of a 131k-token launch repeated the pass.)  If a row's sum does end above 2^100 (or
+    // inf / nan) the workgroup computes the exact row maxima in a score-only sweep and repeats the
+    // pass with those (pass 1), which cannot overflow: a correctness net.
     __shared__ int redo_flag;
     float l_tot[NB];
 #ifdef KVS_DIAG_CLOCK
@@ -518,7 +524,7 @@ __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
             // a row whose keys all lie before this piece sees nothing here: a finite reference keeps
             // its weights at exp2(-inf) = 0 instead of NaN (the merge drops pieces with zero sum)
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb) m_ref[nb] = fmaxf(row_max(s_cur[nb]), -1.0e30f);
+            for (int nb = 0; nb < NB; ++nb) m_ref[nb] = fmaxf(row_max(s_cur[nb]), -1.0e30f) + kRefShift;
         }
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) { l_run[nb] = 0.f; l_exact[nb] = 0.f; }
@@ -589,11 +595,15 @@ __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
     }
 
 #ifdef KVS_DIAG_CLOCK
-    if (tid == 0 && blockIdx.x < 1024) {
-        kvs_diag_clk[4 * blockIdx.x] = clock64() - diag_t0;
-        kvs_diag_clk[4 * blockIdx.x + 1] = wall_clock64() - diag_w0;
-        kvs_diag_clk[4 * blockIdx.x + 2] = (t_hi - t_lo) + 4096 * max(0, t_hi - max(t_lo, (pmin + 1) / BN)) + 4096 * 4096 * (long long)diag_pass;
-        kvs_diag_clk[4 * blockIdx.x + 3] = diag_w0;
+#ifndef KVS_DIAG_FIRST
+#define KVS_DIAG_FIRST 0
+#endif
+    if (tid == 0 && blockIdx.x >= KVS_DIAG_FIRST && blockIdx.x < KVS_DIAG_FIRST + 1024) {
+        const int di = blockIdx.x - KVS_DIAG_FIRST;
+        kvs_diag_clk[4 * di] = clock64() - diag_t0;
+        kvs_diag_clk[4 * di + 1] = wall_clock64() - diag_w0;
+        kvs_diag_clk[4 * di + 2] = (t_hi - t_lo) + 4096 * max(0, t_hi - max(t_lo, (pmin + 1) / BN)) + 4096 * 4096 * (long long)diag_pass;
+        kvs_diag_clk[4 * di + 3] = diag_w0;
     }
 #endif
     // ---- epilogue: normalise, convert, store ----------------------------------------------------------
@@ -655,7 +665,7 @@ namespace {
 // hands out workgroups strictly in order, so empty pieces in between starve the pieces behind
 // them: the list names the pieces with keys first and all empty slots after them.
 constexpr int PLAN_NT = 256;
-constexpr int PLAN_MAX_TILES = kAttnSplitBelowWgs;   // a split launch has fewer row tiles than this
+constexpr int PLAN_MAX_TILES = kAttnPlanMaxTiles;
 constexpr int PLAN_MAX_ROUNDS = 4;
 __global__ __launch_bounds__(PLAN_NT) void attn_plan_kernel(
     const AttnTiles td, int grp, int n_kv_heads, int total_tiles, const int32_t *__restrict__ sel_pos,
@@ -684,7 +694,7 @@ __global__ __launch_bounds__(PLAN_NT) void attn_plan_kernel(
     const int c_max = max(c_min, ctx_tiles - bottom);
     const int step = (c_max - c_min + PLAN_NT - 1) / PLAN_NT;
     const int c = c_min + tid * step;
-    const bool tries = c <= c_max && (step > 0 || tid == 0);
+    const bool tries = forced_chunk <= 0 && c <= c_max && (step > 0 || tid == 0);   // a fixed chunk needs no search
     int pieces = 0x7fffffff;
     if (tries) {
         const float rc = 1.0f / (float)c;
@@ -773,15 +783,19 @@ kvs_status launch_one(const dim3 grid, size_t lds_bytes, hipStream_t st, const A
 
 AttnSplitPlan attention_mfma2_plan(const kvs_shape *shape, const AttnBatch &bd, size_t workspace_bytes)
 {
-    const AttnSplitPlan whole = {1, 0, 0, 0};
+    const AttnSplitPlan whole = {1, 0, 0, 0, 0};
     const int grp = shape->n_q_heads / shape->n_kv_heads;
-    int64_t tiles = 0, max_ctx = 0;
+    int64_t tiles = 0, max_ctx = 0, kv_bytes = 0;
     for (int i = 0; i < bd.n_req; ++i) {
         tiles += ((bd.cu_sel[i + 1] - bd.cu_sel[i]) * grp + ROWS - 1) / ROWS;
         max_ctx = bd.ctx_len[i] > max_ctx ? bd.ctx_len[i] : max_ctx;
+        if (bd.cu_sel[i + 1] > bd.cu_sel[i]) kv_bytes += bd.ctx_len[i] * (int64_t)shape->n_kv_heads * ROW_B * 2;
     }
     const int64_t wgs = tiles * shape->n_kv_heads;
-    if (wgs <= 0 || wgs >= kAttnSplitBelowWgs) return whole;
+    if (wgs <= 0 || tiles > kAttnPlanMaxTiles) return whole;
+    const bool small_launch = wgs < kAttnSplitBelowWgs;
+    const bool range_major = !small_launch && kv_bytes > kAttnRangeMajorBytes;
+    if (!small_launch && !range_major) return whole;
     const int64_t ctx_tiles = (max_ctx + BN - 1) / BN;
     const int64_t n_rows_total = (bd.cu_sel[bd.n_req] - bd.cu_sel[0]) * shape->n_q_heads;
     int64_t s_max = kAttnSplitMax;
@@ -791,11 +805,19 @@ AttnSplitPlan attention_mfma2_plan(const kvs_shape *shape, const AttnBatch &bd, 
     const int64_t by_ws = (int64_t)((workspace_bytes - kAttnPlanBytes) / (kAttnPartBytesPerSlot * (size_t)(n_rows_total > 0 ? n_rows_total : 1)));
     if (s_max > by_ws) s_max = by_ws;
     if (s_max < 2) return whole;
+    if (range_major) {
+        // as small a piece as the slots allow, down to the one whose K and V fit an L2
+        int64_t chunk = (ctx_tiles + s_max - 1) / s_max;
+        if (chunk < kAttnRangeChunk) chunk = kAttnRangeChunk;
+        const int64_t n = (ctx_tiles + chunk - 1) / chunk;
+        if (n < 2) return whole;
+        return AttnSplitPlan{(int)n, (int)ctx_tiles, 0, 0, (int)chunk};
+    }
     // Small pieces at the bottom of the context (every row tile has them, and they start last)
     // fill the gaps the large ones leave; they pay off once the large pieces can be several times
     // their size.
     const bool taper = s_max >= 6 && ctx_tiles >= 8 * kAttnSmallChunk;
-    return AttnSplitPlan{(int)s_max, (int)ctx_tiles, kAttnSmallChunk, taper ? kAttnSmallPieces : 0};
+    return AttnSplitPlan{(int)s_max, (int)ctx_tiles, kAttnSmallChunk, taper ? kAttnSmallPieces : 0, 0};
 }
 
 kvs_status launch_attention_mfma2(const kvs_shape *shape, const AttnBatch &bd, const void *q_sel,
@@ -829,7 +851,7 @@ kvs_status launch_attention_mfma2(const kvs_shape *shape, const AttnBatch &bd, c
     int4 *split_plan = (int4 *)(ml_base + n_rows_total * n_splits);
     uint16_t *piece_list = (uint16_t *)(split_plan + 1);
     float round_fill = kAttnRoundFill, piece_overhead = kAttnPieceOverhead;
-    int forced_chunk = 0, small_chunk = plan.small_chunk, n_small = plan.n_small;
+    int forced_chunk = plan.chunk, small_chunk = plan.small_chunk, n_small = plan.n_small;
 #ifdef KVS_DIAG_CHUNK
     if (const char *e = getenv("KVS_ATTN_SMALL")) small_chunk = atoi(e);
     if (const char *e = getenv("KVS_ATTN_NSMALL")) n_small = atoi(e);

@@ -16,7 +16,8 @@
 // workgroups share a compute unit and the hardware overlaps one wave's MFMAs with another's
 // vector work.
 //
-// Sweep 1 uses a fixed exponent reference per row, taken from the row's first key tile; if a sum
+// Sweep 1 uses a fixed exponent reference per row, taken from the row's first key tile (plus a
+// shift that centres the fp32 exponent range); if a sum
 // ends above 2^100 the workgroup finds the exact row maxima in a score-only sweep and repeats.
 // Sweep 2 needs none: exp(score - lse) <= 1.  No atomics: the result is identical from run to run.
 #include "kvs_internal.h"
@@ -40,6 +41,9 @@ constexpr int TILE_B = TS * ROW_B;
 constexpr int SLOT_B = TILE_B + 256;    // a tile and the 32 log-sum-exps of its rows (sweep 2)
 constexpr int RING = 4;                 // slots; tiles are requested RING - 1 steps ahead
 constexpr int LDS_BYTES = RING * SLOT_B;
+// base-2 offset of sweep 1's fixed reference above the first tile's maximum: the row sums are then
+// taken around 2^-60, where fp32 is as precise as around 1, and only overflow for a logit 160 above
+constexpr float kRefShift = 60.0f;
 
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4_t v) { return __builtin_bit_cast(bf16x8, v); }
 
@@ -289,7 +293,7 @@ __global__ __launch_bounds__(NT, 2) void colsum_kernel(int n, int n_q_heads, int
                         float mx = s[nb][0];
 #pragma unroll
                         for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[nb][r]);
-                        ref[nb] = fmaxf(mx, __shfl_xor(mx, 32)) * scale_log2;
+                        ref[nb] = fmaxf(mx, __shfl_xor(mx, 32)) * scale_log2 + kRefShift;
                     }
                 }
 #pragma unroll

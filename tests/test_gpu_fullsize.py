@@ -85,6 +85,18 @@ def prefill_layer(w, ratio, n_sample, projected):
     o = out.float()
     assert bool(torch.isfinite(o).all()) and bool(torch.isfinite(lse).all())
     assert float(o.abs().max()) <= float(gv.float().abs().max()) * (1 + 2.0 ** -7)
+    # the same launch with a workspace, as bench.py passes one: small launches (the 5 % selection)
+    # and contexts beyond the last-level cache (131k) then cut their key ranges into pieces
+    ws = torch.empty(B.kvs_workspace_size("partial_attention", sh, 1, n, k), dtype=torch.uint8, device=DEV)
+    out2 = torch.full_like(out, float("nan"))
+    lse2 = torch.full_like(lse, float("nan"))
+    B.kvs_partial_attention(sh, [0], [n], [0, k], q_sel, idx, gk, gv, 1.0, out2, lse2, workspace=ws)
+    torch.cuda.synchronize()
+    attn_close(out2[pick].float().cpu().numpy(), ref, mag)
+    np.testing.assert_allclose(lse2[pick].cpu().numpy(), ref_lse, atol=2e-3)
+    assert bool(torch.isfinite(out2.float()).all()) and bool(torch.isfinite(lse2).all())
+    np.testing.assert_allclose(lse2.cpu().numpy(), lse.cpu().numpy(), atol=2e-3)
+    del ws, out2, lse2
     return lay, gk, gv, gr, dev_v, idx_ref
 
 
