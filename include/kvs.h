@@ -197,8 +197,9 @@ KVS_API kvs_status kvs_decode_check(const kvs_shape *shape, int32_t batch, int64
  * row's log-sum-exp in the workspace, a second one sums exp(score - lse) down the columns.
  * Cost: two passes of n_tokens^2 / 2 * head_dim * n_q_heads multiply-adds on the matrix cores.
  *
- * Built for bf16 with head_dim 128 (KVS_EUNSUPPORTED otherwise, and for scale <= 0 or tensors of
- * 4 GiB and more).  Q and K as for the other calls: [n_tokens, heads, head_dim], 16-byte aligned.
+ * bf16 with head_dim 128 and a positive scale runs on the matrix cores (tensors below 4 GiB);
+ * every other supported shape, fp32 included, takes a plain vector kernel that is only meant for
+ * small problems.  Q and K as for the other calls: [n_tokens, heads, head_dim], 16-byte aligned.
  *
  * q         [dev] [n_tokens, n_q_heads, head_dim]
  * k         [dev] [n_tokens, n_kv_heads, head_dim] (the fresh keys)

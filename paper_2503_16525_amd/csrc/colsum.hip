@@ -380,17 +380,19 @@ extern "C" kvs_status kvs_attn_colsum(const kvs_shape *shape, int64_t n_tokens, 
     if (st != KVS_OK) return st;
     if (n_tokens < 0) return fail(KVS_EINVAL, "kvs_attn_colsum: n_tokens < 0");
     if (n_tokens == 0) return KVS_OK;
-    if (shape->dtype != KVS_BF16 || shape->head_dim != D)
-        return fail(KVS_EUNSUPPORTED, "kvs_attn_colsum: bf16 with head_dim 128 is built");
-    if (!(scale > 0.f) || !isfinite(scale)) return fail(KVS_EUNSUPPORTED, "kvs_attn_colsum: needs a positive finite scale");
+    if (!isfinite(scale)) return fail(KVS_EINVAL, "kvs_attn_colsum: scale is not finite");
     if (!q || !k || !alpha) return fail(KVS_EINVAL, "kvs_attn_colsum: NULL tensor pointer");
     if (!aligned16(q) || !aligned16(k)) return fail(KVS_EINVAL, "kvs_attn_colsum: Q/K pointers must be 16-byte aligned");
-    // rows are addressed with 32-bit byte offsets and divided by the group size with a 24-bit trick
-    if (n_tokens * shape->n_q_heads * (int64_t)ROW_B >= ((int64_t)1 << 32) || n_tokens * (shape->n_q_heads / shape->n_kv_heads) >= (1 << 24))
-        return fail(KVS_EUNSUPPORTED, "kvs_attn_colsum: %lld tokens x %d heads exceed the 4 GiB the kernel addresses", (long long)n_tokens, shape->n_q_heads);
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return fail(KVS_EINVAL, "kvs_attn_colsum: workspace must be given, 256-byte aligned");
     if (workspace_bytes < colsum_workspace_bytes(shape, n_tokens))
         return fail(KVS_EWORKSPACE, "kvs_attn_colsum: workspace of %zu bytes, %zu needed", workspace_bytes, colsum_workspace_bytes(shape, n_tokens));
+    // the matrix-core kernel: bf16, head_dim 128, a positive scale (it folds the scale into an exp2
+    // argument after taking maxima), rows addressed with 32-bit byte offsets and divided by the group
+    // size with a 24-bit trick.  Everything else takes the plain vector kernels.
+    const bool mfma = shape->dtype == KVS_BF16 && shape->head_dim == D && scale > 0.f;
+    if (!mfma) return launch_colsum_valu(shape, n_tokens, q, k, scale, (float *)workspace, alpha, (hipStream_t)stream);
+    if (n_tokens * shape->n_q_heads * (int64_t)ROW_B >= ((int64_t)1 << 32) || n_tokens * (shape->n_q_heads / shape->n_kv_heads) >= (1 << 24))
+        return fail(KVS_EUNSUPPORTED, "kvs_attn_colsum: %lld tokens x %d heads exceed the 4 GiB the kernel addresses", (long long)n_tokens, shape->n_q_heads);
     float *lse2 = (float *)workspace;
     const float scale_log2 = scale * 1.4426950408889634f;
     hipStream_t hs = (hipStream_t)stream;

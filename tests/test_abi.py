@@ -123,13 +123,17 @@ def test_attn_colsum_argument_errors(lib):
         return lib.kvs_attn_colsum(ctypes.byref(shape), n, q, k, scale, alpha, ws, ws_bytes, None)
     assert call(n=-1) == B.EINVAL
     assert call(n=0, q=None, k=None, alpha=None, ws=None, ws_bytes=0) == B.OK      # empty: no-op
-    assert call(shape=_shape(dt=B.F32, d=64, hq=4, hk=4)) == B.EUNSUPPORTED
-    assert call(scale=0.0) == B.EUNSUPPORTED
-    assert call(scale=float("nan")) == B.EUNSUPPORTED
+    assert call(scale=float("nan")) == B.EINVAL
     assert call(q=None) == B.EINVAL
     assert call(k=FAKE + 8) == B.EINVAL
     assert call(ws=None) == B.EINVAL
     assert call(ws=FAKE * 16 + 64) == B.EINVAL                # workspace alignment
     assert call(ws_bytes=need - 1) == B.EWORKSPACE
-    assert call(n=1 << 20) == B.EUNSUPPORTED                  # 8 GiB of queries: past the 32-bit offsets
+    big = 1 << 20                                             # 8 GiB of queries: past the 32-bit offsets
+    assert call(n=big, ws_bytes=B.kvs_workspace_size("attn_colsum", sh, 1, big)) == B.EUNSUPPORTED
     assert b"4 GiB" in lib.kvs_last_error()
+    # shapes without a matrix-core kernel take the vector path, which refuses long contexts
+    f32 = _shape(dt=B.F32, d=64, hq=4, hk=4)
+    n_long = 1 << 17
+    assert call(shape=f32, n=n_long, ws_bytes=B.kvs_workspace_size("attn_colsum", f32, 1, n_long)) == B.EUNSUPPORTED
+    assert b"vector path" in lib.kvs_last_error()

@@ -514,6 +514,28 @@ def test_attn_colsum_parity(name, w):
     np.testing.assert_allclose(got2, ref2, rtol=COLSUM_RTOL, atol=COLSUM_ATOL)
 
 
+VALU_COLSUM_CASES = [
+    ("tiny-f32", synth.TINY, 1.0, 2e-5),
+    ("f32-d128-g2", synth.scaled(synth.TINY, 512, head_dim=128, n_q_heads=4, n_kv_heads=2), 1.0, 2e-5),
+    ("bf16-d64", synth.scaled(synth.QWEN, 700, head_dim=64, n_kv_heads=2, n_q_heads=4, span_mean=32.0), 1.0, 2e-5),
+    ("bf16-d128-negative-scale", synth.scaled(synth.LLAMA, 333, span_mean=32.0), -0.5, 2e-5),
+]
+
+
+@pytest.mark.parametrize("name,w,scale,rtol", VALU_COLSUM_CASES, ids=[c[0] for c in VALU_COLSUM_CASES])
+def test_attn_colsum_vector_path(name, w, scale, rtol):
+    # shapes (and scales) without a matrix-core kernel: exact fp32 arithmetic on the same inputs,
+    # so the agreement with the oracle is at fp32 rounding level
+    say(f"attention column mass, vector path {name}")
+    lay = synth.make_layer(w)
+    q, k = lay["q"], lay["k_fresh"]
+    _, ref = oracle.alpha_prefill(q, k, scale)
+    got = run_gpu_colsum(w, q, k, scale)
+    np.testing.assert_allclose(got, ref, rtol=rtol, atol=1e-7)
+    grp = w.n_q_heads // w.n_kv_heads
+    np.testing.assert_allclose(got.sum(axis=1), np.full(w.n_kv_heads, w.n_ctx * grp), rtol=1e-5)
+
+
 def test_attn_colsum_feeds_deviation_like_the_oracle_alpha():
     # Alg. 1 on the GPU end to end: alpha from kvs_attn_colsum into kvs_deviation; the scores agree
     # with the oracle's (own alpha, own deviation) to the column mass's tolerance
