@@ -146,9 +146,11 @@ KVS_API kvs_status kvs_scatter_kv(const kvs_shape *shape, int64_t n_rows,
  * lse_out [dev] fp32[n_sel, n_q_heads] or NULL
  * workspace [dev] optional (NULL / 0 is valid), 256-byte aligned.  With at least
  *         kvs_workspace_size("partial_attention", ...) bytes, launches too small to fill the chip
- *         (few selected tokens over long contexts, e.g. the decode-stage recompute) cut each row
- *         tile's key range into pieces handled by separate workgroups and merge them; results
- *         are the same up to fp32 summation order.
+ *         (few selected tokens over long contexts, e.g. the decode-stage recompute), and single
+ *         requests whose K and V outgrow the last-level cache (above 192 MiB: then the size asked
+ *         for is 528 bytes x 16 per output row), cut each row tile's key range into pieces
+ *         handled by separate workgroups and merge them; results are the same up to fp32
+ *         summation order.  With less, such launches keep whole key ranges.
  * bf16 inputs (head_dim 128, scale > 0) are contracted on the matrix cores with fp32 accumulation
  * and an fp32 softmax, the softmax weights entering the second product as bf16; every other case
  * takes an fp32 vector path.

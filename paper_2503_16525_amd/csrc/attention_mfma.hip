@@ -543,8 +543,10 @@ size_t attention_workspace_bytes(const kvs_shape *shape, int32_t batch, int64_t 
     // kSplitBelowWgs workgroups: at most kSplitMaxWgs workgroup-pieces of 32*KVS_ATTN_NWAVES rows
     // each (128-row kernel) or fewer than kAttnSplitBelowWgs tiles of 256 rows with up to kSplitMax
     // pieces each (256-row kernel).
+    // (a batch is sized for the capped case: with several requests the rows say nothing about the
+    // longest one, and a launch whose workspace is too small for pieces keeps whole key ranges)
     const int64_t kv_bytes = n_rows_total * shape->n_kv_heads * (int64_t)D * 2 * 2;
-    if (kv_bytes <= kAttnRangeMajorBytes) {
+    if (batch > 1 || kv_bytes <= kAttnRangeMajorBytes) {
         const int64_t cap = (int64_t)(kSplitMaxWgs + kSplitBelowWgs) * 256 + (int64_t)batch * 256 * kSplitMax;
         if (slots > cap) slots = cap;
     }

@@ -789,7 +789,11 @@ AttnSplitPlan attention_mfma2_plan(const kvs_shape *shape, const AttnBatch &bd, 
     for (int i = 0; i < bd.n_req; ++i) {
         tiles += ((bd.cu_sel[i + 1] - bd.cu_sel[i]) * grp + ROWS - 1) / ROWS;
         max_ctx = bd.ctx_len[i] > max_ctx ? bd.ctx_len[i] : max_ctx;
-        if (bd.cu_sel[i + 1] > bd.cu_sel[i]) kv_bytes += bd.ctx_len[i] * (int64_t)shape->n_kv_heads * ROW_B * 2;
+        // (what has to stay cached is one request's K and V: requests do not share keys)
+        if (bd.cu_sel[i + 1] > bd.cu_sel[i]) {
+            const int64_t b = bd.ctx_len[i] * (int64_t)shape->n_kv_heads * ROW_B * 2;
+            kv_bytes = b > kv_bytes ? b : kv_bytes;
+        }
     }
     const int64_t wgs = tiles * shape->n_kv_heads;
     if (wgs <= 0 || tiles > kAttnPlanMaxTiles) return whole;
