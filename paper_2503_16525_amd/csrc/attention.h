@@ -19,9 +19,13 @@ struct AttnBatch {
 
 // Per-launch table for the matrix-core kernels: request geometry plus the first row tile of each
 // request in the launch's grid (row tiles never span requests).
+// The entries are the launch's requests ordered by context length, longest last: the kernels take
+// row tiles from the end of the table, so the workgroups with the longest sweeps start first and
+// the short ones fill the end of the launch.
 struct AttnTiles {
     int64_t ctx_off[kAttnMaxReq];
-    int64_t cu_sel[kAttnMaxReq + 1];
+    int64_t sel_lo[kAttnMaxReq];      // first selected token of the entry's request (global numbering)
+    int32_t n_sel[kAttnMaxReq];       // and how many
     int32_t ctx_len[kAttnMaxReq];
     int32_t tile_begin[kAttnMaxReq + 1];
     int32_t n_req;

@@ -93,8 +93,8 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_mfma_kernel(
     while (b + 1 < td.n_req && tile_lin >= td.tile_begin[b + 1]) ++b;
     const int tile = tile_lin - td.tile_begin[b];
     const int grp = n_q_heads / n_kv_heads;
-    const int64_t sel0 = td.cu_sel[b];
-    const int n_rows = (int)(td.cu_sel[b + 1] - sel0) * grp;
+    const int64_t sel0 = td.sel_lo[b];
+    const int n_rows = td.n_sel[b] * grp;
     const int ctx_len = td.ctx_len[b];
     const int64_t ctx_off = td.ctx_off[b];
 
@@ -471,17 +471,26 @@ kvs_status launch_attention_merge(int64_t n_rows, int n_splits, const float *par
 int64_t build_attn_tiles(const kvs_shape *shape, const AttnBatch &bd, int rows_per_tile, AttnTiles &td)
 {
     const int grp = shape->n_q_heads / shape->n_kv_heads;
+    // requests by context length, ascending (insertion sort: at most kAttnMaxReq entries, usually
+    // already in order); ties keep the caller's order
+    int order[kAttnMaxReq];
+    for (int i = 0; i < bd.n_req; ++i) {
+        int j = i;
+        while (j > 0 && bd.ctx_len[order[j - 1]] > bd.ctx_len[i]) { order[j] = order[j - 1]; --j; }
+        order[j] = i;
+    }
     int64_t tiles = 0;
-    for (int i = 0; i < kAttnMaxReq; ++i) {
-        const bool live = i < bd.n_req;
-        td.ctx_off[i] = live ? bd.ctx_off[i] : 0;
-        td.ctx_len[i] = live ? (int32_t)bd.ctx_len[i] : 0;
-        td.cu_sel[i] = bd.cu_sel[i];
-        td.tile_begin[i] = (int32_t)tiles;
-        if (live) tiles += ((bd.cu_sel[i + 1] - bd.cu_sel[i]) * grp + rows_per_tile - 1) / rows_per_tile;
+    for (int e = 0; e < kAttnMaxReq; ++e) {
+        const bool live = e < bd.n_req;
+        const int i = live ? order[e] : 0;
+        td.ctx_off[e] = live ? bd.ctx_off[i] : 0;
+        td.ctx_len[e] = live ? (int32_t)bd.ctx_len[i] : 0;
+        td.sel_lo[e] = live ? bd.cu_sel[i] : 0;
+        td.n_sel[e] = live ? (int32_t)(bd.cu_sel[i + 1] - bd.cu_sel[i]) : 0;
+        td.tile_begin[e] = (int32_t)tiles;
+        if (live) tiles += ((int64_t)td.n_sel[e] * grp + rows_per_tile - 1) / rows_per_tile;
         if (tiles * shape->n_kv_heads > 0x7fffffffLL) return -1;
     }
-    td.cu_sel[kAttnMaxReq] = bd.cu_sel[kAttnMaxReq];
     td.tile_begin[kAttnMaxReq] = (int32_t)tiles;
     td.n_req = bd.n_req;
     return tiles;

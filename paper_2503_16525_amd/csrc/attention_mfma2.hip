@@ -131,8 +131,8 @@ __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
     while (b + 1 < td.n_req && tile_lin >= td.tile_begin[b + 1]) ++b;
     const int tile = tile_lin - td.tile_begin[b];
     const int grp = n_q_heads / n_kv_heads;
-    const int64_t sel0 = td.cu_sel[b];
-    const int n_rows = (int)(td.cu_sel[b + 1] - sel0) * grp;
+    const int64_t sel0 = td.sel_lo[b];
+    const int n_rows = td.n_sel[b] * grp;
     // Row tiles are aligned to the end of the request's rows: the one partly filled tile is then the
     // first, whose rows sit lowest in the context and see the fewest keys, so the padding lanes of
     // the launch idle through the shortest sweep instead of the longest.
@@ -682,9 +682,9 @@ __global__ __launch_bounds__(PLAN_NT) void attn_plan_kernel(
         int b = 0;
         while (b + 1 < td.n_req && t >= td.tile_begin[b + 1]) ++b;
         const int tile = t - td.tile_begin[b];
-        const int n_rows = (int)(td.cu_sel[b + 1] - td.cu_sel[b]) * grp;
+        const int n_rows = td.n_sel[b] * grp;
         const int last_row = (tile + 1) * ROWS - ((td.tile_begin[b + 1] - td.tile_begin[b]) * ROWS - n_rows) - 1;   // tiles end-aligned
-        int p = sel_pos[td.cu_sel[b] + last_row / grp];
+        int p = sel_pos[td.sel_lo[b] + last_row / grp];
         p = min(max(p, 0), td.ctx_len[b] - 1);
         len[t] = p / BN + 1;
     }
