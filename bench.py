@@ -239,7 +239,7 @@ def main() -> int:
                     help="attention column mass fed to kvs_deviation: none = magnitude-only score (alpha = 1, the "
                          "headline workload), synthetic = a fixed harmonic-tail profile, gpu = the exact Alg. 1 alpha, "
                          "produced by kvs_attn_colsum inside every timed step (adds two sweeps of the N x N score matrix)")
-    ap.add_argument("--cpu-sample", type=int, default=256, help="selected queries in the oracle's attention sample (0 = skip the CPU leg)")
+    ap.add_argument("--cpu-sample", type=int, default=1024, help="selected queries in the oracle's attention sample (0 = skip the CPU leg)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build is single-GPU by design (one process, one MI355X); run with --gpus 1",
