@@ -426,56 +426,126 @@ __global__ __launch_bounds__(kThreads) void decode_score_kernel(
 }
 
 // ---- 5. optional decode attention output -------------------------------------------------------
-// one workgroup per (request, kv head); thread = (half, channel); tokens split even/odd over halves
-template <int DTYPE, int D>
-__global__ __launch_bounds__(kThreads) void decode_attn_kernel(
-    const DecodeBatch bd, int n_q_heads, int n_kv_heads, int64_t n_rows,
+// sum_i a[h, i] * V_i.  The V stream is cut into tiles of kAttTok tokens; a workgroup takes one
+// tile of one KV head (LPH lanes per 256-byte row, 16 bytes per lane, several rows in flight per
+// lane), computes the tile's weights once from the stored logits and the softmax statistics, and leaves the
+// tile's share of the group's outputs in the workspace; a second kernel adds the tiles of a
+// request in order.  (One workgroup per (request, KV head), as this used to be, took 14 ms for a
+// single 32k context: eight workgroups on a 256-unit chip.)
+constexpr int kAttTok = 256;
+constexpr int kAttMaxG = 8;        // query heads of a group handled per sweep over V
+
+template <int DTYPE, int LPH>
+__global__ __launch_bounds__(kThreads) void decode_attn_partial_kernel(
+    const DecodeBatch bd /* tile_begin counts kAttTok-token tiles */, int n_q_heads, int n_kv_heads, int64_t n_rows,
     const float *__restrict__ logits, const float2 *__restrict__ stats,
-    const void *__restrict__ v_cache, void *__restrict__ attn_out)
+    const uint4 *__restrict__ v_cache, float *__restrict__ part /* [tile][n_q_heads][D] */)
 {
-    constexpr int MAXG = 8;
-    constexpr int PARTS = kThreads / D;
-    __shared__ float part[PARTS][MAXG][D];
-    const int b = blockIdx.x / n_kv_heads, g = blockIdx.x % n_kv_heads;
-    const int len = bd.ctx_len[b];
-    const int64_t row0 = bd.ctx_off[b];
+    constexpr int EPL = DTYPE == KVS_BF16 ? 8 : 4;
+    constexpr int D = LPH * EPL;
+    constexpr int SLOTS = kThreads / LPH;          // rows a workgroup works on at once
+    constexpr int UNROLL = 4;
+    __shared__ float red[kThreads / 64][kAttMaxG][D];
+    __shared__ __align__(16) float wts[kAttTok][kAttMaxG];
+    static_assert(kAttTok == kThreads, "one token per thread in the weights step");
+    const int g = blockIdx.x % n_kv_heads;
+    const int tile_id = blockIdx.x / n_kv_heads;
+    int b = 0;
+    while (b + 1 < bd.n_req && tile_id >= bd.tile_begin[b + 1]) ++b;
+    const int tok0 = (tile_id - bd.tile_begin[b]) * kAttTok;
+    const int ntok = min(kAttTok, bd.ctx_len[b] - tok0);
+    const int64_t row0 = bd.ctx_off[b] + tok0;
     const int grp = n_q_heads / n_kv_heads;
-    const int c = threadIdx.x % D, part_id = threadIdx.x / D;
+    const int tid = threadIdx.x, sub = tid % LPH, slot = tid / LPH, wave = tid >> 6, lane = tid & 63;
     const float2 *st = stats + (int64_t)(bd.req0 + b) * n_q_heads;
-    for (int h0 = 0; h0 < grp; h0 += MAXG) {
-        const int nh = min(MAXG, grp - h0);
-        float acc[MAXG];
-        float mx[MAXG], inv[MAXG];
+    for (int h0 = 0; h0 < grp; h0 += kAttMaxG) {
+        const int nh = min(kAttMaxG, grp - h0);
+        float acc[kAttMaxG][EPL];
 #pragma unroll
-        for (int hh = 0; hh < MAXG; ++hh) {
-            acc[hh] = 0.f;
-            const float2 ms = hh < nh ? st[g * grp + h0 + hh] : make_float2(0.f, 1.f);
-            mx[hh] = ms.x;
-            inv[hh] = 1.0f / ms.y;
-        }
-        for (int i = part_id; i < len; i += PARTS) {
-            const int64_t gi = ((row0 + i) * n_kv_heads + g) * (int64_t)D + c;
-            float v;
-            if (DTYPE == KVS_F32) v = ((const float *)v_cache)[gi];
-            else v = __uint_as_float((uint32_t)((const uint16_t *)v_cache)[gi] << 16);
+        for (int hh = 0; hh < kAttMaxG; ++hh)
 #pragma unroll
-            for (int hh = 0; hh < MAXG; ++hh)
-                if (hh < nh) acc[hh] += expf(logits[(int64_t)(g * grp + h0 + hh) * n_rows + row0 + i] - mx[hh]) * inv[hh] * v;
-        }
+            for (int e = 0; e < EPL; ++e) acc[hh][e] = 0.f;
+        // the tile's weights once, one token per thread (the logits of a head are contiguous over tokens)
+        if (tid < ntok) {
 #pragma unroll
-        for (int hh = 0; hh < MAXG; ++hh) part[part_id][hh][c] = acc[hh];
-        __syncthreads();
-        if (part_id == 0) {
-            for (int hh = 0; hh < nh; ++hh) {
-                float s = 0.f;
-                for (int pp = 0; pp < PARTS; ++pp) s += part[pp][hh][c];
-                const int64_t oi = ((int64_t)(bd.req0 + b) * n_q_heads + g * grp + h0 + hh) * D + c;
-                if (DTYPE == KVS_F32) ((float *)attn_out)[oi] = s;
-                else ((uint16_t *)attn_out)[oi] = (uint16_t)f32_to_bf16_bits(s);
+            for (int hh = 0; hh < kAttMaxG; ++hh) {
+                float a = 0.f;
+                if (hh < nh) {
+                    const float2 ms = st[g * grp + h0 + hh];
+                    const float lg = logits[(int64_t)(g * grp + h0 + hh) * n_rows + row0 + tid];
+                    a = __builtin_amdgcn_exp2f((lg - ms.x) * 1.4426950408889634f) / ms.y;
+                }
+                wts[tid][hh] = a;
             }
         }
         __syncthreads();
+        for (int t0 = slot; t0 < ntok; t0 += SLOTS * UNROLL) {
+            uint4 w[UNROLL];
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) {
+                const int t = min(t0 + u * SLOTS, ntok - 1);
+                w[u] = stream_load16(v_cache + ((row0 + t) * n_kv_heads + g) * LPH + sub);
+            }
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) {
+                const int t = t0 + u * SLOTS;
+                if (t < ntok) {                         // uniform over the LPH lanes of a row
+                    float vx[EPL];
+                    unpack_piece<DTYPE, EPL>(w[u], vx);
+                    const float4 a0 = *reinterpret_cast<const float4 *>(&wts[t][0]);
+                    const float4 a1 = *reinterpret_cast<const float4 *>(&wts[t][4]);
+                    const float a[kAttMaxG] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
+#pragma unroll
+                    for (int hh = 0; hh < kAttMaxG; ++hh) {
+                        if (hh < nh) {
+#pragma unroll
+                            for (int e = 0; e < EPL; ++e) acc[hh][e] = fmaf(a[hh], vx[e], acc[hh][e]);
+                        }
+                    }
+                }
+            }
+        }
+        // add the row slots: inside a wave by shuffles, across the waves through LDS, fixed order
+#pragma unroll
+        for (int hh = 0; hh < kAttMaxG; ++hh)
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) {
+                float v = acc[hh][e];
+#pragma unroll
+                for (int o = LPH; o < 64; o <<= 1) v += __shfl_xor(v, o);
+                acc[hh][e] = v;
+            }
+        if (lane < LPH) {
+#pragma unroll
+            for (int hh = 0; hh < kAttMaxG; ++hh)
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) red[wave][hh][sub * EPL + e] = acc[hh][e];
+        }
+        __syncthreads();
+        for (int i = tid; i < nh * D; i += kThreads) {
+            const int hh = i / D, c = i - hh * D;
+            float s = 0.f;
+#pragma unroll
+            for (int wv = 0; wv < kThreads / 64; ++wv) s += red[wv][hh][c];
+            part[((int64_t)tile_id * n_q_heads + g * grp + h0 + hh) * D + c] = s;
+        }
+        __syncthreads();
     }
+}
+
+// one workgroup per (request, query head), one thread per channel: the request's tiles in order
+template <int DTYPE>
+__global__ void decode_attn_merge_kernel(const DecodeBatch bd, int n_q_heads, int d, const float *__restrict__ part,
+                                         void *__restrict__ attn_out)
+{
+    const int b = blockIdx.x / n_q_heads, h = blockIdx.x % n_q_heads;
+    const int c = threadIdx.x;
+    if (c >= d) return;
+    float s = 0.f;
+    for (int t = bd.tile_begin[b]; t < bd.tile_begin[b + 1]; ++t) s += part[((int64_t)t * n_q_heads + h) * d + c];
+    const int64_t oi = ((int64_t)(bd.req0 + b) * n_q_heads + h) * d + c;
+    if (DTYPE == KVS_F32) ((float *)attn_out)[oi] = s;
+    else ((uint16_t *)attn_out)[oi] = (uint16_t)f32_to_bf16_bits(s);
 }
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -488,7 +558,9 @@ size_t decode_workspace_bytes(const kvs_shape *shape, int32_t batch, int64_t n_r
     size_t stats = align_up(sizeof(float2) * (size_t)batch * (size_t)shape->n_q_heads, 256);
     size_t score = align_up(sizeof(float) * (size_t)n_rows, 256);
     size_t partial = align_up(sizeof(float2) * ((size_t)n_rows / kTok + (size_t)batch + 1) * (size_t)shape->n_q_heads, 256);
-    return logits + stats + score + partial;
+    // per-tile shares of the optional attention output
+    size_t attn = align_up(sizeof(float) * ((size_t)n_rows / kAttTok + (size_t)batch + 1) * (size_t)shape->n_q_heads * (size_t)shape->head_dim, 256);
+    return logits + stats + score + partial + attn;
 }
 
 } // namespace kvs
@@ -535,6 +607,8 @@ extern "C" kvs_status kvs_decode_check(const kvs_shape *shape, int32_t batch, in
     float *score = score_out ? score_out : (float *)ws;
     ws += align_up(sizeof(float) * (size_t)n_rows, 256);
     float2 *partial = (float2 *)ws;
+    ws += align_up(sizeof(float2) * ((size_t)n_rows / kTok + (size_t)batch + 1) * (size_t)hq, 256);
+    float *attn_part = (float *)ws;
     const int lph = (int)(d * elem_bytes(shape->dtype) / 16);
 
     for (int32_t b0 = 0; b0 < batch; b0 += kMaxReq) {
@@ -555,7 +629,9 @@ extern "C" kvs_status kvs_decode_check(const kvs_shape *shape, int32_t batch, in
         bd_tok.n_req = nr;
         if (tiles_tok == 0) continue;
         const int grp = hq / hk;
-        const bool regq = (kThreads / lph) % hk == 0;   // every lane group keeps one kv head
+        // every lane group keeps one kv head and the group size is one of the compiled ones: the
+        // queries live in registers; every other shape reads them from LDS
+        const bool regq = (kThreads / lph) % hk == 0 && (grp == 1 || grp == 2 || grp == 4 || grp == 7 || grp == 8);
         const size_t lds = sizeof(float) * (size_t)hq * (kTok + (regq ? 0 : d));
         dim3 block(kThreads);
         // partials of this launch start at the launch's first tile: offset the pointer so that the
@@ -568,7 +644,7 @@ extern "C" kvs_status kvs_decode_check(const kvs_shape *shape, int32_t batch, in
         else if (regq && grp == 2) KVS_DEC_LAUNCH(DT, L, 2);                   \
         else if (regq && grp == 4) KVS_DEC_LAUNCH(DT, L, 4);                   \
         else if (regq && grp == 7) KVS_DEC_LAUNCH(DT, L, 7);                   \
-        else if (regq && grp == 8) KVS_DEC_LAUNCH(DT, L, 8);                   \
+        else if (regq) KVS_DEC_LAUNCH(DT, L, 8);                               \
         else KVS_DEC_LAUNCH(DT, L, 0);                                         \
     } while (0)
         // bf16 / head_dim 128: the matrix-core kernel, as long as 32-bit byte offsets reach the whole cache
@@ -606,12 +682,24 @@ extern "C" kvs_status kvs_decode_check(const kvs_shape *shape, int32_t batch, in
 #undef KVS_DEC_SCORE
         if ((st = check_launch("kvs_decode_check(score)")) != KVS_OK) return st;
         if (attn_out) {
-            dim3 grid((unsigned)(nr * hk));
-            if (shape->dtype == KVS_BF16 && d == 128) hipLaunchKernelGGL((decode_attn_kernel<KVS_BF16, 128>), grid, block, 0, hs, bd_tok, hq, hk, n_rows, logits, stats, v_cache, attn_out);
-            else if (shape->dtype == KVS_BF16 && d == 64) hipLaunchKernelGGL((decode_attn_kernel<KVS_BF16, 64>), grid, block, 0, hs, bd_tok, hq, hk, n_rows, logits, stats, v_cache, attn_out);
-            else if (shape->dtype == KVS_F32 && d == 128) hipLaunchKernelGGL((decode_attn_kernel<KVS_F32, 128>), grid, block, 0, hs, bd_tok, hq, hk, n_rows, logits, stats, v_cache, attn_out);
-            else hipLaunchKernelGGL((decode_attn_kernel<KVS_F32, 64>), grid, block, 0, hs, bd_tok, hq, hk, n_rows, logits, stats, v_cache, attn_out);
+            DecodeBatch bd_att = bd_tok;   // the same requests in kAttTok-token tiles
+            int64_t tiles_att = 0;
+            for (int i = 0; i < kMaxReq; ++i) {
+                bd_att.tile_begin[i] = (int32_t)tiles_att;
+                tiles_att += ((int64_t)bd_att.ctx_len[i] + kAttTok - 1) / kAttTok;
+            }
+            bd_att.tile_begin[kMaxReq] = (int32_t)tiles_att;
+            const dim3 agrid((unsigned)(tiles_att * hk));
+#define KVS_DEC_ATTN(DT, L) hipLaunchKernelGGL((decode_attn_partial_kernel<DT, L>), agrid, block, 0, hs, bd_att, hq, hk, n_rows, logits, stats, (const uint4 *)v_cache, attn_part)
+            if (shape->dtype == KVS_BF16 && lph == 16) KVS_DEC_ATTN(KVS_BF16, 16);
+            else if (shape->dtype == KVS_BF16 && lph == 8) KVS_DEC_ATTN(KVS_BF16, 8);
+            else if (shape->dtype == KVS_F32 && lph == 16) KVS_DEC_ATTN(KVS_F32, 16);
+            else KVS_DEC_ATTN(KVS_F32, 32);
+#undef KVS_DEC_ATTN
             if ((st = check_launch("kvs_decode_check(attn)")) != KVS_OK) return st;
+            if (shape->dtype == KVS_BF16) hipLaunchKernelGGL(decode_attn_merge_kernel<KVS_BF16>, dim3((unsigned)(nr * hq)), dim3(128), 0, hs, bd_att, hq, d, attn_part, attn_out);
+            else hipLaunchKernelGGL(decode_attn_merge_kernel<KVS_F32>, dim3((unsigned)(nr * hq)), dim3(128), 0, hs, bd_att, hq, d, attn_part, attn_out);
+            if ((st = check_launch("kvs_decode_check(attn merge)")) != KVS_OK) return st;
         }
     }
     if (total_k == 0) return KVS_OK;

@@ -636,6 +636,40 @@ def test_decode_check_parity(dtype):
         np.testing.assert_array_equal(gr.cpu().numpy(), reused)
 
 
+@pytest.mark.parametrize("dtype,d,hq,hk,batch,lo,hi", [
+    ("bf16", 64, 24, 2, 3, 200, 900),       # groups of 12 query heads: two sweeps over V
+    ("f32", 128, 4, 4, 4, 1, 700),          # no grouping, a one-token context possible
+    ("bf16", 128, 8, 2, 70, 10, 300),       # more requests than one launch's table holds
+], ids=["bf16-d64-grp12", "f32-d128-grp1", "bf16-70req"])
+def test_decode_attention_output_shapes(dtype, d, hq, hk, batch, lo, hi):
+    """The optional attention output of the decode check on other head layouts: weights from the
+    new token's row, V summed over tiles of the context (ragged last tile, several launches)."""
+    w = synth.scaled(synth.DECODE, 0, dtype=dtype, head_dim=d, n_q_heads=hq, n_kv_heads=hk)
+    say(f"decode attention output {dtype} d{d} {hq}/{hk} heads, {batch} requests")
+    bt = synth.make_decode_batch(w, batch, lo, hi, 0, salt=3)
+    rows = bt["k_cache"].shape[0]
+    off, lens = bt["ctx_off"], bt["ctx_len"]
+    sh = shape_for(w)
+    g = torch.Generator().manual_seed(11)
+    q_new = (torch.randn((batch, hq, d), generator=g) / math.sqrt(d)).to(w.torch_dtype)
+    dev_v = torch.rand((hk, rows), generator=g)
+    kc, vc = oracle._as_np(bt["k_cache"]), oracle._as_np(bt["v_cache"])
+    reused = bt["reused"].numpy()
+    kreq = [0] * batch
+    _, ref_score, ref_attn = oracle.decode_check(q_new, kc, dev_v.numpy(), reused, 1.0, off, lens, kreq,
+                                                 v_cache=vc, want_attn=True)
+    _, _, mag_attn = oracle.decode_check(q_new, kc, dev_v.numpy(), reused, 1.0, off, lens, kreq,
+                                         v_cache=abs_values(vc), want_attn=True)
+    ws = torch.empty(B.kvs_workspace_size("decode_check", sh, batch, rows), dtype=torch.uint8, device=DEV)
+    score = torch.full((rows,), float("nan"), device=DEV)
+    attn = torch.empty((batch, hq, d), dtype=w.torch_dtype, device=DEV)
+    B.kvs_decode_check(sh, rows, off, lens, q_new.to(DEV), bt["k_cache"].to(DEV), bt["v_cache"].to(DEV), dev_v.to(DEV),
+                       bt["reused"].to(DEV), 1.0, kreq, None, score, attn, ws)
+    torch.cuda.synchronize()
+    assert_attn_close(attn.float().cpu().numpy(), ref_attn, w, mag_attn)
+    assert_scores_close(score.cpu().numpy(), ref_score)
+
+
 # --------------------------------------------------------------------------------- whole path
 
 @pytest.mark.parametrize("w", [synth.TINY, synth.scaled(synth.QWEN, 1024, span_mean=64.0)], ids=["tiny", "qwen-1024"])
