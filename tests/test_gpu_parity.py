@@ -145,6 +145,40 @@ def test_select_ties_and_special_values():
     check_select(s, [0, n], [150], "denormal/huge")
 
 
+def test_select_key_range_edges():
+    """Rows at the edges of the key space: no finite score, one finite score, the threshold at
+    and below the last finite score, a tie larger than the candidate list in LDS, scores from
+    -3.4e38 to 3.4e38, two adjacent values, a tight cluster with outliers."""
+    rng = np.random.default_rng(8)
+    n = 20000
+    check_select(np.full(n, -np.inf, np.float32), [0, n], [777], "all -inf")
+    s = np.full(n, -np.inf, np.float32)
+    s[12345] = 2.5
+    for k in (1, 2, 5000):
+        check_select(s, [0, n], [k], "one finite score")
+    s = rng.lognormal(-3, 1.5, n).astype(np.float32)
+    s[rng.random(n) < 0.5] = -np.inf
+    nf = int(np.isfinite(s).sum())
+    for k in (nf - 1, nf, nf + 1, nf + 3000):
+        check_select(s, [0, n], [k], "threshold at / below the last finite score")
+    s = rng.lognormal(-3, 1.5, n).astype(np.float32)
+    s[2000:12000] = np.float32(0.05)                 # 10000 equal scores: more than the candidate list holds
+    for k in (3000, 9000, 15000):
+        check_select(s, [0, n], [k], "large tie in the threshold bin")
+    s = rng.standard_normal(n).astype(np.float32)
+    s[0], s[1] = np.float32(-3.4e38), np.float32(3.4e38)
+    for k in (1, 2, 10000, n - 1, n):
+        check_select(s, [0, n], [k], "widest key range")
+    s = np.where(rng.random(n) < 0.3, np.float32(1.0), np.float32(1.0000001)).astype(np.float32)
+    for k in (1, 6000, 14000, 19999):
+        check_select(s, [0, n], [k], "two adjacent values")
+    # clustered far from a few outliers: the bulk shares one bin of the first digit
+    s = (1.0 + 1e-4 * rng.random(n)).astype(np.float32)
+    s[:5] = np.float32(1e6)
+    for k in (3, 5, 6, 2500, 12000):
+        check_select(s, [0, n], [k], "cluster + outliers")
+
+
 def test_select_ragged_rows():
     rng = np.random.default_rng(6)
     lens = [5, 0, 4096, 1, 7000, 33000, 129, 64, 20000] + [int(x) for x in rng.integers(1, 3000, 70)]
