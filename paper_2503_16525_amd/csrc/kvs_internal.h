@@ -22,9 +22,11 @@ kvs_status check_shape(const kvs_shape *s);
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-// exact top-k over rows given as (begin, len) pairs of one score array (select.hip)
+// exact top-k over rows given as (begin, len) pairs of one score array (select.hip); the workspace
+// (may be NULL) lets rows too long for one workgroup spread over several
 kvs_status launch_select(const float *scores, int32_t n_rows, const int64_t *begin, const int64_t *len,
-                         const int32_t *k_row, int32_t *idx_out, hipStream_t stream);
+                         const int32_t *k_row, int32_t *idx_out, void *workspace, size_t workspace_bytes, hipStream_t stream);
+size_t select_workspace_bytes(int32_t n_rows, int64_t n_scores);
 size_t decode_workspace_bytes(const kvs_shape *shape, int32_t batch, int64_t n_rows);
 size_t colsum_workspace_bytes(const kvs_shape *shape, int64_t n_tokens);
 kvs_status launch_colsum_valu(const kvs_shape *shape, int64_t n, const void *q, const void *k, float scale,

@@ -18,6 +18,15 @@
 //     #greater before it + min(#equal before it, quota of equals).
 // When no tie is cut (the usual case) the predicate collapses to key >= T.  Integer counting only:
 // the result is exact and identical from run to run.
+//
+// Rows longer than 49152 entries do not fit one workgroup's registers.  With a workspace they are
+// cut into parts of 32768 entries, one workgroup each, and the same select runs as four launches
+// with the launch boundaries as the only synchronisation (no atomics between workgroups, no
+// spinning): leading-digit histogram per part -> every part finds the threshold's leading digit
+// from the row's histograms and sets its candidates aside -> one workgroup per row resolves the
+// other two digits on the candidates and hands every part its threshold, its share of the tie
+// and its place in the output -> the parts write.  Without a workspace such rows take the
+// one-workgroup kernel, which then re-reads its keys from L2 on every sweep.
 #include "kvs_internal.h"
 
 #include <new>
@@ -245,27 +254,322 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const float *__rest
     }
 }
 
+// ---- rows cut into parts: one workgroup per part, four launches ------------------------------------
+constexpr int kPartKpt = 32;
+constexpr int kPartLen = kPartKpt * kSelThreads;      // entries per part
+constexpr int kOneWgMax = 48 * kSelThreads;           // longest row whose keys one workgroup holds in registers
+constexpr int kMaxParts = 64;                         // parts per group of launches
+
+struct LongParts {
+    int64_t begin[kMaxParts];      // first score of the part
+    int64_t cand_off[kMaxParts];   // the part's segment of the candidate list
+    int64_t out_off[kMaxParts];    // where the row's indices go in idx_out
+    int32_t len[kMaxParts];
+    int32_t local0[kMaxParts];     // row-local index of the part's first entry
+    int32_t row_first[kMaxParts];  // first part of the part's row
+    int32_t row_parts[kMaxParts];  // parts of that row
+    int32_t k[kMaxParts];          // the row's k
+};
+
+struct PartKeys {
+    uint32_t key[kPartKpt];
+    uint32_t e0;                   // part-local index of slot 0; slot j holds e0 + 64 j
+};
+
+// wave w owns the w-th contiguous sixteenth of the part (as in select_kernel); empty slots carry key 0
+__device__ __forceinline__ void load_part(const float *__restrict__ row, int len, PartKeys &pk)
+{
+    const uint32_t tid = threadIdx.x, lane = tid & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
+    const int nj = (len + kSelThreads - 1) / kSelThreads;
+    pk.e0 = (uint32_t)(wave * nj) * kWave + lane;
+#pragma unroll
+    for (int j = 0; j < kPartKpt; ++j) {
+        const uint32_t e = pk.e0 + j * kWave;
+        const uint32_t key = score_key(row[min(e, (uint32_t)len - 1)]);
+        pk.key[j] = (j < nj && e < (uint32_t)len) ? key : 0u;
+    }
+}
+
+// Every thread holds the count `mine` of the bins it owns (bins ascending with the thread index).
+// The thread whose bins hold the remaining-th entry counted from the top calls
+// resolve(rank from the top inside its bins).  Every thread of the workgroup must call this.
+template <typename F>
+__device__ __forceinline__ void owner_from_top(int mine, int remaining, int *wave_tot, F resolve)
+{
+    const uint32_t tid = threadIdx.x, lane = tid & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
+    const int incl = wave_incl_scan(mine);
+    const int wtot = __builtin_amdgcn_readlane(incl, kWave - 1);
+    if (lane == 0) wave_tot[wave] = wtot;
+    __syncthreads();
+    int above = wtot - incl;
+    for (int w = wave + 1; w < kSelWaves; ++w) above += wave_tot[w];
+    if (above < remaining && remaining <= above + mine) resolve(remaining - above);
+    __syncthreads();
+}
+
+// thread t owns bins 2t and 2t+1 of a 2048-bin histogram: bcast = (bin, rank inside it, its count)
+__device__ __forceinline__ void bin_from_top_2048(const int *h, int rem, int *wave_tot, int *bcast)
+{
+    const int tid = threadIdx.x;
+    const int b_lo = h[2 * tid], b_hi = h[2 * tid + 1];
+    owner_from_top(b_lo + b_hi, rem, wave_tot, [&](int rank) {
+        if (rank <= b_hi) { bcast[0] = 2 * tid + 1; bcast[1] = rank; bcast[2] = b_hi; }
+        else { bcast[0] = 2 * tid; bcast[1] = rank - b_hi; bcast[2] = b_lo; }
+    });
+}
+
+// launch 1: leading-digit histogram of every part, hist[part][1024]
+__global__ __launch_bounds__(kSelThreads) void select_part_hist_kernel(const float *__restrict__ scores, const LongParts lp,
+                                                                       int *__restrict__ hist)
+{
+    __shared__ int h[kHist1Ints];
+    const int part = blockIdx.x, tid = threadIdx.x;
+    PartKeys pk;
+    load_part(scores + lp.begin[part], lp.len[part], pk);
+#pragma unroll
+    for (int i = 0; i < kHist1Ints / kSelThreads; ++i) h[i * kSelThreads + tid] = 0;
+    __syncthreads();
+    const uint32_t copy = tid & (kCopies - 1);
+#pragma unroll
+    for (int j = 0; j < kPartKpt; ++j) atomicAdd(&h[(pk.key[j] >> 22) * kCopies + copy], 1);
+    __syncthreads();
+    int c = 0;
+#pragma unroll
+    for (int i = 0; i < kCopies; ++i) c += h[tid * kCopies + i];
+    hist[part * 1024 + tid] = c;
+}
+
+// launch 2: every part finds the leading digit d1 of the row's threshold from the row's part
+// histograms, counts its entries above that digit and copies those with that digit to its segment
+__global__ __launch_bounds__(kSelThreads) void select_part_cand_kernel(const float *__restrict__ scores, const LongParts lp,
+                                                                       const int *__restrict__ hist, uint32_t *__restrict__ cand,
+                                                                       int4 *__restrict__ part_rec /* (candidates, above d1, -, -) */,
+                                                                       int4 *__restrict__ row_rec /* at the row's first part: (d1, rank in d1, -, -) */)
+{
+    __shared__ int wave_tot[kSelWaves], wave_tot2[kSelWaves], bcast[3];
+    const int part = blockIdx.x, tid = threadIdx.x, lane = tid & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
+    PartKeys pk;
+    load_part(scores + lp.begin[part], lp.len[part], pk);
+    const int first = lp.row_first[part], n_parts = lp.row_parts[part];
+    int c = 0;
+    for (int q = 0; q < n_parts; ++q) c += hist[(first + q) * 1024 + tid];
+    owner_from_top(c, lp.k[part], wave_tot, [&](int rank) { bcast[0] = tid; bcast[1] = rank; });
+    const uint32_t d1 = (uint32_t)bcast[0];
+    int mine = 0, above = 0;
+#pragma unroll
+    for (int j = 0; j < kPartKpt; ++j) {
+        // (an empty slot never counts: with NaN scores the threshold's digit can be the empty slots' own)
+        mine += __popcll(__ballot((pk.key[j] >> 22) == d1 && pk.e0 + j * kWave < (uint32_t)lp.len[part]));
+        above += __popcll(__ballot((pk.key[j] >> 22) > d1));
+    }
+    if (lane == 0) { wave_tot[wave] = mine; wave_tot2[wave] = above; }
+    __syncthreads();
+    uint32_t at = 0;
+    int n_cand = 0, n_above = 0;
+    for (int w = 0; w < kSelWaves; ++w) {
+        if (w < wave) at += wave_tot[w];
+        n_cand += wave_tot[w];
+        n_above += wave_tot2[w];
+    }
+    uint32_t *__restrict__ seg = cand + lp.cand_off[part];
+#pragma unroll
+    for (int j = 0; j < kPartKpt; ++j) {
+        const bool hit = (pk.key[j] >> 22) == d1 && pk.e0 + j * kWave < (uint32_t)lp.len[part];
+        const uint64_t m = __ballot(hit);
+        if (hit) seg[at + lanes_below(m)] = pk.key[j];
+        at += __popcll(m);
+    }
+    if (tid == 0) {
+        part_rec[part] = make_int4(n_cand, n_above, 0, 0);
+        if (part == first) row_rec[part] = make_int4((int)d1, bcast[1], 0, 0);
+    }
+}
+
+// launch 3: one workgroup per row (the one of the row's first part; the others leave at once)
+// resolves the second and third digit on the candidates of all parts, then gives every part the
+// threshold, the number of entries equal to it that the part takes (the tie goes to the lowest
+// indices, i.e. to the earlier parts first) and the part's place in the output
+__global__ __launch_bounds__(kSelThreads) void select_row_threshold_kernel(const LongParts lp, const uint32_t *__restrict__ cand,
+                                                                           const int4 *__restrict__ part_rec, const int4 *__restrict__ row_rec,
+                                                                           int4 *__restrict__ part_thr /* (T, equals taken, all equals taken, -) */,
+                                                                           long long *__restrict__ part_out)
+{
+    __shared__ int hist2[2048], hist3[2048];
+    __shared__ int wave_tot[kSelWaves], bcast[3];
+    __shared__ int cnt[kMaxParts][2];
+    const int part = blockIdx.x, tid = threadIdx.x, lane = tid & (kWave - 1);
+    if (lp.row_first[part] != part) return;             // uniform
+    const int n_parts = lp.row_parts[part];
+    const uint32_t d1 = (uint32_t)row_rec[part].x;
+    int remaining = row_rec[part].y;
+    hist2[tid] = 0; hist2[tid + kSelThreads] = 0;
+    hist3[tid] = 0; hist3[tid + kSelThreads] = 0;
+    if (tid < 2 * kMaxParts) (&cnt[0][0])[tid] = 0;
+    __syncthreads();
+    for (int q = 0; q < n_parts; ++q) {
+        const uint32_t *__restrict__ seg = cand + lp.cand_off[part + q];
+        const int n = part_rec[part + q].x;
+        for (int i = tid; i < n; i += kSelThreads) atomicAdd(&hist2[(seg[i] >> 11) & 2047u], 1);
+    }
+    __syncthreads();
+    bin_from_top_2048(hist2, remaining, wave_tot, bcast);
+    const uint32_t d2 = (uint32_t)bcast[0];
+    remaining = bcast[1];
+    for (int q = 0; q < n_parts; ++q) {
+        const uint32_t *__restrict__ seg = cand + lp.cand_off[part + q];
+        const int n = part_rec[part + q].x;
+        for (int i = tid; i < n; i += kSelThreads) {
+            const uint32_t key = seg[i];
+            if (((key >> 11) & 2047u) == d2) atomicAdd(&hist3[key & 2047u], 1);
+        }
+    }
+    __syncthreads();
+    bin_from_top_2048(hist3, remaining, wave_tot, bcast);
+    uint32_t T = (d1 << 22) | (d2 << 11) | (uint32_t)bcast[0];
+    const int quota_eq = bcast[1];
+    if (T == 0u) T = 1u;                                 // only reachable with NaN scores: never select padding
+    for (int q = 0; q < n_parts; ++q) {
+        const uint32_t *__restrict__ seg = cand + lp.cand_off[part + q];
+        const int n = part_rec[part + q].x;
+        int gt = 0, eq = 0;
+        for (int i = tid; i < n; i += kSelThreads) {
+            const uint32_t key = seg[i];
+            gt += key > T;
+            eq += key == T;
+        }
+        gt = wave_sum_i32(gt);
+        eq = wave_sum_i32(eq);
+        if (lane == 0) { atomicAdd(&cnt[q][0], gt); atomicAdd(&cnt[q][1], eq); }
+    }
+    __syncthreads();
+    if (tid == 0) {
+        long long at = lp.out_off[part];
+        int eq_left = quota_eq;
+        for (int q = 0; q < n_parts; ++q) {
+            const int n_eq = cnt[q][1];
+            const int take = min(eq_left, n_eq);
+            part_thr[part + q] = make_int4((int)T, take, take == n_eq ? 1 : 0, 0);
+            part_out[part + q] = at;
+            at += part_rec[part + q].y + cnt[q][0] + take;
+            eq_left -= take;
+        }
+    }
+}
+
+// launch 4: every part writes its selected entries, in index order, at its place
+__global__ __launch_bounds__(kSelThreads) void select_part_write_kernel(const float *__restrict__ scores, const LongParts lp,
+                                                                        const int4 *__restrict__ part_thr, const long long *__restrict__ part_out,
+                                                                        int32_t *__restrict__ idx_out)
+{
+    __shared__ int wave_tot[kSelWaves], wave_tot2[kSelWaves];
+    const int part = blockIdx.x, tid = threadIdx.x, lane = tid & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
+    PartKeys pk;
+    load_part(scores + lp.begin[part], lp.len[part], pk);
+    const int4 thr = part_thr[part];
+    const uint32_t T = (uint32_t)thr.x;
+    const uint32_t quota_eq = (uint32_t)thr.y;
+    int32_t *__restrict__ out = idx_out + part_out[part];
+    const uint32_t local0 = (uint32_t)lp.local0[part];
+    // entries equal to T count as selected while the part's share of the tie lasts (index order)
+    int n_gt = 0, n_eq = 0;
+#pragma unroll
+    for (int j = 0; j < kPartKpt; ++j) {
+        n_gt += __popcll(__ballot(pk.key[j] > T));
+        n_eq += __popcll(__ballot(pk.key[j] == T));
+    }
+    if (lane == 0) { wave_tot[wave] = n_gt; wave_tot2[wave] = n_eq; }
+    __syncthreads();
+    uint32_t base_gt = 0, base_eq = 0;
+    for (int w = 0; w < wave; ++w) { base_gt += wave_tot[w]; base_eq += wave_tot2[w]; }
+#pragma unroll
+    for (int j = 0; j < kPartKpt; ++j) {
+        const uint32_t key = pk.key[j];
+        const bool is_gt = key > T, is_eq = key == T;
+        const uint64_t m_gt = __ballot(is_gt), m_eq = __ballot(is_eq);
+        const uint32_t gt_before = base_gt + lanes_below(m_gt);
+        const uint32_t eq_before = base_eq + lanes_below(m_eq);
+        const int32_t e = (int32_t)(local0 + pk.e0 + j * kWave);
+        if (is_gt) out[gt_before + min(eq_before, quota_eq)] = e;
+        else if (is_eq && eq_before < quota_eq) out[gt_before + eq_before] = e;
+        base_gt += __popcll(m_gt);
+        base_eq += __popcll(m_eq);
+    }
+}
+
+inline size_t sel_align(size_t x) { return (x + 255) & ~(size_t)255; }
+
+// workspace of one group of parts holding `entries` scores
+inline size_t long_group_bytes(int parts, int64_t entries)
+{
+    return sel_align(sizeof(int) * 1024 * (size_t)parts) + sel_align(sizeof(uint32_t) * (size_t)entries) +
+           3 * sel_align(sizeof(int4) * (size_t)parts) + sel_align(sizeof(long long) * (size_t)parts);
+}
+
+kvs_status launch_long_group(const float *scores, const LongParts &lp, int parts, int64_t entries, int32_t *idx_out,
+                             void *workspace, hipStream_t hs)
+{
+    char *ws = (char *)workspace;
+    int *hist = (int *)ws;                  ws += sel_align(sizeof(int) * 1024 * (size_t)parts);
+    uint32_t *cand = (uint32_t *)ws;        ws += sel_align(sizeof(uint32_t) * (size_t)entries);
+    int4 *part_rec = (int4 *)ws;            ws += sel_align(sizeof(int4) * (size_t)parts);
+    int4 *row_rec = (int4 *)ws;             ws += sel_align(sizeof(int4) * (size_t)parts);
+    int4 *part_thr = (int4 *)ws;            ws += sel_align(sizeof(int4) * (size_t)parts);
+    long long *part_out = (long long *)ws;
+    const dim3 grid(parts), block(kSelThreads);
+    kvs_status st;
+    hipLaunchKernelGGL(select_part_hist_kernel, grid, block, 0, hs, scores, lp, hist);
+    if ((st = check_launch("kvs_select_topk(part histograms)")) != KVS_OK) return st;
+    hipLaunchKernelGGL(select_part_cand_kernel, grid, block, 0, hs, scores, lp, hist, cand, part_rec, row_rec);
+    if ((st = check_launch("kvs_select_topk(part candidates)")) != KVS_OK) return st;
+    hipLaunchKernelGGL(select_row_threshold_kernel, grid, block, 0, hs, lp, cand, part_rec, row_rec, part_thr, part_out);
+    if ((st = check_launch("kvs_select_topk(row threshold)")) != KVS_OK) return st;
+    hipLaunchKernelGGL(select_part_write_kernel, grid, block, 0, hs, scores, lp, part_thr, part_out, idx_out);
+    return check_launch("kvs_select_topk(part write)");
+}
+
 } // namespace
 
-// rows given as (begin, len) pairs so that callers with gaps between rows (decode contexts with
-// slack) can use the same kernel; arguments are already validated
-kvs_status launch_select(const float *scores, int32_t n_rows, const int64_t *begin, const int64_t *len,
-                         const int32_t *k_row, int32_t *idx_out, hipStream_t hs)
+size_t select_workspace_bytes(int32_t n_rows, int64_t n_scores)
 {
+    // every row may end in a short part; groups of launches reuse the same workspace one after the other
+    const int64_t parts = n_scores / kPartLen + n_rows;
+    const int group = (int)(parts < kMaxParts ? parts : kMaxParts);
+    return long_group_bytes(group, n_scores < (int64_t)group * kPartLen ? n_scores : (int64_t)group * kPartLen) + 256;
+}
+
+// rows given as (begin, len) pairs so that callers with gaps between rows (decode contexts with
+// slack) can use the same kernel; arguments are already validated.  workspace may be NULL.
+kvs_status launch_select(const float *scores, int32_t n_rows, const int64_t *begin, const int64_t *len,
+                         const int32_t *k_row, int32_t *idx_out, void *workspace, size_t workspace_bytes, hipStream_t hs)
+{
+    // a row goes the several-workgroups way if it is too long for one workgroup's registers and
+    // the workspace holds it
+    auto parts_of = [&](int32_t r) { return (len[r] + kPartLen - 1) / kPartLen; };
+    auto is_long = [&](int32_t r) {
+        return workspace && k_row[r] > 0 && len[r] > kOneWgMax && parts_of(r) <= kMaxParts &&
+               long_group_bytes((int)parts_of(r), len[r]) <= workspace_bytes;
+    };
     int64_t out_base = 0;
+    bool any_long = false;
     for (int32_t r0 = 0; r0 < n_rows; r0 += kMaxRowsPerLaunch) {
         const int nr = (n_rows - r0) < kMaxRowsPerLaunch ? (n_rows - r0) : kMaxRowsPerLaunch;
         SelectRows rows;
         int64_t max_len = 0;
         for (int i = 0; i < kMaxRowsPerLaunch; ++i) {
             const bool live = i < nr;
+            const bool lng = live && is_long(r0 + i);
+            any_long |= lng;
             rows.begin[i] = live ? begin[r0 + i] : 0;
             rows.len[i] = live ? (int32_t)len[r0 + i] : 0;
-            rows.k[i] = live ? k_row[r0 + i] : 0;
+            rows.k[i] = live && !lng ? k_row[r0 + i] : 0;
             rows.out_off[i] = out_base;
             if (live) {
                 out_base += k_row[r0 + i];
-                if (k_row[r0 + i] > 0 && len[r0 + i] > max_len) max_len = len[r0 + i];
+                if (rows.k[i] > 0 && len[r0 + i] > max_len) max_len = len[r0 + i];
             }
         }
         if (max_len == 0) continue;
@@ -280,6 +584,40 @@ kvs_status launch_select(const float *scores, int32_t n_rows, const int64_t *beg
         kvs_status st = check_launch("kvs_select_topk");
         if (st != KVS_OK) return st;
     }
+    if (!any_long) return KVS_OK;
+    // the long rows, in groups of parts that share the workspace one group after the other
+    LongParts lp = {};
+    int parts = 0;
+    int64_t entries = 0;
+    out_base = 0;
+    for (int32_t r = 0; r <= n_rows; ++r) {
+        const bool lng = r < n_rows && is_long(r);
+        const int p = lng ? (int)parts_of(r) : 0;
+        if (parts > 0 && (r == n_rows || (lng && (parts + p > kMaxParts || long_group_bytes(parts + p, entries + len[r]) > workspace_bytes)))) {
+            const kvs_status st = launch_long_group(scores, lp, parts, entries, idx_out, workspace, hs);
+            if (st != KVS_OK) return st;
+            lp = LongParts{};
+            parts = 0;
+            entries = 0;
+        }
+        if (r == n_rows) break;
+        if (lng) {
+            for (int q = 0; q < p; ++q) {
+                const int64_t at = (int64_t)q * kPartLen;
+                lp.begin[parts + q] = begin[r] + at;
+                lp.len[parts + q] = (int32_t)(len[r] - at < kPartLen ? len[r] - at : kPartLen);
+                lp.local0[parts + q] = (int32_t)at;
+                lp.cand_off[parts + q] = entries + at;
+                lp.out_off[parts + q] = out_base;
+                lp.row_first[parts + q] = parts;
+                lp.row_parts[parts + q] = p;
+                lp.k[parts + q] = k_row[r];
+            }
+            parts += p;
+            entries += len[r];
+        }
+        out_base += k_row[r];
+    }
     return KVS_OK;
 }
 
@@ -290,9 +628,8 @@ extern "C" kvs_status kvs_select_topk(const float *scores, int32_t n_rows, const
                                       void *workspace, size_t workspace_bytes, void *stream)
 {
     using namespace kvs;
-    (void)workspace;
-    (void)workspace_bytes;
     if (n_rows < 0) return fail(KVS_EINVAL, "kvs_select_topk: n_rows < 0");
+    if (workspace && (reinterpret_cast<uintptr_t>(workspace) & 255u)) return fail(KVS_EINVAL, "kvs_select_topk: workspace must be 256-byte aligned");
     if (n_rows == 0) return KVS_OK;
     if (!row_off || !k_row) return fail(KVS_EINVAL, "kvs_select_topk: row_off/k_row is NULL");
     int64_t total_k = 0;
@@ -311,7 +648,7 @@ extern "C" kvs_status kvs_select_topk(const float *scores, int32_t n_rows, const
     int64_t *lens = n_rows <= kStack ? lens_stack : new (std::nothrow) int64_t[n_rows];
     if (!lens) return fail(KVS_EINVAL, "kvs_select_topk: out of host memory");
     for (int32_t r = 0; r < n_rows; ++r) lens[r] = row_off[r + 1] - row_off[r];
-    kvs_status st = launch_select(scores, n_rows, row_off, lens, k_row, idx_out, (hipStream_t)stream);
+    kvs_status st = launch_select(scores, n_rows, row_off, lens, k_row, idx_out, workspace, workspace_bytes, (hipStream_t)stream);
     if (lens != lens_stack) delete[] lens;
     return st;
 }

@@ -65,6 +65,11 @@ def test_select_argument_errors(lib):
     kr = np.array([3], np.int32)
     assert lib.kvs_select_topk(None, 1, ro.ctypes.data, kr.ctypes.data, FAKE, None, 0, None) == B.EINVAL
     assert lib.kvs_select_topk(FAKE, -1, ro.ctypes.data, kr.ctypes.data, FAKE, None, 0, None) == B.EINVAL
+    # the optional workspace must be 256-byte aligned; its size grows with the scores (one candidate slot each)
+    assert lib.kvs_select_topk(FAKE, 1, ro.ctypes.data, kr.ctypes.data, FAKE, FAKE + 16, 4096, None) == B.EINVAL
+    sh = _shape()
+    small, large = B.kvs_workspace_size("select_topk", sh, 1, 1000), B.kvs_workspace_size("select_topk", sh, 4, 4 * 131072)
+    assert 0 < small < large and large >= 4 * 4 * 131072
     # k = 0 everywhere and zero rows are no-ops
     kr = np.array([0], np.int32)
     assert lib.kvs_select_topk(None, 1, ro.ctypes.data, kr.ctypes.data, None, None, 0, None) == B.OK

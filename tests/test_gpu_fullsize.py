@@ -123,7 +123,13 @@ def test_yi_131k_select_per_head_rows():
     k = 12452
     ref = oracle.select_topk(rows.reshape(-1), [i * n for i in range(hk + 1)], [k] * hk)
     idx = torch.empty((hk * k,), dtype=torch.int32, device=DEV)
-    B.kvs_select_topk(torch.from_numpy(rows.reshape(-1)).to(DEV), [i * n for i in range(hk + 1)], [k] * hk, idx)
+    scores = torch.from_numpy(rows.reshape(-1)).to(DEV)
+    B.kvs_select_topk(scores, [i * n for i in range(hk + 1)], [k] * hk, idx)
+    np.testing.assert_array_equal(idx.cpu().numpy(), ref)
+    # with a workspace each row is cut into four parts that run on workgroups of their own
+    ws = torch.empty(B.kvs_workspace_size("select_topk", B.shape_of(w), hk, hk * n), dtype=torch.uint8, device=DEV)
+    idx.fill_(-1)
+    B.kvs_select_topk(scores, [i * n for i in range(hk + 1)], [k] * hk, idx, ws)
     np.testing.assert_array_equal(idx.cpu().numpy(), ref)
 
 

@@ -93,10 +93,14 @@ def test_deviation_value_only_without_keys_and_mask():
 
 # --------------------------------------------------------------------------------- select
 
-def gpu_select(scores_np, row_off, k_row):
+def gpu_select(scores_np, row_off, k_row, with_workspace=False):
     s = torch.from_numpy(np.ascontiguousarray(scores_np)).to(DEV)
     out = torch.full((max(int(np.sum(k_row)), 1),), -7, dtype=torch.int32, device=DEV)
-    B.kvs_select_topk(s, row_off, k_row, out)
+    ws = None
+    if with_workspace:
+        ws = torch.empty(B.kvs_workspace_size("select_topk", shape_for(synth.TINY), len(k_row), len(scores_np)),
+                         dtype=torch.uint8, device=DEV)
+    B.kvs_select_topk(s, row_off, k_row, out, ws)
     torch.cuda.synchronize()
     return out.cpu().numpy()[: int(np.sum(k_row))]
 
@@ -106,6 +110,10 @@ def check_select(scores_np, row_off, k_row, what):
     ref = oracle.select_topk(scores_np, row_off, k_row)
     got = gpu_select(scores_np, row_off, k_row)
     np.testing.assert_array_equal(got, ref)
+    if np.max(np.diff(np.asarray(row_off))) > 49152:
+        # rows this long spread over several workgroups when the call gets a workspace
+        got = gpu_select(scores_np, row_off, k_row, with_workspace=True)
+        np.testing.assert_array_equal(got, ref)
 
 
 @pytest.mark.parametrize("n", [1, 63, 64, 1000, 4096, 4097, 16384, 20001, 32768, 32769, 50000, 131072])
@@ -177,6 +185,41 @@ def test_select_key_range_edges():
     s[:5] = np.float32(1e6)
     for k in (3, 5, 6, 2500, 12000):
         check_select(s, [0, n], [k], "cluster + outliers")
+
+
+def test_select_long_rows_over_several_workgroups():
+    """Rows beyond 49152 entries with a workspace: parts of 32768 entries, a ragged last part, ties
+    cut across parts, long and short rows in one call, more parts than one group of launches."""
+    rng = np.random.default_rng(9)
+    n = 150001
+    s = rng.lognormal(-3, 1.5, n).astype(np.float32)
+    s[rng.random(n) < 0.1] = -np.inf
+    for k in (1, 2, 15000, 75000, n - 1, n):
+        check_select(s, [0, n], [k], "long row")
+    # a tie that spans the parts: the lowest indices win, so the earlier parts take it first
+    s = np.full(n, 0.5, np.float32)
+    s[rng.random(n) < 0.2] = 1.0
+    n_hi = int((s == 1.0).sum())
+    for k in (n_hi - 1, n_hi, n_hi + 1, n_hi + 40000, n_hi + 100000):
+        check_select(s, [0, n], [k], "tie across parts")
+    # quantised scores, all -inf, identical leading bits
+    s = (np.round(rng.standard_normal(n) * 4) / 4).astype(np.float32)
+    check_select(s, [0, n], [60000], "quantised long row")
+    check_select(np.full(n, -np.inf, np.float32), [0, n], [5], "long row, all -inf")
+    s = (np.float32(1.0).view(np.uint32) + rng.integers(0, 64, n).astype(np.uint32)).view(np.float32)
+    check_select(s, [0, n], [33333], "long row, low bits only")
+    # long rows among short ones, with an empty and a k = 0 row; the first has more parts than a group of
+    # launches holds and takes the one-workgroup kernel
+    lens = [2300000, 100, 0, 98304, 49153, 5000, 49152, 65537]
+    off = np.concatenate([[0], np.cumsum(lens)])
+    s = rng.lognormal(0, 1, int(off[-1])).astype(np.float32)
+    s[rng.random(len(s)) < 0.15] = -np.inf
+    ks = [123456, 10, 0, 98304, 0, 77, 4000, 30000]
+    check_select(s, off, ks, "long + short rows")
+    lens = [1200000, 1200000, 60000]
+    off = np.concatenate([[0], np.cumsum(lens)])
+    s = rng.standard_normal(int(off[-1])).astype(np.float32)
+    check_select(s, off, [500000, 3, 59999], "two groups of parts")
 
 
 def test_select_ragged_rows():
@@ -702,6 +745,41 @@ def test_decode_attention_output_shapes(dtype, d, hq, hk, batch, lo, hi):
     torch.cuda.synchronize()
     assert_attn_close(attn.float().cpu().numpy(), ref_attn, w, mag_attn)
     assert_scores_close(score.cpu().numpy(), ref_score)
+
+
+def test_decode_check_long_context():
+    """One context beyond what a single workgroup's top-k holds in registers (the call's workspace
+    lets that row run in parts) next to a short one."""
+    w = synth.scaled(synth.DECODE, 0, n_q_heads=8, n_kv_heads=2)
+    say("decode check, 60k-token context + a short one")
+    bt = synth.make_decode_batch(w, 2, 3000, 3000, 0, salt=5)
+    long_len = 60001
+    g = torch.Generator().manual_seed(21)
+    hk, hq, d = w.n_kv_heads, w.n_q_heads, w.head_dim
+    k_long = torch.randn((long_len, hk, d), generator=g).to(w.torch_dtype)
+    kc = torch.cat([k_long, bt["k_cache"]]).contiguous()
+    rows = kc.shape[0]
+    off = np.array([0, long_len], dtype=np.int64)
+    lens = np.array([long_len, 3000], dtype=np.int64)
+    q_new = (torch.randn((2, hq, d), generator=g) / math.sqrt(d)).to(w.torch_dtype)
+    dev_v = torch.rand((hk, rows), generator=g)
+    reused = (torch.rand((rows,), generator=g) < 0.9).to(torch.uint8)
+    kreq = [1200, 60]
+    ref_idx, ref_score, _ = oracle.decode_check(q_new, oracle._as_np(kc), dev_v.numpy(), reused.numpy(), 1.0, off, lens, kreq)
+    sh = shape_for(w)
+    ws = torch.empty(B.kvs_workspace_size("decode_check", sh, 2, rows), dtype=torch.uint8, device=DEV)
+    idx = torch.full((sum(kreq),), -1, dtype=torch.int32, device=DEV)
+    score = torch.full((rows,), float("nan"), device=DEV)
+    B.kvs_decode_check(sh, rows, off, lens, q_new.to(DEV), kc.to(DEV), None, dev_v.to(DEV), reused.to(DEV), 1.0, kreq,
+                       idx, score, None, ws)
+    torch.cuda.synchronize()
+    sc, ix = score.cpu().numpy(), idx.cpu().numpy()
+    assert_scores_close(sc[:long_len], ref_score[:long_len])
+    check_topk_band(ix[:1200], ref_score[:long_len], 1200)
+    check_topk_band(ix[1200:], ref_score[long_len:long_len + 3000], 60)
+    # the indices are exactly the top-k of the scores the GPU itself wrote (oracle select on those)
+    own = oracle.select_topk(sc, [0, long_len, long_len + 3000], kreq)
+    np.testing.assert_array_equal(ix, own)
 
 
 # --------------------------------------------------------------------------------- whole path
