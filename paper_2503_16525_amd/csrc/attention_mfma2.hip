@@ -495,18 +495,24 @@ __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
         diag_pass = pass;
 #endif
         if (pass == 1) {
-            // exact row maxima: one tile at a time through the K ring
+            // exact row maxima: a score-only sweep with three tiles on their way.  Tile jt+3 goes to
+            // the K slot of tile jt-1, which every wave has finished reading when it passes the
+            // barrier of step jt; tiles past the end are requested too (rows clamped, never
+            // read), so the count of younger loads in flight at a barrier is always two tiles' worth.
+            static_assert(K_RING >= 4, "the score-only sweep keeps three tiles in flight beside the one in use");
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb) m_ref[nb] = -INFINITY;
+            for (int k = 0; k < 3; ++k) stage_tile(t_lo + k);
             for (int jt = t_lo; jt < t_hi; ++jt) {
-                stage_tile(jt);
-                KVS_ATTN_BARRIER(0);
+                KVS_ATTN_BARRIER(8);
+                stage_tile(jt + 3);
                 floatx16 s[NB];
                 qk(jt, s);
                 mask_tile(jt, s);
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb) m_ref[nb] = fmaxf(m_ref[nb], row_max(s[nb]));
             }
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             __syncthreads();   // every wave is done with the ring before the sweep refills it
         }
         // Invariant at the top of step j, in either loop: the loads of tiles j .. j+AHEAD-1 have been sent

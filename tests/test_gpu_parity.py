@@ -530,6 +530,28 @@ def test_partial_attention_first_tile_reference_fallback():
     np.testing.assert_allclose(lse, ref_lse, rtol=2e-3, atol=2e-3)
 
 
+@pytest.mark.parametrize("with_workspace", [False, True], ids=["whole-range", "pieces"])
+def test_partial_attention_reference_fallback_late_in_a_long_sweep(with_workspace):
+    """The logit jump sits ~60 key tiles into a 94-tile context, so the repeat with exact maxima
+    runs its score-only sweep (several tiles in flight) well past its start-up, over a ragged
+    last tile, and, with a workspace, inside key-range pieces."""
+    w = synth.scaled(synth.LLAMA, 3001)
+    say(f"attention with a late 2^180 logit jump, workspace={with_workspace}")
+    n, hk, hq, d = w.n_ctx, w.n_kv_heads, w.n_q_heads, w.head_dim
+    g = torch.Generator().manual_seed(92)
+    k = torch.randn((n, hk, d), generator=g) * 0.05
+    k[1930:1934] += 1.0               # four keys whose q.k is ~128 for q = ones, then back to ~0
+    k[2700] += 1.5
+    v = torch.randn((n, hk, d), generator=g)
+    pos = np.arange(2, n, 5, dtype=np.int32)
+    q = torch.ones((len(pos), hq, d)) + 0.01 * torch.randn((len(pos), hq, d), generator=g)
+    kb, vb, qb = k.to(torch.bfloat16), v.to(torch.bfloat16), q.to(torch.bfloat16)
+    ref, ref_lse = oracle.partial_attention(qb, pos, kb, vb, 1.0)
+    got, lse = run_gpu_attention(w, qb, pos, kb, vb, 1.0, with_workspace=with_workspace)
+    assert_attn_close(got, ref, w)
+    np.testing.assert_allclose(lse, ref_lse, rtol=2e-3, atol=2e-3)
+
+
 # --------------------------------------------------------------------------------- decode check
 
 def check_topk_band(idx, score_ref, k, rtol=2e-5):
