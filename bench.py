@@ -233,7 +233,7 @@ def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--ratio", type=float, default=0.15, help="recompute ratio (fraction of reused tokens)")
     ap.add_argument("--alpha", choices=["none", "synthetic", "gpu"], default="none",
                     help="attention column mass fed to kvs_deviation: none = magnitude-only score (alpha = 1, the "
@@ -287,6 +287,7 @@ def main() -> int:
 
     seg = np.array([[ev[j].elapsed_time(ev[j + 1]) for j in range(5)] for ev in events])  # ms
     t_devsel, t_scat, t_attn, t_dec, t_decrec = seg.mean(0)
+    seg_med, seg_min = np.median(seg, axis=0), seg.min(axis=0)
     t_alpha = float(np.mean([ev[6].elapsed_time(ev[0]) for ev in events]))   # ~0 unless --alpha gpu
     used_slots = [slots[(args.warmup + i) % n_slots] for i in range(args.steps)]
     flops = float(np.mean([s.flops for s in used_slots]))
@@ -317,6 +318,9 @@ def main() -> int:
                      "achieved": attn_tflops, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": attn_tflops / MFMA_BF16_PEAK_TFLOPS, "traffic": read_traffic("attn_mfma2_kernel prefill launch"),
                      "flops_per_launch": flops, "avg_launch_ms": float(t_attn)},
+        # per-call HIP-event times over the timed steps, ms: [deviation+select, scatter, attention, decode check, decode recompute]
+        "per_call_ms": {"mean": [float(x) for x in seg.mean(0)], "median": [float(x) for x in seg_med],
+                        "min": [float(x) for x in seg_min]},
         "components": {
             "deviation_select": {"ms": float(t_devsel), "GBps": (bytes_dev + bytes_sel) / (t_devsel * 1e-3) / 1e9,
                                  "frac_hbm": (bytes_dev + bytes_sel) / (t_devsel * 1e-3) / 1e9 / HBM_PEAK_GBS},
