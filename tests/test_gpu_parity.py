@@ -552,6 +552,34 @@ def test_partial_attention_reference_fallback_late_in_a_long_sweep(with_workspac
     np.testing.assert_allclose(lse, ref_lse, rtol=2e-3, atol=2e-3)
 
 
+def test_partial_attention_more_tiles_than_units():
+    """An unsplit launch with more row tiles per KV head than compute units serving the head: one
+    workgroup per unit then runs several tiles in a row.  64 KV heads leave 4 units per head, so two
+    ragged requests with 7 + 4 tiles are enough; sampled rows of every tile against the oracle."""
+    w = synth.scaled(synth.LLAMA, 0, n_q_heads=64, n_kv_heads=64)
+    say("attention, 11 row tiles on 4 units per KV head")
+    hk, hq, d = w.n_kv_heads, w.n_q_heads, w.head_dim
+    g = torch.Generator().manual_seed(93)
+    lens = [3500, 2100]
+    off = [0, 3600]                                   # slack rows between the requests
+    rows = 3600 + 2100
+    k = torch.randn((rows, hk, d), generator=g).to(torch.bfloat16)
+    v = torch.randn((rows, hk, d), generator=g).to(torch.bfloat16)
+    pos = np.concatenate([np.arange(1, 3500, 2)[:1700], np.arange(0, 2100, 2)[:1000]]).astype(np.int32)
+    cu = [0, 1700, 2700]
+    q = (torch.randn((len(pos), hq, d), generator=g) / math.sqrt(d)).to(torch.bfloat16)
+    got, lse = run_gpu_attention(w, q, pos, k, v, 1.0, off, lens, cu, with_workspace=False)
+    # sampled selected tokens: the ends of both requests and every 37th in between
+    samp = sorted(set(list(range(0, 2700, 37)) + [0, 1, 1699, 1700, 1701, 2699, 255, 256, 1443, 1444]))
+    for b in range(2):
+        ids = [i for i in samp if cu[b] <= i < cu[b + 1]]
+        sl = slice(off[b], off[b] + lens[b])
+        ref, ref_lse = oracle.partial_attention(q[ids], pos[ids], k[sl], v[sl], 1.0)
+        mag = attn_magnitude(q[ids], pos[ids], k[sl], v[sl], 1.0)
+        assert_attn_close(got[ids], ref, w, mag)
+        np.testing.assert_allclose(lse[ids], ref_lse, atol=2e-3)
+
+
 # --------------------------------------------------------------------------------- decode check
 
 def check_topk_band(idx, score_ref, k, rtol=2e-5):
