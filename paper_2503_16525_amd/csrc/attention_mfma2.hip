@@ -37,7 +37,6 @@
 // and the LDS operands of a step's first MFMAs are fetched at the end of the step before.
 #include "attention.h"
 
-#include <algorithm>
 
 #include <math.h>
 #include <type_traits>
@@ -59,6 +58,9 @@ constexpr int ROW_B = D * 2;            // bytes of one K or V row of one head
 constexpr int TILE_B = BN * ROW_B;      // a K or V tile in LDS: 32 rows of 256 B, 16-byte pieces XOR-swizzled
 // Tiles are requested AHEAD steps before their softmax; the barrier of a step lets the
 // 4 * (AHEAD - 3) staging instructions of the younger tiles stay in flight.
+#ifndef KVS_ATTN_SHARE_MAX_X2
+#define KVS_ATTN_SHARE_MAX_X2 7      // launches run per-unit shares up to this many half-tiles per unit (7 = 3.5 tiles)
+#endif
 #ifndef KVS_ATTN_AHEAD
 #define KVS_ATTN_AHEAD 4
 #define KVS_ATTN_IN_FLIGHT 4
@@ -95,16 +97,85 @@ __device__ long long kvs_diag_clk[4096];
 #endif
 
 
-// Row tiles of an unsplit launch packed onto the compute units that serve a KV head, passed in the
-// kernel arguments: workgroup (unit u, KV head g) runs tiles tile[first[u]] .. tile[first[u+1]-1]
-// of that head one after the other.  n == 0: one workgroup per tile, heaviest tile first.
-constexpr int kAttnOrderMax = 512;
-constexpr int kAttnUnitsMax = 256;
-struct AttnOrder {
-    int32_t n;
-    uint16_t first[kAttnUnitsMax + 1];
-    uint16_t tile[kAttnOrderMax];
-};
+// An unsplit launch with shares (share_units > 0) starts one workgroup per compute unit and KV
+// head; every workgroup packs the head's row tiles onto the head's units by itself, from the
+// tiles' actual reach in the context, and runs its own unit's share (see plan_shares).
+constexpr int kAttnShareMaxTiles = 512;
+constexpr int kAttnShareMaxUnits = 64;     // one lane of a wavefront per unit
+constexpr float kAttnTileOverhead = 8.0f;  // key-tile steps a tile costs before its first
+
+// Packs the row tiles of one KV head onto `units` compute units and returns the share of unit
+// `unit` (heaviest tile first) in LDS; every workgroup of the launch computes the same packing.
+//
+// Why: within an XCD the dispatcher deals workgroup n of a launch to shader engine n % 4 (8 compute
+// units each), strictly in order: a workgroup whose engine is full holds back everything behind
+// it, also workgroups whose engine has room.  With one workgroup per tile, heaviest first, and
+// tile weights that grow up the context, the first two rounds pair up to equal sums on every unit
+// and whatever is left lands on top: 72 tiles per head finish 11 % above the mean load of the
+// head's 32 units (measured, and reproduced by a model of those rules; no list order is robustly
+// better under them).  The units of an XCD run at the same pace (+-0.5 % measured), so a fixed
+// share per unit loses nothing against a queue.
+//
+// How: weight of a tile = key tiles up to its last row's position (read from sel_pos: exact) plus
+// a fixed cost; tiles ranked by weight; first fit decreasing under a capacity, one lane per unit
+// (a ballot finds the first unit with room); the four waves try capacities 0.5 / 1.5 / 3 / 6 %
+// above the mean load and the smallest that works is taken (twice the mean always works).
+__device__ __forceinline__ void plan_shares(const AttnTiles &td, int grp, int total_tiles, const int32_t *__restrict__ sel_pos,
+                                            int units, int unit, char *scratch, uint16_t *my_tiles, int *n_my_tiles)
+{
+    float *w = reinterpret_cast<float *>(scratch);                                   // [total_tiles]
+    uint16_t *desc = reinterpret_cast<uint16_t *>(scratch + sizeof(float) * kAttnShareMaxTiles);   // tiles by falling weight
+    int *works = reinterpret_cast<int *>(scratch + (sizeof(float) + sizeof(uint16_t)) * kAttnShareMaxTiles);   // [NWAVES]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    for (int t = tid; t < total_tiles; t += NT) {
+        int b = 0;
+        while (b + 1 < td.n_req && t >= td.tile_begin[b + 1]) ++b;
+        const int tile = t - td.tile_begin[b];
+        const int n_rows = td.n_sel[b] * grp;
+        const int last_row = (tile + 1) * ROWS - ((td.tile_begin[b + 1] - td.tile_begin[b]) * ROWS - n_rows) - 1;   // tiles end-aligned
+        int p = sel_pos[td.sel_lo[b] + last_row / grp];
+        p = min(max(p, 0), td.ctx_len[b] - 1);
+        w[t] = (float)(p / BN + 1) + kAttnTileOverhead;
+    }
+    __syncthreads();
+    float sum = 0.f, biggest = 0.f;
+    for (int t = 0; t < total_tiles; ++t) { sum += w[t]; biggest = fmaxf(biggest, w[t]); }   // same order in every thread
+    for (int t = tid; t < total_tiles; t += NT) {
+        const float wt = w[t];
+        int rank = 0;
+        for (int j = 0; j < total_tiles; ++j) rank += (w[j] > wt || (w[j] == wt && j > t)) ? 1 : 0;
+        desc[rank] = (uint16_t)t;
+    }
+    __syncthreads();
+    const float mean = fmaxf(sum / (float)units, biggest);
+    // first fit decreasing under `cap`; lane l is unit l; returns whether every tile found room, and
+    // leaves the tiles of `unit` in my_tiles if `keep`
+    auto pack = [&](float cap, bool keep) -> bool {
+        float load = lane < units ? 0.f : 3.0e38f;
+        int n_mine = 0;
+        for (int i = 0; i < total_tiles; ++i) {
+            const int t = desc[i];
+            const float wt = w[t];
+            const unsigned long long room = __ballot(load + wt <= cap);
+            if (room == 0) return false;
+            const int first = __ffsll((long long)room) - 1;
+            if (lane == first) load += wt;
+            if (keep && first == unit) { if (lane == 0) my_tiles[n_mine] = (uint16_t)t; ++n_mine; }
+        }
+        if (keep && lane == 0) *n_my_tiles = n_mine;
+        return true;
+    };
+    const float tries[NWAVES] = {1.005f, 1.015f, 1.03f, 1.06f};
+    static_assert(NWAVES == 4, "one capacity per wave");
+    const bool fits = pack(mean * tries[wave], false);
+    if (lane == 0) works[wave] = fits ? 1 : 0;
+    __syncthreads();
+    float cap = 2.0f * mean;
+#pragma unroll
+    for (int v = NWAVES - 1; v >= 0; --v) cap = works[v] ? mean * tries[v] : cap;
+    if (wave == 0) pack(cap, true);
+    __syncthreads();
+}
 
 // WANT_LSE: additionally keep the unrounded sum of weights, from which the log-sum-exp is reported.
 // SPLIT: the key range is cut into pieces handled by different workgroups (launches with few row
@@ -121,7 +192,7 @@ __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
     const uint16_t *__restrict__ k_cache, const uint16_t *__restrict__ v_cache,
     float scale_log2, uint16_t *__restrict__ out, float *__restrict__ lse_out,
     int n_splits, const int4 *__restrict__ split_plan, const uint16_t *__restrict__ piece_list,
-    float *__restrict__ part_o, float4 *__restrict__ part_ml, const AttnOrder ord)
+    float *__restrict__ part_o, float4 *__restrict__ part_ml, int share_units)
 {
     extern __shared__ __attribute__((aligned(16))) uint16_t lds[];   // K ring, then V^T ring
     __shared__ int wg_max_pos[NWAVES];
@@ -131,10 +202,14 @@ __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
     // ---- which (request, kv head, row tile) -----------------------------------------------------
     const int g = blockIdx.x % n_kv_heads;
     const int wg = (int)(blockIdx.x / n_kv_heads);
-    // With a list the workgroup is one compute unit's share of KV head g and works through its
+    // With shares the workgroup is one compute unit's part of KV head g and works through its
     // tiles; otherwise it has the one tile (or piece) its index names.
-    const bool listed = !SPLIT && ord.n > 0;
-    const int it_begin = listed ? (int)ord.first[wg] : wg, it_end = listed ? (int)ord.first[wg + 1] : wg + 1;
+    const bool listed = !SPLIT && share_units > 0;
+    __shared__ uint16_t my_tiles[kAttnShareMaxTiles];
+    __shared__ int n_my_tiles;
+    if (listed) plan_shares(td, n_q_heads / n_kv_heads, total_tiles, sel_pos, share_units, wg,
+                            reinterpret_cast<char *>(lds), my_tiles, &n_my_tiles);
+    const int it_begin = listed ? 0 : wg, it_end = listed ? n_my_tiles : wg + 1;
     for (int it = it_begin; it < it_end; ++it) {
     if (it != it_begin) __syncthreads();   // every wave has left the previous tile: rings and tables are free
 #ifdef KVS_DIAG_CLOCK
@@ -146,7 +221,7 @@ __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
     const int piece = SPLIT ? piece_list[rest] : rest;
     const int split = SPLIT ? piece / total_tiles : 0;
     const int tile_lin = SPLIT ? total_tiles - 1 - piece % total_tiles
-                               : (listed ? (int)ord.tile[rest] : total_tiles - 1 - rest);
+                               : (listed ? (int)my_tiles[rest] : total_tiles - 1 - rest);
     int b = 0;
     while (b + 1 < td.n_req && tile_lin >= td.tile_begin[b + 1]) ++b;
     const int tile = tile_lin - td.tile_begin[b];
@@ -792,7 +867,7 @@ template <bool WANT_LSE, bool SPLIT>
 kvs_status launch_one(const dim3 grid, size_t lds_bytes, hipStream_t st, const AttnTiles &td, const kvs_shape *shape,
                       int tiles, const void *q_sel, const int32_t *sel_pos, const void *k_cache, const void *v_cache,
                       float scale_log2, void *out, float *lse_out, int n_splits, const int4 *split_plan,
-                      const uint16_t *piece_list, float *part_o, float4 *part_ml, const AttnOrder &ord)
+                      const uint16_t *piece_list, float *part_o, float4 *part_ml, int share_units)
 {
     static bool attr_set = false;   // idempotent; a race only repeats the same call
     if (!attr_set) {
@@ -804,82 +879,22 @@ kvs_status launch_one(const dim3 grid, size_t lds_bytes, hipStream_t st, const A
     hipLaunchKernelGGL((attn_mfma2_kernel<WANT_LSE, SPLIT>), grid, dim3(NT), lds_bytes, st, td, shape->n_q_heads,
                        shape->n_kv_heads, tiles, (const uint16_t *)q_sel, sel_pos, (const uint16_t *)k_cache,
                        (const uint16_t *)v_cache, scale_log2, (uint16_t *)out, lse_out, n_splits, split_plan, piece_list,
-                       part_o, part_ml, ord);
+                       part_o, part_ml, share_units);
     return check_launch("kvs_partial_attention(mfma2)");
 }
 
-// Within one XCD the dispatcher deals workgroup n of the launch to shader engine n % 4 (8 compute
-// units each), strictly in order: a workgroup whose engine is full holds back everything behind
-// it, also workgroups whose engine has room.  With one workgroup per tile, heaviest first, and
-// tile weights that grow linearly with the tile's place in the context, 72 tiles per KV head
-// finish 11-12 % above the mean load of the head's 32 units (measured and reproduced by that
-// model); no list order is robustly better under those rules.  So a launch with more tiles than
-// units starts exactly one workgroup per unit, and each works through a share of the tiles that was
-// packed on the host: first fit decreasing under the smallest capacity that works (bisection),
-// about 1 % above the mean load.  The units of an XCD run at the same clock and pace (+-0.5 %
-// measured), so a fixed share loses nothing against taking tiles from a queue.  The weights
-// are estimates (selected tokens spread evenly over the context: the positions themselves are
-// in device memory); a wrong estimate costs balance, never correctness.
-void build_attn_order(const kvs_shape *shape, const AttnTiles &td, int tiles, AttnOrder &ord)
+// units per KV head for a launch that runs shares (0: one workgroup per tile).  Few tiles per unit
+// is where the dispatcher does badly; from ~3.5 per unit on its one-by-one hand-out evens out as
+// well as fixed shares do (3 % above the mean load at 4.5 per unit).
+int share_units_for(const kvs_shape *shape, int64_t tiles)
 {
-    ord.n = 0;
 #ifdef KVS_ATTN_NO_ORDER
-    return;
+    return 0;
 #endif
-    int units = kAttnSplitCus / shape->n_kv_heads > 0 ? kAttnSplitCus / shape->n_kv_heads : 1;
-    if (units > kAttnUnitsMax) units = kAttnUnitsMax;
-    // Few tiles per unit is where the dispatcher does badly; from ~3.5 per unit on its taking
-    // tiles one by one evens out more (3 % above the mean at 4.5 per unit) than fixed shares
-    // built on estimated weights can (5-7 % there).
-    if (tiles > kAttnOrderMax || tiles <= units || 2 * tiles > 7 * units) return;
-    constexpr float kTileOverhead = 8.0f;                     // key-tile steps a tile costs before its first
-    const int grp = shape->n_q_heads / shape->n_kv_heads;
-    float w[kAttnOrderMax];
-    uint16_t desc[kAttnOrderMax];
-    float sum = 0.f, biggest = 0.f;
-    for (int e = 0; e < td.n_req; ++e) {
-        const int t_e = td.tile_begin[e + 1] - td.tile_begin[e];
-        const float n_rows = (float)td.n_sel[e] * (float)grp;
-        for (int t = 0; t < t_e; ++t) {
-            const float rows_end = n_rows - (float)(t_e - 1 - t) * ROWS;     // tiles are aligned to the end of the rows
-            const float x = rows_end / n_rows * (float)td.ctx_len[e] / BN + kTileOverhead;
-            w[td.tile_begin[e] + t] = x;
-            sum += x;
-            biggest = x > biggest ? x : biggest;
-        }
-    }
-    for (int i = 0; i < tiles; ++i) desc[i] = (uint16_t)i;
-    std::sort(desc, desc + tiles, [&](uint16_t a, uint16_t b) { return w[a] > w[b] || (w[a] == w[b] && a > b); });
-    float load[kAttnUnitsMax];
-    uint16_t unit_of[kAttnOrderMax];
-    auto pack = [&](float cap) {
-        for (int u = 0; u < units; ++u) load[u] = 0.f;
-        for (int i = 0; i < tiles; ++i) {
-            int u = 0;
-            while (u < units && load[u] + w[desc[i]] > cap) ++u;
-            if (u == units) return false;
-            load[u] += w[desc[i]];
-            unit_of[desc[i]] = (uint16_t)u;
-        }
-        return true;
-    };
-    float lo = sum / units > biggest ? sum / units : biggest, hi = 1.25f * lo;
-    if (!pack(hi)) return;
-    for (int it = 0; it < 12; ++it) {
-        const float mid = 0.5f * (lo + hi);
-        if (pack(mid)) hi = mid; else lo = mid;
-    }
-    if (!pack(hi)) return;
-    // every unit's tiles, heaviest first
-    int count[kAttnUnitsMax + 1] = {0};
-    for (int i = 0; i < tiles; ++i) ++count[unit_of[i] + 1];
-    ord.first[0] = 0;
-    for (int u = 0; u < units; ++u) { count[u + 1] += count[u]; ord.first[u + 1] = (uint16_t)count[u + 1]; }
-    for (int i = 0; i < tiles; ++i) {
-        const int t = desc[i];
-        ord.tile[count[unit_of[t]]++] = (uint16_t)t;
-    }
-    ord.n = units;
+    const int units = kAttnSplitCus / shape->n_kv_heads;
+    if (units < 1 || units > kAttnShareMaxUnits || tiles > kAttnShareMaxTiles) return 0;
+    if (tiles <= units || 2 * tiles > KVS_ATTN_SHARE_MAX_X2 * units) return 0;
+    return units;
 }
 } // namespace
 
@@ -939,13 +954,12 @@ kvs_status launch_attention_mfma2(const kvs_shape *shape, const AttnBatch &bd, c
     const float scale_log2 = scale * 1.4426950408889634f;
     const int n_splits = plan.n_splits;
     if (n_splits <= 1 || !workspace) {
-        AttnOrder ord;
-        build_attn_order(shape, td, (int)tiles, ord);
-        const dim3 grid((unsigned)((ord.n > 0 ? ord.n : tiles) * shape->n_kv_heads));
+        const int share_units = share_units_for(shape, tiles);
+        const dim3 grid((unsigned)((share_units > 0 ? share_units : tiles) * shape->n_kv_heads));
         return lse_out ? launch_one<true, false>(grid, lds_bytes, st, td, shape, (int)tiles, q_sel, sel_pos, k_cache, v_cache,
-                                                 scale_log2, out, lse_out, 1, nullptr, nullptr, nullptr, nullptr, ord)
+                                                 scale_log2, out, lse_out, 1, nullptr, nullptr, nullptr, nullptr, share_units)
                        : launch_one<false, false>(grid, lds_bytes, st, td, shape, (int)tiles, q_sel, sel_pos, k_cache, v_cache,
-                                                  scale_log2, out, lse_out, 1, nullptr, nullptr, nullptr, nullptr, ord);
+                                                  scale_log2, out, lse_out, 1, nullptr, nullptr, nullptr, nullptr, share_units);
     }
     if (tiles > PLAN_MAX_TILES) return fail(KVS_EINVAL, "kvs_partial_attention: split launch with %lld row tiles", (long long)tiles);
     // workspace: the pieces' accumulators, their (reference, sums) records, the plan, the piece list.  Pieces are
@@ -974,12 +988,10 @@ kvs_status launch_attention_mfma2(const kvs_shape *shape, const AttnBatch &bd, c
     kvs_status stt = check_launch("kvs_partial_attention(plan)");
     if (stt != KVS_OK) return stt;
     const dim3 grid((unsigned)(tiles * shape->n_kv_heads * n_splits));
-    AttnOrder no_order;
-    no_order.n = 0;
     stt = lse_out ? launch_one<true, true>(grid, lds_bytes, st, td, shape, (int)tiles, q_sel, sel_pos, k_cache, v_cache,
-                                           scale_log2, out, lse_out, n_splits, split_plan, piece_list, part_o, part_ml, no_order)
+                                           scale_log2, out, lse_out, n_splits, split_plan, piece_list, part_o, part_ml, 0)
                   : launch_one<false, true>(grid, lds_bytes, st, td, shape, (int)tiles, q_sel, sel_pos, k_cache, v_cache,
-                                            scale_log2, out, lse_out, n_splits, split_plan, piece_list, part_o, part_ml, no_order);
+                                            scale_log2, out, lse_out, n_splits, split_plan, piece_list, part_o, part_ml, 0);
     if (stt != KVS_OK) return stt;
     return launch_attention_merge(n_rows_total, n_splits, (const float *)workspace, ml_base,
                                   (uint16_t *)out + row0 * D, lse_out ? lse_out + row0 : nullptr, st);
