@@ -123,9 +123,12 @@ constexpr float kAttnTileOverhead = 8.0f;  // key-tile steps a tile costs before
 __device__ __forceinline__ void plan_shares(const AttnTiles &td, int grp, int total_tiles, const int32_t *__restrict__ sel_pos,
                                             int units, int unit, char *scratch, uint16_t *my_tiles, int *n_my_tiles)
 {
-    float *w = reinterpret_cast<float *>(scratch);                                   // [total_tiles]
-    uint16_t *desc = reinterpret_cast<uint16_t *>(scratch + sizeof(float) * kAttnShareMaxTiles);   // tiles by falling weight
-    int *works = reinterpret_cast<int *>(scratch + (sizeof(float) + sizeof(uint16_t)) * kAttnShareMaxTiles);   // [NWAVES]
+    constexpr int MAXT = kAttnShareMaxTiles;
+    float *w = reinterpret_cast<float *>(scratch);                       // [MAXT] weight of tile t
+    float *sw = w + MAXT;                                                // [MAXT] weights in falling order
+    uint16_t *st = reinterpret_cast<uint16_t *>(sw + MAXT);              // [MAXT] the tiles in that order
+    uint16_t *found = st + MAXT;                                         // [NWAVES][MAXT] ranks that fall to `unit`, per trial
+    int *n_found = reinterpret_cast<int *>(found + NWAVES * MAXT);       // [NWAVES], -1: the capacity did not work
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     for (int t = tid; t < total_tiles; t += NT) {
         int b = 0;
@@ -144,36 +147,52 @@ __device__ __forceinline__ void plan_shares(const AttnTiles &td, int grp, int to
         const float wt = w[t];
         int rank = 0;
         for (int j = 0; j < total_tiles; ++j) rank += (w[j] > wt || (w[j] == wt && j > t)) ? 1 : 0;
-        desc[rank] = (uint16_t)t;
+        sw[rank] = wt;
+        st[rank] = (uint16_t)t;
     }
     __syncthreads();
     const float mean = fmaxf(sum / (float)units, biggest);
-    // first fit decreasing under `cap`; lane l is unit l; returns whether every tile found room, and
-    // leaves the tiles of `unit` in my_tiles if `keep`
-    auto pack = [&](float cap, bool keep) -> bool {
+    // the sorted weights, rank 64 k + lane in register k of the lane (read back with a lane broadcast:
+    // an LDS round trip per tile would dominate the loop)
+    float mine_w[MAXT / 64];
+#pragma unroll
+    for (int k = 0; k < MAXT / 64; ++k) mine_w[k] = 64 * k + lane < total_tiles ? sw[64 * k + lane] : 0.f;
+    // first fit decreasing under `cap`: lane l is unit l, a ballot finds the first unit with room;
+    // the ranks that fall to `unit` go to found[wave]
+    auto pack = [&](float cap) {
         float load = lane < units ? 0.f : 3.0e38f;
-        int n_mine = 0;
-        for (int i = 0; i < total_tiles; ++i) {
-            const int t = desc[i];
-            const float wt = w[t];
-            const unsigned long long room = __ballot(load + wt <= cap);
-            if (room == 0) return false;
-            const int first = __ffsll((long long)room) - 1;
-            if (lane == first) load += wt;
-            if (keep && first == unit) { if (lane == 0) my_tiles[n_mine] = (uint16_t)t; ++n_mine; }
+        int n = 0;
+        bool ok = true;
+#pragma unroll
+        for (int k = 0; k < MAXT / 64; ++k) {
+            const int n_here = min(64, total_tiles - 64 * k);          // uniform
+            for (int l = 0; l < n_here; ++l) {
+                const float wt = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, mine_w[k]), l));
+                const unsigned long long room = __ballot(load + wt <= cap);
+                ok = ok && room != 0;
+                const int first = room ? __ffsll((long long)room) - 1 : 0;
+                if (lane == first) load += wt;
+                if (first == unit) { if (lane == 0) found[wave * MAXT + n] = (uint16_t)(64 * k + l); ++n; }
+            }
         }
-        if (keep && lane == 0) *n_my_tiles = n_mine;
-        return true;
+        if (lane == 0) n_found[wave] = ok ? n : -1;
     };
     const float tries[NWAVES] = {1.005f, 1.015f, 1.03f, 1.06f};
     static_assert(NWAVES == 4, "one capacity per wave");
-    const bool fits = pack(mean * tries[wave], false);
-    if (lane == 0) works[wave] = fits ? 1 : 0;
+    pack(mean * tries[wave]);
     __syncthreads();
-    float cap = 2.0f * mean;
+    int pick = -1;
 #pragma unroll
-    for (int v = NWAVES - 1; v >= 0; --v) cap = works[v] ? mean * tries[v] : cap;
-    if (wave == 0) pack(cap, true);
+    for (int v = NWAVES - 1; v >= 0; --v) pick = n_found[v] >= 0 ? v : pick;
+    if (pick < 0) {                                  // uniform; twice the mean load always works
+        __syncthreads();
+        if (wave == 0) pack(2.0f * mean);
+        __syncthreads();
+        pick = 0;
+    }
+    const int n = n_found[pick];
+    for (int i = tid; i < n; i += NT) my_tiles[i] = st[found[pick * MAXT + i]];
+    if (tid == 0) *n_my_tiles = n;
     __syncthreads();
 }
 
