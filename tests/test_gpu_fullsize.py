@@ -100,7 +100,9 @@ def prefill_layer(w, ratio, n_sample, projected):
     return lay, gk, gv, gr, dev_v, idx_ref
 
 
-@pytest.mark.parametrize("ratio", [0.05, 0.30])
+# 5 %: few row tiles, the key range is cut into pieces; 15 % and 20 %: 72 and 96 row tiles per KV head on
+# 32 compute units, every unit works through a planned share of them; 30 %: one workgroup per tile
+@pytest.mark.parametrize("ratio", [0.05, 0.15, 0.20, 0.30])
 def test_llama_32k_layer_full_size(ratio):
     say(f"llama 32k full size ratio {ratio}")
     prefill_layer(synth.LLAMA, ratio, n_sample=24, projected=True)
