@@ -910,6 +910,14 @@ int share_units_for(const kvs_shape *shape, int64_t tiles)
 #ifdef KVS_ATTN_NO_ORDER
     return 0;
 #endif
+    // one workgroup per compute unit only works out if the device has the units the shares are made for
+    static int device_cus = -1;   // idempotent; a race only repeats the same query
+    if (device_cus < 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) n = 0;
+        device_cus = n;
+    }
+    if (device_cus != kAttnSplitCus) return 0;
     const int units = kAttnSplitCus / shape->n_kv_heads;
     if (units < 1 || units > kAttnShareMaxUnits || tiles > kAttnShareMaxTiles) return 0;
     if (tiles <= units || 2 * tiles > KVS_ATTN_SHARE_MAX_X2 * units) return 0;
