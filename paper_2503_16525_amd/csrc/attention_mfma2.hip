@@ -118,8 +118,8 @@ constexpr float kAttnTileOverhead = 8.0f;  // key-tile steps a tile costs before
 //
 // How: weight of a tile = key tiles up to its last row's position (read from sel_pos: exact) plus
 // a fixed cost; tiles ranked by weight; first fit decreasing under a capacity, one lane per unit
-// (a ballot finds the first unit with room); the four waves try capacities 0.5 / 1.5 / 3 / 6 %
-// above the mean load and the smallest that works is taken (twice the mean always works).
+// (a ballot finds the first unit with room); the four waves try four capacities at a time, from
+// 0.5 % above the mean load upwards, and the smallest that works is taken.
 __device__ __forceinline__ void plan_shares(const AttnTiles &td, int grp, int total_tiles, const int32_t *__restrict__ sel_pos,
                                             int units, int unit, char *scratch, uint16_t *my_tiles, int *n_my_tiles)
 {
@@ -177,22 +177,33 @@ __device__ __forceinline__ void plan_shares(const AttnTiles &td, int grp, int to
         }
         if (lane == 0) n_found[wave] = ok ? n : -1;
     };
-    const float tries[NWAVES] = {1.005f, 1.015f, 1.03f, 1.06f};
+    // The four waves try four capacities at once, the smallest that works is taken; the ladder goes
+    // on until twice the mean load, which always works (a tile that finds no room under it would
+    // mean every unit already carries more than the mean).  Tile sets that one wave of equal
+    // weights spread evenly need the first round only; very uneven ones (a few tiles per unit and
+    // reaches bunched together) can need 10-20 %.
     static_assert(NWAVES == 4, "one capacity per wave");
-    pack(mean * tries[wave]);
-    __syncthreads();
+    const float ladder[3][NWAVES] = {{1.005f, 1.015f, 1.03f, 1.06f}, {1.09f, 1.13f, 1.18f, 1.25f}, {1.35f, 1.5f, 1.7f, 2.0f}};
     int pick = -1;
+    for (int round = 0; round < 3 && pick < 0; ++round) {      // uniform over the workgroup
+        if (round > 0) __syncthreads();                           // n_found of the round before has been read
+        pack(mean * ladder[round][wave]);
+        __syncthreads();
 #pragma unroll
-    for (int v = NWAVES - 1; v >= 0; --v) pick = n_found[v] >= 0 ? v : pick;
-    if (pick < 0) {                                  // uniform; twice the mean load always works
-        __syncthreads();
-        if (wave == 0) pack(2.0f * mean);
-        __syncthreads();
-        pick = 0;
+        for (int v = NWAVES - 1; v >= 0; --v) pick = n_found[v] >= 0 ? v : pick;
     }
-    const int n = n_found[pick];
-    for (int i = tid; i < n; i += NT) my_tiles[i] = st[found[pick * MAXT + i]];
-    if (tid == 0) *n_my_tiles = n;
+    if (pick < 0) {
+        // not reachable by the argument above; if rounding ever defeats it, deal the ranks round robin
+        // (every tile still runs exactly once)
+        int n = 0;
+        for (int i = unit; i < total_tiles; i += units, ++n)
+            if (tid == 0) my_tiles[n] = st[i];
+        if (tid == 0) *n_my_tiles = n;
+    } else {
+        const int n = n_found[pick];
+        for (int i = tid; i < n; i += NT) my_tiles[i] = st[found[pick * MAXT + i]];
+        if (tid == 0) *n_my_tiles = n;
+    }
     __syncthreads();
 }
 

@@ -552,12 +552,15 @@ def test_partial_attention_reference_fallback_late_in_a_long_sweep(with_workspac
     np.testing.assert_allclose(lse, ref_lse, rtol=2e-3, atol=2e-3)
 
 
-def test_partial_attention_more_tiles_than_units():
+@pytest.mark.parametrize("bunched", [False, True], ids=["spread", "bunched"])
+def test_partial_attention_more_tiles_than_units(bunched):
     """An unsplit launch with more row tiles per KV head than compute units serving the head: one
     workgroup per unit then runs several tiles in a row.  64 KV heads leave 4 units per head, so two
-    ragged requests with 7 + 4 tiles are enough; sampled rows of every tile against the oracle."""
+    ragged requests with 7 + 4 tiles are enough; sampled rows of every tile against the oracle.
+    With the selected tokens bunched at the top of their contexts all tiles weigh about the same,
+    and 11 equal tiles on 4 units cannot be packed within a few percent of the mean load."""
     w = synth.scaled(synth.LLAMA, 0, n_q_heads=64, n_kv_heads=64)
-    say("attention, 11 row tiles on 4 units per KV head")
+    say(f"attention, 11 row tiles on 4 units per KV head, bunched={bunched}")
     hk, hq, d = w.n_kv_heads, w.n_q_heads, w.head_dim
     g = torch.Generator().manual_seed(93)
     lens = [3500, 2100]
@@ -565,7 +568,10 @@ def test_partial_attention_more_tiles_than_units():
     rows = 3600 + 2100
     k = torch.randn((rows, hk, d), generator=g).to(torch.bfloat16)
     v = torch.randn((rows, hk, d), generator=g).to(torch.bfloat16)
-    pos = np.concatenate([np.arange(1, 3500, 2)[:1700], np.arange(0, 2100, 2)[:1000]]).astype(np.int32)
+    if bunched:
+        pos = np.concatenate([np.arange(3500 - 1700, 3500), np.arange(2100 - 1000, 2100)]).astype(np.int32)
+    else:
+        pos = np.concatenate([np.arange(1, 3500, 2)[:1700], np.arange(0, 2100, 2)[:1000]]).astype(np.int32)
     cu = [0, 1700, 2700]
     q = (torch.randn((len(pos), hq, d), generator=g) / math.sqrt(d)).to(torch.bfloat16)
     got, lse = run_gpu_attention(w, q, pos, k, v, 1.0, off, lens, cu, with_workspace=False)
