@@ -354,6 +354,7 @@ __global__ __launch_bounds__(kSelThreads) void select_part_cand_kernel(const flo
     PartKeys pk;
     load_part(scores + lp.begin[part], lp.len[part], pk);
     const int first = lp.row_first[part], n_parts = lp.row_parts[part];
+    if (tid < 3) bcast[tid] = 0;       // (always overwritten: the row holds at least k entries)
     int c = 0;
     for (int q = 0; q < n_parts; ++q) c += hist[(first + q) * 1024 + tid];
     owner_from_top(c, lp.k[part], wave_tot, [&](int rank) { bcast[0] = tid; bcast[1] = rank; });
@@ -394,7 +395,7 @@ __global__ __launch_bounds__(kSelThreads) void select_part_cand_kernel(const flo
 // indices, i.e. to the earlier parts first) and the part's place in the output
 __global__ __launch_bounds__(kSelThreads) void select_row_threshold_kernel(const LongParts lp, const uint32_t *__restrict__ cand,
                                                                            const int4 *__restrict__ part_rec, const int4 *__restrict__ row_rec,
-                                                                           int4 *__restrict__ part_thr /* (T, equals taken, all equals taken, -) */,
+                                                                           int4 *__restrict__ part_thr /* (T, equals taken, entries the part writes, -) */,
                                                                            long long *__restrict__ part_out)
 {
     __shared__ int hist2[2048], hist3[2048];
@@ -408,6 +409,7 @@ __global__ __launch_bounds__(kSelThreads) void select_row_threshold_kernel(const
     hist2[tid] = 0; hist2[tid + kSelThreads] = 0;
     hist3[tid] = 0; hist3[tid + kSelThreads] = 0;
     if (tid < 2 * kMaxParts) (&cnt[0][0])[tid] = 0;
+    if (tid < 3) bcast[tid] = 0;       // NaN scores can leave a digit without an owner: stay defined
     __syncthreads();
     for (int q = 0; q < n_parts; ++q) {
         const uint32_t *__restrict__ seg = cand + lp.cand_off[part + q];
@@ -447,13 +449,17 @@ __global__ __launch_bounds__(kSelThreads) void select_row_threshold_kernel(const
     __syncthreads();
     if (tid == 0) {
         long long at = lp.out_off[part];
-        int eq_left = quota_eq;
+        int eq_left = max(quota_eq, 0), room = lp.k[part];
         for (int q = 0; q < n_parts; ++q) {
             const int n_eq = cnt[q][1];
             const int take = min(eq_left, n_eq);
-            part_thr[part + q] = make_int4((int)T, take, take == n_eq ? 1 : 0, 0);
+            // with well-formed scores the parts' counts add up to k exactly; the allotment keeps the
+            // writes inside the row's k entries whatever NaN scores do to the counts
+            const int n_out = min(part_rec[part + q].y + cnt[q][0] + take, room);
+            part_thr[part + q] = make_int4((int)T, take, n_out, 0);
             part_out[part + q] = at;
-            at += part_rec[part + q].y + cnt[q][0] + take;
+            at += n_out;
+            room -= n_out;
             eq_left -= take;
         }
     }
@@ -471,7 +477,7 @@ __global__ __launch_bounds__(kSelThreads) void select_part_write_kernel(const fl
     load_part(scores + lp.begin[part], lp.len[part], pk);
     const int4 thr = part_thr[part];
     const uint32_t T = (uint32_t)thr.x;
-    const uint32_t quota_eq = (uint32_t)thr.y;
+    const uint32_t quota_eq = (uint32_t)thr.y, n_out = (uint32_t)thr.z;
     int32_t *__restrict__ out = idx_out + part_out[part];
     const uint32_t local0 = (uint32_t)lp.local0[part];
     // entries equal to T count as selected while the part's share of the tie lasts (index order)
@@ -493,8 +499,8 @@ __global__ __launch_bounds__(kSelThreads) void select_part_write_kernel(const fl
         const uint32_t gt_before = base_gt + lanes_below(m_gt);
         const uint32_t eq_before = base_eq + lanes_below(m_eq);
         const int32_t e = (int32_t)(local0 + pk.e0 + j * kWave);
-        if (is_gt) out[gt_before + min(eq_before, quota_eq)] = e;
-        else if (is_eq && eq_before < quota_eq) out[gt_before + eq_before] = e;
+        const uint32_t slot = gt_before + min(eq_before, quota_eq);
+        if ((is_gt || (is_eq && eq_before < quota_eq)) && slot < n_out) out[slot] = e;
         base_gt += __popcll(m_gt);
         base_eq += __popcll(m_eq);
     }

@@ -222,6 +222,31 @@ def test_select_long_rows_over_several_workgroups():
     check_select(s, off, [500000, 3, 59999], "two groups of parts")
 
 
+@pytest.mark.parametrize("n", [9000, 150001])
+def test_select_nan_scores_stay_inside_the_output(n):
+    """NaN scores are a caller error with unspecified results, but the call must stay inside its
+    buffers: whatever comes out is at most k in-range indices per row and nothing is written past
+    them.  (The output tensor carries a guard region as large as the row, so a violation would
+    show up as changed guard entries, never as a stray write.)"""
+    rng = np.random.default_rng(12)
+    s = rng.standard_normal(n).astype(np.float32)
+    bits = s.view(np.uint32).copy()
+    nan_at = rng.random(n) < 0.3
+    bits[nan_at] = np.where(rng.random(int(nan_at.sum())) < 0.5, np.uint32(0x7FC00001), np.uint32(0xFFFFFFFF))
+    sc = torch.from_numpy(bits.view(np.float32).copy()).to(DEV)
+    ws = torch.empty(B.kvs_workspace_size("select_topk", shape_for(synth.TINY), 1, n), dtype=torch.uint8, device=DEV)
+    for k in (1, n // 2, n - 5, n):
+        for workspace in (None, ws):
+            say(f"select with NaN scores n={n} k={k} workspace={'yes' if workspace is not None else 'no'}")
+            out = torch.full((k + n,), -7, dtype=torch.int32, device=DEV)
+            B.kvs_select_topk(sc, [0, n], [k], out, workspace)
+            torch.cuda.synchronize()
+            got = out.cpu().numpy()
+            assert np.all(got[k:] == -7), "wrote past the row's k entries"
+            written = got[:k][got[:k] != -7]
+            assert np.all((written >= 0) & (written < n))
+
+
 def test_select_ragged_rows():
     rng = np.random.default_rng(6)
     lens = [5, 0, 4096, 1, 7000, 33000, 129, 64, 20000] + [int(x) for x in rng.integers(1, 3000, 70)]
