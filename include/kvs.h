@@ -7,7 +7,9 @@
  * --------------------------------
  * Pointers marked [dev] are device (HBM) addresses, pointers marked [host] are ordinary host
  * memory that is read before the call returns.  The caller owns every buffer; the library
- * allocates nothing, keeps no state between calls, and never synchronises: each call checks
+ * allocates nothing, reads no environment variable, and never synchronises.  The only state it
+ * keeps between calls is, per device, which kernels have had their launch attributes set and the
+ * device's compute-unit count (both written once, safely from several host threads).  Each call checks
  * its arguments on the host, enqueues its kernels on `stream` (a hipStream_t passed as
  * void*, NULL = the default stream) and returns.  Outputs are valid in stream order.
  *
@@ -112,6 +114,25 @@ KVS_API kvs_status kvs_select_topk(const float *scores, int32_t n_rows, const in
                            void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * kvs_select_topk_static -- kvs_select_topk for callers that cannot allocate device memory (code
+ * under stream capture, serving loops and harnesses that forbid hipMalloc): same arguments without
+ * the workspace, same results.  Rows longer than 49152 scores, which kvs_select_topk spreads over
+ * several workgroups only when given a workspace, here use a scratch buffer that belongs to the
+ * library: a file-scope device array of 4.3 MB (each device the library runs on holds it until
+ * the process ends).  The call allocates and frees nothing; on its first call on a device it asks
+ * the runtime once for that device's address of the array (a call with n_rows = 0 does just
+ * that and may be made ahead of time, e.g. before a stream capture begins).
+ *
+ * Limit: every row at most 1048576 (2^20) scores; a longer row returns KVS_EINVAL before anything
+ * is launched.  All calls on one device share that device's scratch and the kernels overwrite what
+ * they use before reading it, so nothing has to be cleared between calls; calls that overlap in
+ * time on one device (different streams, or host threads) race on it and must be serialised by
+ * the caller.
+ */
+KVS_API kvs_status kvs_select_topk_static(const float *scores, int32_t n_rows, const int64_t *row_off,
+                                  const int32_t *k_row, int32_t *idx_out, void *stream);
+
+/*
  * kvs_scatter_kv -- the KV Writer of App. A: recomputed K/V replace the reused entries.
  *
  *   k_cache[sel_pos[s]] = k_new[s],  v_cache[sel_pos[s]] = v_new[s]      for s in [0, n_sel)
@@ -177,6 +198,8 @@ KVS_API kvs_status kvs_partial_attention(const kvs_shape *shape, int32_t batch,
  * as ascending request-local indices at idx_out + sum(k_req[0..b)).
  *
  * n_rows    rows of the packed cache (row stride of dev_v, length of reused / score_out)
+ * ctx_off, ctx_len [host] int64[batch]; every context lies inside [0, n_rows) and no two contexts
+ *           share a cache row (KVS_EINVAL otherwise: scores and logits are kept per cache row)
  * q_new     [dev] [batch, n_q_heads, head_dim]
  * v_cache   [dev] only read when attn_out != NULL
  * dev_v     [dev] fp32[n_kv_heads, n_rows] as left by kvs_deviation / kvs_scatter_kv

@@ -21,7 +21,7 @@ F32, BF16 = 0, 1
 SCORE_V, SCORE_KV = 0, 1
 OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP = 0, 1, 2, 3, 4
 
-EXPORTS = ("kvs_deviation", "kvs_select_topk", "kvs_scatter_kv", "kvs_partial_attention",
+EXPORTS = ("kvs_deviation", "kvs_select_topk", "kvs_select_topk_static", "kvs_scatter_kv", "kvs_partial_attention",
            "kvs_decode_check", "kvs_attn_colsum", "kvs_workspace_size", "kvs_strerror", "kvs_last_error", "kvs_version")
 
 
@@ -54,13 +54,14 @@ def load(build_if_missing: bool = True) -> ctypes.CDLL:
     sp = ctypes.POINTER(Shape)
     lib.kvs_deviation.argtypes = [sp, i64, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp]
     lib.kvs_select_topk.argtypes = [vp, i32, vp, vp, vp, vp, sz, vp]
+    lib.kvs_select_topk_static.argtypes = [vp, i32, vp, vp, vp, vp]
     lib.kvs_scatter_kv.argtypes = [sp, i64, vp, vp, vp, i64, vp, vp, vp, vp, vp]
     lib.kvs_partial_attention.argtypes = [sp, i32, vp, vp, vp, vp, vp, vp, vp, f32, vp, vp, vp, sz, vp]
     lib.kvs_decode_check.argtypes = [sp, i32, i64, vp, vp, vp, vp, vp, vp, vp, f32, vp, vp, vp, vp, vp, sz, vp]
     lib.kvs_attn_colsum.argtypes = [sp, i64, vp, vp, f32, vp, vp, sz, vp]
     lib.kvs_workspace_size.argtypes = [ctypes.c_char_p, sp, i32, i64, i64]
-    for n in ("kvs_deviation", "kvs_select_topk", "kvs_scatter_kv", "kvs_partial_attention", "kvs_decode_check",
-              "kvs_attn_colsum"):
+    for n in ("kvs_deviation", "kvs_select_topk", "kvs_select_topk_static", "kvs_scatter_kv", "kvs_partial_attention",
+              "kvs_decode_check", "kvs_attn_colsum"):
         getattr(lib, n).restype = ctypes.c_int
     lib.kvs_workspace_size.restype = sz
     lib.kvs_strerror.argtypes = [ctypes.c_int]
@@ -139,6 +140,15 @@ def kvs_select_topk(scores, row_off: Sequence[int], k_row: Sequence[int], idx_ou
     rc = load().kvs_select_topk(_ptr(scores, torch.float32), len(kr), _hp(ro), _hp(kr),
                                 _ptr(idx_out, torch.int32), _ptr(workspace), ws_bytes, _stream(stream))
     _check(rc, "kvs_select_topk")
+
+
+def kvs_select_topk_static(scores, row_off: Sequence[int], k_row: Sequence[int], idx_out, stream=None) -> None:
+    ro, kr = _host(row_off, np.int64), _host(k_row, np.int32)
+    if len(ro) != len(kr) + 1:
+        raise ValueError("row_off must have len(k_row)+1 entries")
+    rc = load().kvs_select_topk_static(_ptr(scores, torch.float32), len(kr), _hp(ro), _hp(kr),
+                                       _ptr(idx_out, torch.int32), _stream(stream))
+    _check(rc, "kvs_select_topk_static")
 
 
 def kvs_scatter_kv(shape: Shape, n_rows: int, k_new, v_new, sel_pos, n_sel: int, k_cache, v_cache,

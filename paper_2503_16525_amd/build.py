@@ -13,6 +13,10 @@ CSRC = os.path.join(PKG, "csrc")
 INCLUDE = os.path.join(ROOT, "include")
 OBJ_DIR = os.path.join(PKG, "_build")
 LIB_PATH = os.path.join(PKG, "libkvshare_hip.so")
+# the same library with the large-launch attention kernel pinned at compile time: only the test
+# suite loads it, to run that kernel at sizes the oracle can follow (the shipped library has no
+# run-time switch)
+LIB_BIGATTN_PATH = os.path.join(PKG, "libkvshare_hip_bigattn.so")
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
@@ -36,12 +40,12 @@ def sources():
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
 
 
-def _compile(src: str, force: bool) -> str:
-    obj = os.path.join(OBJ_DIR, os.path.basename(src) + ".o")
+def _compile(src: str, force: bool, defines=(), tag: str = "") -> str:
+    obj = os.path.join(OBJ_DIR, os.path.basename(src) + tag + ".o")
     deps = [src] + glob.glob(os.path.join(CSRC, "*.h")) + glob.glob(os.path.join(INCLUDE, "*.h"))
     if not force and os.path.exists(obj) and all(os.path.getmtime(obj) >= os.path.getmtime(d) for d in deps):
         return obj
-    cmd = [HIPCC] + FLAGS + EXTRA_FLAGS.get(os.path.basename(src), []) + ["-c", src, "-o", obj]
+    cmd = [HIPCC] + FLAGS + EXTRA_FLAGS.get(os.path.basename(src), []) + list(defines) + ["-c", src, "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     msgs = "\n".join(l for l in (r.stdout + r.stderr).splitlines()
                      if "is not a recognized feature for this target" not in l)
@@ -52,18 +56,27 @@ def _compile(src: str, force: bool) -> str:
     return obj
 
 
-def build(force: bool = False, jobs: int = 8) -> str:
-    os.makedirs(OBJ_DIR, exist_ok=True)
-    srcs = sources()
-    with concurrent.futures.ThreadPoolExecutor(max_workers=jobs) as ex:
-        objs = list(ex.map(lambda s: _compile(s, force), srcs))
-    if force or not os.path.exists(LIB_PATH) or any(os.path.getmtime(o) > os.path.getmtime(LIB_PATH) for o in objs):
-        tmp = LIB_PATH + f".tmp{os.getpid()}"
-        r = subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp] + objs,
+def _link(objs, lib: str, force: bool) -> None:
+    if force or not os.path.exists(lib) or any(os.path.getmtime(o) > os.path.getmtime(lib) for o in objs):
+        tmp = lib + f".tmp{os.getpid()}"
+        r = subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp] + list(objs),
                            capture_output=True, text=True)
         if r.returncode != 0:
             raise RuntimeError("link failed:\n" + r.stdout + r.stderr)
-        os.replace(tmp, LIB_PATH)
+        os.replace(tmp, lib)
+
+
+def build(force: bool = False, jobs: int = 8) -> str:
+    os.makedirs(OBJ_DIR, exist_ok=True)
+    srcs = sources()
+    pinned = os.path.join(CSRC, "attention_mfma.hip")      # holds the choice between the attention kernels
+    with concurrent.futures.ThreadPoolExecutor(max_workers=jobs) as ex:
+        big = ex.submit(_compile, pinned, force, ("-DKVS_ATTN_FORCE=2",), ".bigattn")
+        objs = list(ex.map(lambda s: _compile(s, force), srcs))
+        big_obj = big.result()
+    _link(objs, LIB_PATH, force)
+    plain = os.path.join(OBJ_DIR, os.path.basename(pinned) + ".o")
+    _link([big_obj if o == plain else o for o in objs], LIB_BIGATTN_PATH, force)
     return LIB_PATH
 
 

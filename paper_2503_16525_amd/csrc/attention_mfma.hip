@@ -407,16 +407,16 @@ kvs_status launch_mfma_variant(const kvs_shape *shape, const AttnBatch &bd, cons
     if (tiles < 0) return fail(KVS_EINVAL, "kvs_partial_attention: too many row tiles");
     if (tiles == 0) return KVS_OK;
     const size_t lds_bytes = 2 * STAGE * sizeof(uint16_t);
-    static bool attr_set = false;   // idempotent; a race only repeats the same call
-    if (!attr_set) {
+    static DeviceOnce attr_once;
+    const kvs_status ast = once_per_device(attr_once, [] {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_mfma_kernel<NWAVES, false>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
         if (e == hipSuccess)
             e = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_mfma_kernel<NWAVES, true>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
-        if (e != hipSuccess) return fail(KVS_EHIP, "kvs_partial_attention: hipFuncSetAttribute: %s", hipGetErrorString(e));
-        attr_set = true;
-    }
+        return e == hipSuccess ? KVS_OK : fail(KVS_EHIP, "kvs_partial_attention: hipFuncSetAttribute: %s", hipGetErrorString(e));
+    });
+    if (ast != KVS_OK) return ast;
     const float scale_log2 = scale * 1.4426950408889634f;
     // split the key range when the launch is too small to fill the chip, the contexts are long
     // enough for every piece to have work, and the caller's workspace can hold the pieces
@@ -509,14 +509,13 @@ kvs_status launch_attention_mfma(const kvs_shape *shape, const AttnBatch &bd, in
     if (!attention_mfma_supports(shape)) return fail(KVS_EUNSUPPORTED, "kvs_partial_attention: matrix-core path needs bf16, head_dim 128");
     if (!(scale > 0.f) || !isfinite(scale)) return fail(KVS_EUNSUPPORTED, "kvs_partial_attention: matrix-core path needs a positive finite scale");
     // enough 256-row tiles to give every CU work: the 64-rows-per-wave kernel; otherwise the
-    // finer-grained one, which fills the chip better.  KVS_ATTN_VARIANT=small|big in the environment
-    // pins the choice (used by the tests to reach both kernels at small sizes).
-    static const int forced = [] {
-        const char *e = getenv("KVS_ATTN_VARIANT");
-        if (e && strcmp(e, "small") == 0) return 1;
-        if (e && strcmp(e, "big") == 0) return 2;
-        return 0;
-    }();
+    // finer-grained one, which fills the chip better.  A build with -DKVS_ATTN_FORCE=1 (small) or 2
+    // (large) pins the choice: the test suite builds such a library beside the shipped one to reach
+    // the large-launch kernel at sizes the oracle can follow.  The shipped library has no switch.
+#ifndef KVS_ATTN_FORCE
+#define KVS_ATTN_FORCE 0
+#endif
+    constexpr int forced = KVS_ATTN_FORCE;
     const int grp = shape->n_q_heads / shape->n_kv_heads;
     int64_t big_tiles = 0, rows = 0;
     // the large kernel addresses a request's keys with 32-bit byte offsets from its first token

@@ -92,9 +92,6 @@ __device__ __forceinline__ float add_rounded_pair(uint32_t w, float acc)   // ac
     typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
     return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w), __builtin_bit_cast(bf16x2, 0x3f803f80u), acc, false);
 }
-#ifdef KVS_DIAG_CLOCK
-__device__ long long kvs_diag_clk[4096];
-#endif
 
 
 // An unsplit launch with shares (share_units > 0) starts one workgroup per compute unit and KV
@@ -242,9 +239,6 @@ __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
     const int it_begin = listed ? 0 : wg, it_end = listed ? n_my_tiles : wg + 1;
     for (int it = it_begin; it < it_end; ++it) {
     if (it != it_begin) __syncthreads();   // every wave has left the previous tile: rings and tables are free
-#ifdef KVS_DIAG_CLOCK
-    const long long diag_t0 = clock64(), diag_w0 = wall_clock64();
-#endif
     const int rest = it;
     // split launches walk the list of pieces the plan kernel wrote: the pieces that have keys first,
     // from the top of the context down, then the empty ones (which only mark their slot)
@@ -612,13 +606,7 @@ __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
     // pass with those (pass 1), which cannot overflow: a correctness net.
     __shared__ int redo_flag;
     float l_tot[NB];
-#ifdef KVS_DIAG_CLOCK
-    int diag_pass = 0;
-#endif
     for (int pass = 0; pass < 2; ++pass) {
-#ifdef KVS_DIAG_CLOCK
-        diag_pass = pass;
-#endif
         if (pass == 1) {
             // exact row maxima: a score-only sweep with three tiles on their way.  Tile jt+3 goes to
             // the K slot of tile jt-1, which every wave has finished reading when it passes the
@@ -725,19 +713,6 @@ __global__ __launch_bounds__(NT, 1) void attn_mfma2_kernel(
         if (redo_flag == 0) break;
     }
 
-#ifdef KVS_DIAG_CLOCK
-#ifndef KVS_DIAG_FIRST
-#define KVS_DIAG_FIRST 0
-#endif
-    const int diag_id = listed ? tile_lin * n_kv_heads + g : (int)blockIdx.x;
-    if (tid == 0 && diag_id >= KVS_DIAG_FIRST && diag_id < KVS_DIAG_FIRST + 1024) {
-        const int di = diag_id - KVS_DIAG_FIRST;
-        kvs_diag_clk[4 * di] = clock64() - diag_t0;
-        kvs_diag_clk[4 * di + 1] = wall_clock64() - diag_w0;
-        kvs_diag_clk[4 * di + 2] = (t_hi - t_lo) + 4096 * max(0, t_hi - max(t_lo, (pmin + 1) / BN)) + 4096 * 4096 * (long long)diag_pass;
-        kvs_diag_clk[4 * di + 3] = diag_w0;
-    }
-#endif
     // ---- epilogue: normalise, convert, store ----------------------------------------------------------
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
@@ -899,13 +874,13 @@ kvs_status launch_one(const dim3 grid, size_t lds_bytes, hipStream_t st, const A
                       float scale_log2, void *out, float *lse_out, int n_splits, const int4 *split_plan,
                       const uint16_t *piece_list, float *part_o, float4 *part_ml, int share_units)
 {
-    static bool attr_set = false;   // idempotent; a race only repeats the same call
-    if (!attr_set) {
+    static DeviceOnce attr_once;
+    const kvs_status ast = once_per_device(attr_once, [lds_bytes] {
         const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_mfma2_kernel<WANT_LSE, SPLIT>),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
-        if (e != hipSuccess) return fail(KVS_EHIP, "kvs_partial_attention: hipFuncSetAttribute: %s", hipGetErrorString(e));
-        attr_set = true;
-    }
+        return e == hipSuccess ? KVS_OK : fail(KVS_EHIP, "kvs_partial_attention: hipFuncSetAttribute: %s", hipGetErrorString(e));
+    });
+    if (ast != KVS_OK) return ast;
     hipLaunchKernelGGL((attn_mfma2_kernel<WANT_LSE, SPLIT>), grid, dim3(NT), lds_bytes, st, td, shape->n_q_heads,
                        shape->n_kv_heads, tiles, (const uint16_t *)q_sel, sel_pos, (const uint16_t *)k_cache,
                        (const uint16_t *)v_cache, scale_log2, (uint16_t *)out, lse_out, n_splits, split_plan, piece_list,
@@ -922,10 +897,14 @@ int share_units_for(const kvs_shape *shape, int64_t tiles)
     return 0;
 #endif
     // one workgroup per compute unit only works out if the device has the units the shares are made for
-    static int device_cus = -1;   // idempotent; a race only repeats the same query
-    if (device_cus < 0) {
-        int dev = 0, n = 0;
-        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) n = 0;
+    static std::atomic<int> cus_of[kMaxDevices];   // 0: not asked yet; the query is idempotent
+    const int dev = current_device();
+    if (dev < 0 || dev >= kMaxDevices) return 0;
+    int device_cus = cus_of[dev].load(std::memory_order_relaxed);
+    if (device_cus == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = -1;
+        cus_of[dev].store(n, std::memory_order_relaxed);
         device_cus = n;
     }
     if (device_cus != kAttnSplitCus) return 0;
@@ -1012,14 +991,6 @@ kvs_status launch_attention_mfma2(const kvs_shape *shape, const AttnBatch &bd, c
     uint16_t *piece_list = (uint16_t *)(split_plan + 1);
     float round_fill = kAttnRoundFill, piece_overhead = kAttnPieceOverhead;
     int forced_chunk = plan.chunk, small_chunk = plan.small_chunk, n_small = plan.n_small;
-#ifdef KVS_DIAG_CHUNK
-    if (const char *e = getenv("KVS_ATTN_SMALL")) small_chunk = atoi(e);
-    if (const char *e = getenv("KVS_ATTN_NSMALL")) n_small = atoi(e);
-    if (const char *e = getenv("KVS_ATTN_FILL")) round_fill = (float)atof(e);
-    if (const char *e = getenv("KVS_ATTN_OVH")) piece_overhead = (float)atof(e);
-    if (const char *e = getenv("KVS_ATTN_CHUNK")) forced_chunk = atoi(e);
-    if (n_small * small_chunk * 2 > plan.ctx_tiles || n_small + 2 > n_splits) n_small = 0;
-#endif
     hipLaunchKernelGGL(attn_plan_kernel, dim3(1), dim3(PLAN_NT), 0, st, td, shape->n_q_heads / shape->n_kv_heads,
                        shape->n_kv_heads, (int)tiles, sel_pos, n_splits, plan.ctx_tiles, small_chunk, n_small, round_fill,
                        piece_overhead, forced_chunk, split_plan, piece_list);
@@ -1037,9 +1008,3 @@ kvs_status launch_attention_mfma2(const kvs_shape *shape, const AttnBatch &bd, c
 
 } // namespace kvs
 
-#ifdef KVS_DIAG_CLOCK
-extern "C" __attribute__((visibility("default"))) int kvs_diag_read(long long *host, int n)
-{
-    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(kvs::kvs_diag_clk), sizeof(long long) * n);
-}
-#endif

@@ -346,13 +346,13 @@ template <int SWEEP>
 kvs_status launch_sweep(const kvs_shape *shape, int64_t n, const void *q, const void *k, float scale_log2,
                         float *lse2, float *alpha, hipStream_t st)
 {
-    static bool attr_set = false;   // idempotent; a race only repeats the same call
-    if (!attr_set) {
+    static DeviceOnce attr_once;
+    const kvs_status ast = once_per_device(attr_once, [] {
         const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&colsum_kernel<SWEEP>),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
-        if (e != hipSuccess) return fail(KVS_EHIP, "kvs_attn_colsum: hipFuncSetAttribute: %s", hipGetErrorString(e));
-        attr_set = true;
-    }
+        return e == hipSuccess ? KVS_OK : fail(KVS_EHIP, "kvs_attn_colsum: hipFuncSetAttribute: %s", hipGetErrorString(e));
+    });
+    if (ast != KVS_OK) return ast;
     const int grp = shape->n_q_heads / shape->n_kv_heads;
     const int64_t n_fixed = SWEEP == 1 ? n * grp : n;
     const int64_t blocks = (n_fixed + FIXED - 1) / FIXED;

@@ -593,6 +593,27 @@ extern "C" kvs_status kvs_decode_check(const kvs_shape *shape, int32_t batch, in
         total_k += k_req[b];
     }
     if (total_k > 0 && !idx_out) return fail(KVS_EINVAL, "kvs_decode_check: idx_out is NULL");
+    // The contexts must not share cache rows: logits, scores and the per-tile softmax partials are
+    // indexed by cache row, so overlapping requests would overwrite each other's and overrun the
+    // tile tables, which are sized for n_rows rows in all.  Batches whose offsets ascend (the usual
+    // packing) are checked in one pass, any other order pairwise.
+    {
+        bool ascending = true;
+        for (int32_t b = 1; b < batch && ascending; ++b) ascending = ctx_off[b] >= ctx_off[b - 1];
+        int64_t end_so_far = 0;   // ascending offsets: end of the last non-empty context seen
+        for (int32_t b = 0; b < batch; ++b) {
+            if (ctx_len[b] == 0) continue;
+            if (ascending) {
+                if (ctx_off[b] < end_so_far)
+                    return fail(KVS_EINVAL, "kvs_decode_check: request %d shares cache rows with an earlier one", b);
+                end_so_far = ctx_off[b] + ctx_len[b];
+            } else {
+                for (int32_t a = 0; a < b; ++a)
+                    if (ctx_len[a] > 0 && ctx_off[a] < ctx_off[b] + ctx_len[b] && ctx_off[b] < ctx_off[a] + ctx_len[a])
+                        return fail(KVS_EINVAL, "kvs_decode_check: requests %d and %d share cache rows", a, b);
+            }
+        }
+    }
     if (shape->n_q_heads > 256) return fail(KVS_EUNSUPPORTED, "kvs_decode_check: more than 256 query heads");
     const size_t need = decode_workspace_bytes(shape, batch, n_rows);
     if (!workspace || workspace_bytes < need) return fail(KVS_EWORKSPACE, "kvs_decode_check: workspace %zu < %zu bytes", workspace_bytes, need);
@@ -654,13 +675,13 @@ extern "C" kvs_status kvs_decode_check(const kvs_shape *shape, int32_t batch, in
         const bool mma = shape->dtype == KVS_BF16 && d == 128 && grp <= 32 && n_rows * (int64_t)hk * 256 < ((int64_t)1 << 32) &&
                          aligned16(q_new) && aligned16(k_cache);
         if (mma) {
-            static bool attr_set = false;   // idempotent; a race only repeats the same call
-            if (!attr_set) {
+            static DeviceOnce attr_once;
+            st = once_per_device(attr_once, [] {
                 const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&decode_logits_mfma_kernel),
                                                          hipFuncAttributeMaxDynamicSharedMemorySize, kMmaLds);
-                if (e != hipSuccess) return fail(KVS_EHIP, "kvs_decode_check: hipFuncSetAttribute: %s", hipGetErrorString(e));
-                attr_set = true;
-            }
+                return e == hipSuccess ? KVS_OK : fail(KVS_EHIP, "kvs_decode_check: hipFuncSetAttribute: %s", hipGetErrorString(e));
+            });
+            if (st != KVS_OK) return st;
             hipLaunchKernelGGL(decode_logits_mfma_kernel, dim3((unsigned)tiles_tok), block, kMmaLds, hs, bd_tok, hq, hk, n_rows,
                                (const uint16_t *)q_new, (const uint16_t *)k_cache, scale, logits, part_l);
         }

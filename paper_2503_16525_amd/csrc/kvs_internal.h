@@ -6,6 +6,8 @@
 #include <stdint.h>
 #include <stddef.h>
 
+#include <atomic>
+
 #include "kvs.h"
 
 namespace kvs {
@@ -21,6 +23,30 @@ inline size_t elem_bytes(int32_t dtype) { return dtype == KVS_F32 ? 4 : 2; }
 kvs_status check_shape(const kvs_shape *s);
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// One-time set-up per device (kernel attributes, device queries).  The HIP runtime keeps function
+// attributes per device, so the "done" flag is per device as well.  The set-up calls are idempotent:
+// two host threads that race through one only repeat the same calls, and the flag is published
+// with release/acquire ordering.  Devices past the table simply repeat the set-up on every call.
+constexpr int kMaxDevices = 64;
+struct DeviceOnce {
+    std::atomic<int> done[kMaxDevices];
+};
+inline int current_device()
+{
+    int dev = -1;
+    return hipGetDevice(&dev) == hipSuccess ? dev : -1;
+}
+template <typename F>
+inline kvs_status once_per_device(DeviceOnce &once, F setup)
+{
+    const int dev = current_device();
+    const bool tracked = dev >= 0 && dev < kMaxDevices;
+    if (tracked && once.done[dev].load(std::memory_order_acquire)) return KVS_OK;
+    const kvs_status st = setup();
+    if (st == KVS_OK && tracked) once.done[dev].store(1, std::memory_order_release);
+    return st;
+}
 
 // exact top-k over rows given as (begin, len) pairs of one score array (select.hip); the workspace
 // (may be NULL) lets rows too long for one workgroup spread over several

@@ -29,8 +29,6 @@
 // one-workgroup kernel, which then re-reads its keys from L2 on every sweep.
 #include "kvs_internal.h"
 
-#include <new>
-
 namespace kvs {
 namespace {
 
@@ -506,10 +504,10 @@ __global__ __launch_bounds__(kSelThreads) void select_part_write_kernel(const fl
     }
 }
 
-inline size_t sel_align(size_t x) { return (x + 255) & ~(size_t)255; }
+constexpr size_t sel_align(size_t x) { return (x + 255) & ~(size_t)255; }
 
 // workspace of one group of parts holding `entries` scores
-inline size_t long_group_bytes(int parts, int64_t entries)
+constexpr size_t long_group_bytes(int parts, int64_t entries)
 {
     return sel_align(sizeof(int) * 1024 * (size_t)parts) + sel_align(sizeof(uint32_t) * (size_t)entries) +
            3 * sel_align(sizeof(int4) * (size_t)parts) + sel_align(sizeof(long long) * (size_t)parts);
@@ -629,6 +627,54 @@ kvs_status launch_select(const float *scores, int32_t n_rows, const int64_t *beg
 
 } // namespace kvs
 
+namespace kvs {
+namespace {
+
+// ---- the scratch of kvs_select_topk_static -----------------------------------------------------------
+// Device memory that belongs to the library instead of the caller: room for one group of parts of
+// rows up to kStaticMaxRow scores (part histograms, candidate keys, per-part records), 4.3 MB that
+// every device the library runs on holds until the process ends.  In host code the array's name
+// is only a handle: the address the kernels get comes from hipGetSymbolAddress, asked once per
+// device with that device current (every device has its own copy at its own address).
+constexpr int64_t kStaticMaxRow = (int64_t)1 << 20;
+constexpr size_t kStaticScratchBytes = long_group_bytes((int)(kStaticMaxRow / kPartLen), kStaticMaxRow);
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+std::atomic<void *> g_scratch_ptr[kMaxDevices];
+
+kvs_status static_scratch(void **out)
+{
+    const int dev = current_device();
+    if (dev < 0 || dev >= kMaxDevices) return fail(KVS_EHIP, "kvs_select_topk_static: no current device, or more than %d devices", kMaxDevices);
+    void *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) return fail(KVS_EHIP, "kvs_select_topk_static: hipGetSymbolAddress: %s", hipGetErrorString(e));
+        g_scratch_ptr[dev].store(p, std::memory_order_release);
+    }
+    *out = p;
+    return KVS_OK;
+}
+
+} // namespace
+} // namespace kvs
+
+extern "C" kvs_status kvs_select_topk_static(const float *scores, int32_t n_rows, const int64_t *row_off,
+                                             const int32_t *k_row, int32_t *idx_out, void *stream)
+{
+    using namespace kvs;
+    // the address is looked up before anything else, so a call with n_rows = 0 is a way to get the
+    // one-time lookup done (outside a stream capture, say) without launching anything
+    void *ws = nullptr;
+    const kvs_status st = static_scratch(&ws);
+    if (st != KVS_OK) return st;
+    if (n_rows > 0 && row_off)
+        for (int32_t r = 0; r < n_rows; ++r)
+            if (row_off[r + 1] - row_off[r] > kStaticMaxRow)
+                return fail(KVS_EINVAL, "kvs_select_topk_static: row %d has %lld scores, the library's own scratch holds rows up to %lld",
+                            r, (long long)(row_off[r + 1] - row_off[r]), (long long)kStaticMaxRow);
+    return kvs_select_topk(scores, n_rows, row_off, k_row, idx_out, ws, kStaticScratchBytes, stream);
+}
+
 extern "C" kvs_status kvs_select_topk(const float *scores, int32_t n_rows, const int64_t *row_off,
                                       const int32_t *k_row, int32_t *idx_out,
                                       void *workspace, size_t workspace_bytes, void *stream)
@@ -648,13 +694,23 @@ extern "C" kvs_status kvs_select_topk(const float *scores, int32_t n_rows, const
     }
     if (total_k == 0) return KVS_OK;
     if (!scores || !idx_out) return fail(KVS_EINVAL, "kvs_select_topk: scores/idx_out is NULL");
-    // (begin, len) view of the packed rows
+    // (begin, len) view of the packed rows, a stack table of 256 rows at a time (no host allocation)
     constexpr int kStack = 256;
-    int64_t lens_stack[kStack];
-    int64_t *lens = n_rows <= kStack ? lens_stack : new (std::nothrow) int64_t[n_rows];
-    if (!lens) return fail(KVS_EINVAL, "kvs_select_topk: out of host memory");
-    for (int32_t r = 0; r < n_rows; ++r) lens[r] = row_off[r + 1] - row_off[r];
-    kvs_status st = launch_select(scores, n_rows, row_off, lens, k_row, idx_out, workspace, workspace_bytes, (hipStream_t)stream);
-    if (lens != lens_stack) delete[] lens;
-    return st;
+    int64_t lens[kStack];
+    int64_t out_base = 0;
+    for (int32_t r0 = 0; r0 < n_rows; r0 += kStack) {
+        const int32_t nr = n_rows - r0 < kStack ? n_rows - r0 : kStack;
+        int64_t k_here = 0;
+        for (int32_t r = 0; r < nr; ++r) {
+            lens[r] = row_off[r0 + r + 1] - row_off[r0 + r];
+            k_here += k_row[r0 + r];
+        }
+        if (k_here > 0) {
+            const kvs_status st = launch_select(scores, nr, row_off + r0, lens, k_row + r0, idx_out + out_base, workspace,
+                                                workspace_bytes, (hipStream_t)stream);
+            if (st != KVS_OK) return st;
+        }
+        out_base += k_here;
+    }
+    return KVS_OK;
 }

@@ -116,6 +116,13 @@ def test_decode_argument_errors(lib):
     assert call(k=np.array([1, 61], np.int32)) == B.EINVAL
     assert call(attn=FAKE) == B.EINVAL                        # attn_out without v_cache
     assert b"v_cache" in lib.kvs_last_error()
+    # contexts may not share cache rows, whichever order the requests come in
+    for offs, lens in (([0, 40], [50, 60]), ([40, 0], [60, 50])):
+        co2, cl2 = np.array(offs, np.int64), np.array(lens, np.int64)
+        k0 = np.array([0, 0], np.int32)
+        rc = lib.kvs_decode_check(ctypes.byref(sh), 2, 110, co2.ctypes.data, cl2.ctypes.data, FAKE, FAKE, None,
+                                  FAKE, None, 1.0, k0.ctypes.data, FAKE, None, None, FAKE * 16, need, None)
+        assert rc == B.EINVAL and b"cache rows" in lib.kvs_last_error()
     assert B.kvs_workspace_size("nonsense", sh, 1, 10) == 0
 
 

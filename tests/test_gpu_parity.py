@@ -13,14 +13,17 @@ import pytest
 import torch
 
 import oracle
+from attn_check import check_attention, check_topk_band
 from paper_2503_16525_amd import binding as B
 from paper_2503_16525_amd import synth
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda"
+CASE = [""]     # what say() last announced: labels the tolerance records
 
 
 def say(msg):
+    CASE[0] = msg
     print(f"[case] {msg}", flush=True)
     sys.stdout.flush()
 
@@ -337,20 +340,10 @@ def attn_magnitude(q_sel, pos, k, v, scale, *args):
 
 
 def assert_attn_close(got, ref, w, mag=None):
-    """fp32: 1e-4 absolute.  bf16: 2e-2 absolute plus 2^-8 of the attended magnitude
-    mag = sum_i a_i |v_i| (|ref| if not given).  The second term is what bf16 itself costs on the
-    matrix-core path: each softmax weight enters the PV product rounded to bf16 (relative error up
-    to 2^-9, either sign, so the terms of a cancelling sum do not cancel their errors) and the
-    output is stored in bf16 (up to 2^-9 of |o| <= mag).  With N(0,1) values mag is about 0.8 and
-    the bound is 2.3e-2; the heavy-tailed cache noise of the synthetic workloads produces rows with
-    |V| in the tens, where an absolute 2e-2 is below bf16's resolution."""
-    got, ref = np.asarray(got, np.float64), np.asarray(ref, np.float64)
-    tol = np.full(ref.shape, attn_tol(w))
-    if w.dtype == "bf16":
-        tol = tol + (np.abs(ref) if mag is None else np.asarray(mag, np.float64)) * 2.0 ** -8
-    err = np.abs(got - ref)
-    worst = np.unravel_index(np.argmax(err - tol), err.shape)
-    assert np.all(err <= tol), f"max excess at {worst}: got {got[worst]} ref {ref[worst]} err {err[worst]}"
+    """fp32: 1e-4 absolute.  bf16: the flat 2e-2 wherever the attended magnitude mag = sum_i a_i |v_i|
+    is at most 2.5, and 2e-2 + 2^-8 mag above that, where the output's own bf16 spacing reaches the
+    flat bar (attn_check.py has the argument and logs how much of the slack each case used)."""
+    check_attention(got, ref, mag, w.dtype, CASE[0])
 
 
 ATT_CASES = [
@@ -612,20 +605,6 @@ def test_partial_attention_more_tiles_than_units(bunched):
 
 
 # --------------------------------------------------------------------------------- decode check
-
-def check_topk_band(idx, score_ref, k, rtol=2e-5):
-    """idx is a valid top-k of scores that agree with score_ref to rtol: everything clearly above
-    the k-th reference score is in, everything clearly below is out, indices ascending/unique."""
-    assert len(idx) == k
-    if k == 0:
-        return
-    assert np.all(np.diff(idx) > 0) and idx[0] >= 0 and idx[-1] < len(score_ref)
-    thr = np.sort(score_ref)[::-1][k - 1]
-    chosen = np.zeros(len(score_ref), bool)
-    chosen[idx] = True
-    assert np.all(chosen[score_ref > thr * (1 + rtol) + 1e-30]), "a clearly better candidate was left out"
-    assert not np.any(chosen[score_ref < thr * (1 - rtol) - 1e-30]), "a clearly worse candidate was taken"
-
 
 # ------------------------------------------------------------------- attention column mass
 
