@@ -203,9 +203,9 @@ def cpu_baseline_and_parity(w, ratio: float, sh, alpha, n_sample: int) -> dict:
     out = torch.empty((len(pick), hq, d), dtype=torch.bfloat16, device="cuda")
     B.kvs_partial_attention(sh, [0], [n], [0, len(pick)], q_s.cuda(), torch.from_numpy(pos_s).cuda(), gk, gv, 1.0, out)
     err = np.abs(out.float().cpu().numpy() - out_ref)
-    # flat 2e-2 where the attended magnitude sum_i a_i |v_i| is at most 2.5; above that the output's own
+    # flat 2e-2 where the attended magnitude sum_i a_i |v_i| is at most 4; above that the output's own
     # bf16 spacing reaches the flat bar and 2^-8 of the magnitude is added
-    tol = np.where(mag_ref <= 2.5, 2e-2, 2e-2 + mag_ref * 2.0 ** -8)
+    tol = np.where(mag_ref <= 4.0, 2e-2, 2e-2 + mag_ref * 2.0 ** -8)
     assert np.all(err <= tol), f"attention differs from the oracle by {err.max()}"
     log(f"[bench] parity vs oracle on layer 0: scores rtol 1e-5 ok, top-{k} exact, scatter exact, "
         f"attention max err {err.max():.4f} on {len(pick)} sampled queries")

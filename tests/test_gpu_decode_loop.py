@@ -138,7 +138,8 @@ def run_decode_loop(batch, len_lo, len_hi, steps, attn_every, half_reused_reques
             n_attn_checked += 1
     assert int(remaining.sum()) == 0, "the pool did not drain"
     assert first_idle is not None and first_idle < steps - 1, "no k = 0 step was reached"
-    assert int(gr.sum()) == 0 and float(dev_gpu.abs().max()) == 0.0
+    was_candidate = torch.from_numpy(reused0.astype(bool)).to(DEV)
+    assert int(gr.sum()) == 0 and float(dev_gpu[:, was_candidate].abs().max()) == 0.0
     for b in range(batch):      # every reused token of the initial context was recomputed exactly once
         assert ever[b] == set(np.nonzero(reused0[off[b]: off[b] + lens0[b]])[0].tolist())
     assert n_attn_checked >= 3

@@ -27,7 +27,7 @@ def say(msg):
 
 
 def attn_close(got, ref, mag, what=""):
-    """The bf16 bar of attn_check.py: flat 2e-2 where the attended magnitude is at most 2.5,
+    """The bf16 bar of attn_check.py: flat 2e-2 where the attended magnitude is at most 4,
     2e-2 + 2^-8 of it above; the slack each case used is logged."""
     check_attention(got, ref, mag, "bf16", f"{CASE[0]} {what}".strip())
 
