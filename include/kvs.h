@@ -90,6 +90,36 @@ KVS_API kvs_status kvs_deviation(const kvs_shape *shape, int64_t n_tokens,
                          float *dev_k, float *dev_v, float *score, void *stream);
 
 /*
+ * kvs_deviation_topk -- Alg. 1 steps 3 and 4 in one call: the scores of kvs_deviation and, from
+ * them, the k highest-scoring tokens of the one row of n_tokens scores, exactly as
+ * kvs_select_topk(score, 1, {0, n_tokens}, {k}, idx_out) would return them (order (score
+ * descending, index ascending), -0 equal to +0, -inf last, ascending indices out; bit-identical
+ * to the two separate calls).  All arguments up to `score` are those of kvs_deviation.
+ *
+ * k        0 <= k <= n_tokens           idx_out [dev] int32[k]
+ * score    [dev] fp32[n_tokens]; may be NULL for rows of at most 262144 tokens
+ * workspace [dev] optional, as for kvs_select_topk: only used by rows above 262144 tokens, which
+ *          run as the two separate calls
+ *
+ * Rows of at most 262144 tokens take three launches: the scoring kernel also stores every token's
+ * order-preserving key and counts the keys' leading 13 bits into a histogram (integer atomics, so
+ * the counts do not depend on arrival order and the result stays deterministic); then, with one
+ * workgroup per 1024 keys, a launch that reads the threshold's bin off the histogram and sets the
+ * few hundred keys of that bin aside, and a launch that resolves the other 19 bits on those and
+ * writes the list.  Keys, histogram (32 KiB) and the records the launches exchange live in
+ * device memory that belongs to the library (2.1 MB per device); the histogram is all zero
+ * whenever no such call is in flight.  Calls that overlap in time on one device (two streams, two
+ * host threads) would mix their counts: the caller serialises them.
+ */
+KVS_API kvs_status kvs_deviation_topk(const kvs_shape *shape, int64_t n_tokens,
+                              const void *k_fresh, const void *v_fresh,
+                              const void *k_cache, const void *v_cache,
+                              const uint8_t *reused, const float *alpha, int32_t mode,
+                              float *dev_k, float *dev_v, float *score,
+                              int32_t k, int32_t *idx_out,
+                              void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * kvs_select_topk -- Alg. 1 step 4: the k highest-scoring entries of each row.
  *
  * Row r of the ragged matrix is scores[row_off[r] .. row_off[r+1]).  The k_row[r] entries

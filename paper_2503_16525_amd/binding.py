@@ -21,7 +21,7 @@ F32, BF16 = 0, 1
 SCORE_V, SCORE_KV = 0, 1
 OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP = 0, 1, 2, 3, 4
 
-EXPORTS = ("kvs_deviation", "kvs_select_topk", "kvs_select_topk_static", "kvs_scatter_kv", "kvs_partial_attention",
+EXPORTS = ("kvs_deviation", "kvs_deviation_topk", "kvs_select_topk", "kvs_select_topk_static", "kvs_scatter_kv", "kvs_partial_attention",
            "kvs_decode_check", "kvs_attn_colsum", "kvs_workspace_size", "kvs_strerror", "kvs_last_error", "kvs_version")
 
 
@@ -53,6 +53,7 @@ def load(build_if_missing: bool = True) -> ctypes.CDLL:
     vp, i32, i64, f32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float, ctypes.c_size_t
     sp = ctypes.POINTER(Shape)
     lib.kvs_deviation.argtypes = [sp, i64, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp]
+    lib.kvs_deviation_topk.argtypes = [sp, i64, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, i32, vp, vp, sz, vp]
     lib.kvs_select_topk.argtypes = [vp, i32, vp, vp, vp, vp, sz, vp]
     lib.kvs_select_topk_static.argtypes = [vp, i32, vp, vp, vp, vp]
     lib.kvs_scatter_kv.argtypes = [sp, i64, vp, vp, vp, i64, vp, vp, vp, vp, vp]
@@ -60,7 +61,7 @@ def load(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.kvs_decode_check.argtypes = [sp, i32, i64, vp, vp, vp, vp, vp, vp, vp, f32, vp, vp, vp, vp, vp, sz, vp]
     lib.kvs_attn_colsum.argtypes = [sp, i64, vp, vp, f32, vp, vp, sz, vp]
     lib.kvs_workspace_size.argtypes = [ctypes.c_char_p, sp, i32, i64, i64]
-    for n in ("kvs_deviation", "kvs_select_topk", "kvs_select_topk_static", "kvs_scatter_kv", "kvs_partial_attention",
+    for n in ("kvs_deviation", "kvs_deviation_topk", "kvs_select_topk", "kvs_select_topk_static", "kvs_scatter_kv", "kvs_partial_attention",
               "kvs_decode_check", "kvs_attn_colsum"):
         getattr(lib, n).restype = ctypes.c_int
     lib.kvs_workspace_size.restype = sz
@@ -129,6 +130,17 @@ def kvs_deviation(shape: Shape, n_tokens: int, k_fresh, v_fresh, k_cache, v_cach
                               _ptr(dev_k, torch.float32), _ptr(dev_v, torch.float32),
                               _ptr(score, torch.float32), _stream(stream))
     _check(rc, "kvs_deviation")
+
+
+def kvs_deviation_topk(shape: Shape, n_tokens: int, k_fresh, v_fresh, k_cache, v_cache, reused, alpha,
+                       mode: int, dev_k, dev_v, score, k: int, idx_out, workspace=None, stream=None) -> None:
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    rc = load().kvs_deviation_topk(ctypes.byref(shape), n_tokens, _ptr(k_fresh), _ptr(v_fresh), _ptr(k_cache),
+                                   _ptr(v_cache), _ptr(reused, torch.uint8), _ptr(alpha, torch.float32), mode,
+                                   _ptr(dev_k, torch.float32), _ptr(dev_v, torch.float32),
+                                   _ptr(score, torch.float32), k, _ptr(idx_out, torch.int32), _ptr(workspace),
+                                   ws_bytes, _stream(stream))
+    _check(rc, "kvs_deviation_topk")
 
 
 def kvs_select_topk(scores, row_off: Sequence[int], k_row: Sequence[int], idx_out,

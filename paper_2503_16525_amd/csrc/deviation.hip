@@ -50,13 +50,17 @@ __device__ __forceinline__ float group_sum(float v)
 __device__ __forceinline__ uint4 stream_load(const uint4 *p) { return stream_load16(p); }
 
 // One workgroup = kDevTok consecutive tokens = kDevTok * n_kv_heads cells.
-template <int DTYPE, int LPH, bool HAS_K, int UNROLL>
+// HIST (kvs_deviation_topk): every token's order-preserving key is stored beside its score and
+// counted into the histogram of the keys' leading bits (finite scores only), which the selecting
+// kernel consumes.
+template <int DTYPE, int LPH, bool HAS_K, int UNROLL, bool HIST>
 __global__ __launch_bounds__(kDevThreads) void deviation_kernel(
     int64_t n_tokens, int n_kv_heads,
     const uint4 *__restrict__ k_fresh, const uint4 *__restrict__ v_fresh,
     const uint4 *__restrict__ k_cache, const uint4 *__restrict__ v_cache,
     const uint8_t *__restrict__ reused, const float *__restrict__ alpha, int mode_kv,
-    float *__restrict__ dev_k, float *__restrict__ dev_v, float *__restrict__ score)
+    float *__restrict__ dev_k, float *__restrict__ dev_v, float *__restrict__ score,
+    uint32_t *__restrict__ keys_out, uint32_t *__restrict__ key_hist)
 {
     extern __shared__ float lds[]; // dv[n_kv_heads][kDevTok], then dk[n_kv_heads][kDevTok]
     float *dv_s = lds;
@@ -114,7 +118,7 @@ __global__ __launch_bounds__(kDevThreads) void deviation_kernel(
             if (HAS_K && dev_k) dev_k[o] = dk_s[e];
         }
     }
-    if (score && tid < tile_tok) {
+    if ((score || HIST) && tid < tile_tok) {
         const int64_t i = tok0 + tid;
         float s = 0.f;
         for (int g = 0; g < n_kv_heads; ++g) {
@@ -124,28 +128,68 @@ __global__ __launch_bounds__(kDevThreads) void deviation_kernel(
             s += a * dev;
         }
         const bool cand = reused ? (reused[i] != 0) : true;
-        score[i] = cand ? s : -INFINITY;
+        const float sc = cand ? s : -INFINITY;
+        if (score) score[i] = sc;
+        if (HIST) {
+            const uint32_t key = score_key(sc);
+            keys_out[i] = key;
+            // integer counts: the histogram does not depend on the order in which the atomics land
+            if (sc != -INFINITY)
+                __hip_atomic_fetch_add(key_hist + (blockIdx.x % kKeyHistCopies) * kKeyHistBins + key_hist_slot(key >> kKeyHistShift), 1u,
+                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
     }
 }
 
 template <int DTYPE, int LPH>
 kvs_status launch(int64_t n, int hk, bool has_k, const void *kf, const void *vf, const void *kc,
                   const void *vc, const uint8_t *reused, const float *alpha, int mode_kv,
-                  float *dev_k, float *dev_v, float *score, hipStream_t st)
+                  float *dev_k, float *dev_v, float *score, const FusedScratch *fs, hipStream_t st)
 {
     const int64_t blocks = (n + kDevTok - 1) / kDevTok;
     if (blocks > 0x7fffffff) return fail(KVS_EINVAL, "kvs_deviation: too many tokens");
     const size_t lds = sizeof(float) * hk * kDevTok * 2;
     dim3 grid((unsigned)blocks), block(kDevThreads);
-    if (has_k)
-        hipLaunchKernelGGL((deviation_kernel<DTYPE, LPH, true, 2>), grid, block, lds, st, n, hk,
-                           (const uint4 *)kf, (const uint4 *)vf, (const uint4 *)kc, (const uint4 *)vc,
-                           reused, alpha, mode_kv, dev_k, dev_v, score);
-    else
-        hipLaunchKernelGGL((deviation_kernel<DTYPE, LPH, false, 4>), grid, block, lds, st, n, hk,
-                           (const uint4 *)nullptr, (const uint4 *)vf, (const uint4 *)nullptr,
-                           (const uint4 *)vc, reused, alpha, mode_kv, dev_k, dev_v, score);
+#define KVS_DEV_LAUNCH(HASK, UNR, HIST)                                                                          \
+    hipLaunchKernelGGL((deviation_kernel<DTYPE, LPH, HASK, UNR, HIST>), grid, block, lds, st, n, hk,             \
+                       (const uint4 *)kf, (const uint4 *)vf, (const uint4 *)kc, (const uint4 *)vc, reused, alpha, \
+                       mode_kv, dev_k, dev_v, score, fs ? fs->keys : nullptr, fs ? fs->hist : nullptr)
+    if (has_k) { if (fs) KVS_DEV_LAUNCH(true, 2, true); else KVS_DEV_LAUNCH(true, 2, false); }
+    else { if (fs) KVS_DEV_LAUNCH(false, 4, true); else KVS_DEV_LAUNCH(false, 4, false); }
+#undef KVS_DEV_LAUNCH
     return check_launch("kvs_deviation");
+}
+
+kvs_status deviation_call(const char *who, const kvs_shape *shape, int64_t n_tokens,
+                          const void *k_fresh, const void *v_fresh, const void *k_cache, const void *v_cache,
+                          const uint8_t *reused, const float *alpha, int32_t mode,
+                          float *dev_k, float *dev_v, float *score, const FusedScratch *fs, hipStream_t hs)
+{
+    kvs_status st = check_shape(shape);
+    if (st != KVS_OK) return st;
+    if (n_tokens < 0) return fail(KVS_EINVAL, "%s: n_tokens < 0", who);
+    if (mode != KVS_SCORE_V && mode != KVS_SCORE_KV) return fail(KVS_EINVAL, "%s: bad mode %d", who, mode);
+    if (n_tokens == 0) return KVS_OK;
+    if (!v_fresh || !v_cache) return fail(KVS_EINVAL, "%s: v_fresh/v_cache is NULL", who);
+    const bool has_k = (mode == KVS_SCORE_KV) || dev_k != nullptr;
+    if (has_k && (!k_fresh || !k_cache)) return fail(KVS_EINVAL, "%s: k_fresh/k_cache is NULL but the key deviation is needed", who);
+    if (!aligned16(v_fresh) || !aligned16(v_cache) || (has_k && (!aligned16(k_fresh) || !aligned16(k_cache))))
+        return fail(KVS_EINVAL, "%s: K/V pointers must be 16-byte aligned", who);
+    if (shape->n_kv_heads > 64) return fail(KVS_EUNSUPPORTED, "%s: more than 64 kv heads", who);
+    const int lph = (int)(shape->head_dim * elem_bytes(shape->dtype) / 16);
+    const int mkv = mode == KVS_SCORE_KV;
+    const int hk = shape->n_kv_heads;
+#define KVS_DEV_CASE(DT, L) \
+    return launch<DT, L>(n_tokens, hk, has_k, k_fresh, v_fresh, k_cache, v_cache, reused, alpha, mkv, dev_k, dev_v, score, fs, hs)
+    if (shape->dtype == KVS_BF16) {
+        if (lph == 8) KVS_DEV_CASE(KVS_BF16, 8);
+        if (lph == 16) KVS_DEV_CASE(KVS_BF16, 16);
+    } else {
+        if (lph == 16) KVS_DEV_CASE(KVS_F32, 16);
+        if (lph == 32) KVS_DEV_CASE(KVS_F32, 32);
+    }
+#undef KVS_DEV_CASE
+    return fail(KVS_EUNSUPPORTED, "%s: head_dim %d with dtype %d", who, shape->head_dim, shape->dtype);
 }
 
 } // namespace
@@ -157,31 +201,39 @@ extern "C" kvs_status kvs_deviation(const kvs_shape *shape, int64_t n_tokens,
                                     const uint8_t *reused, const float *alpha, int32_t mode,
                                     float *dev_k, float *dev_v, float *score, void *stream)
 {
+    return kvs::deviation_call("kvs_deviation", shape, n_tokens, k_fresh, v_fresh, k_cache, v_cache, reused, alpha, mode,
+                               dev_k, dev_v, score, nullptr, (hipStream_t)stream);
+}
+
+extern "C" kvs_status kvs_deviation_topk(const kvs_shape *shape, int64_t n_tokens,
+                                         const void *k_fresh, const void *v_fresh,
+                                         const void *k_cache, const void *v_cache,
+                                         const uint8_t *reused, const float *alpha, int32_t mode,
+                                         float *dev_k, float *dev_v, float *score,
+                                         int32_t k, int32_t *idx_out,
+                                         void *workspace, size_t workspace_bytes, void *stream)
+{
     using namespace kvs;
-    kvs_status st = check_shape(shape);
-    if (st != KVS_OK) return st;
-    if (n_tokens < 0) return fail(KVS_EINVAL, "kvs_deviation: n_tokens < 0");
-    if (mode != KVS_SCORE_V && mode != KVS_SCORE_KV) return fail(KVS_EINVAL, "kvs_deviation: bad mode %d", mode);
-    if (n_tokens == 0) return KVS_OK;
-    if (!v_fresh || !v_cache) return fail(KVS_EINVAL, "kvs_deviation: v_fresh/v_cache is NULL");
-    const bool has_k = (mode == KVS_SCORE_KV) || dev_k != nullptr;
-    if (has_k && (!k_fresh || !k_cache)) return fail(KVS_EINVAL, "kvs_deviation: k_fresh/k_cache is NULL but the key deviation is needed");
-    if (!aligned16(v_fresh) || !aligned16(v_cache) || (has_k && (!aligned16(k_fresh) || !aligned16(k_cache))))
-        return fail(KVS_EINVAL, "kvs_deviation: K/V pointers must be 16-byte aligned");
-    if (shape->n_kv_heads > 64) return fail(KVS_EUNSUPPORTED, "kvs_deviation: more than 64 kv heads");
+    const char *who = "kvs_deviation_topk";
+    if (n_tokens < 0) return fail(KVS_EINVAL, "%s: n_tokens < 0", who);
+    if (k < 0 || k > n_tokens) return fail(KVS_EINVAL, "%s: k=%d outside [0,%lld]", who, k, (long long)n_tokens);
+    if (k > 0 && !idx_out) return fail(KVS_EINVAL, "%s: idx_out is NULL", who);
+    if (workspace && (reinterpret_cast<uintptr_t>(workspace) & 255u)) return fail(KVS_EINVAL, "%s: workspace must be 256-byte aligned", who);
     hipStream_t hs = (hipStream_t)stream;
-    const int lph = (int)(shape->head_dim * elem_bytes(shape->dtype) / 16);
-    const int mkv = mode == KVS_SCORE_KV;
-    const int hk = shape->n_kv_heads;
-#define KVS_DEV_CASE(DT, L) \
-    return launch<DT, L>(n_tokens, hk, has_k, k_fresh, v_fresh, k_cache, v_cache, reused, alpha, mkv, dev_k, dev_v, score, hs)
-    if (shape->dtype == KVS_BF16) {
-        if (lph == 8) KVS_DEV_CASE(KVS_BF16, 8);
-        if (lph == 16) KVS_DEV_CASE(KVS_BF16, 16);
-    } else {
-        if (lph == 16) KVS_DEV_CASE(KVS_F32, 16);
-        if (lph == 32) KVS_DEV_CASE(KVS_F32, 32);
+    if (k > 0 && n_tokens <= kFusedMaxTokens) {
+        // scores, keys and the key histogram in one pass; one more launch turns them into the list
+        FusedScratch fs;
+        kvs_status st = fused_scratch(&fs);
+        if (st != KVS_OK) return st;
+        st = deviation_call(who, shape, n_tokens, k_fresh, v_fresh, k_cache, v_cache, reused, alpha, mode, dev_k, dev_v, score, &fs, hs);
+        if (st != KVS_OK) return st;
+        return launch_select_from_hist(fs, (int32_t)n_tokens, k, idx_out, hs);
     }
-#undef KVS_DEV_CASE
-    return fail(KVS_EUNSUPPORTED, "kvs_deviation: head_dim %d with dtype %d", shape->head_dim, shape->dtype);
+    // longer rows (and k = 0): the two calls one after the other; the ranking needs the scores in memory
+    if (k > 0 && !score) return fail(KVS_EINVAL, "%s: rows above %d tokens need the score array", who, kFusedMaxTokens);
+    kvs_status st = deviation_call(who, shape, n_tokens, k_fresh, v_fresh, k_cache, v_cache, reused, alpha, mode, dev_k, dev_v, score, nullptr, hs);
+    if (st != KVS_OK || k == 0) return st;
+    if (n_tokens > 0x7fffffffLL) return fail(KVS_EINVAL, "%s: row longer than 2^31-1", who);
+    const int64_t begin = 0, len = n_tokens;
+    return launch_select(score, 1, &begin, &len, &k, idx_out, workspace, workspace_bytes, hs);
 }

@@ -58,7 +58,45 @@ size_t colsum_workspace_bytes(const kvs_shape *shape, int64_t n_tokens);
 kvs_status launch_colsum_valu(const kvs_shape *shape, int64_t n, const void *q, const void *k, float scale,
                               float *lse, float *alpha, hipStream_t st);
 
+// ---- deviation scoring and top-k in one call (kvs_deviation_topk) ----------------------------------
+// The scoring kernel leaves, beside the scores, every token's order-preserving key and a histogram
+// of the keys' leading kKeyHistBits bits (device-scope integer atomics: the counts do not depend
+// on the order in which they arrive); two short launches of one workgroup per 1024 keys then find
+// the k-th key from the histogram and write the index list.  Keys, histogram and the records the
+// two launches exchange live in device memory that belongs to the library.
+constexpr int kKeyHistBits = 13;
+constexpr int kKeyHistBins = 1 << kKeyHistBits;
+constexpr int kKeyHistShift = 32 - kKeyHistBits;
+constexpr int kFusedMaxParts = 256;              // selecting workgroups per row, 1024 keys each
+constexpr int kFusedMaxTokens = kFusedMaxParts * 1024;
+struct FusedScratch {
+    uint32_t *hist;   // [kKeyHistCopies][kKeyHistBins], all zero between calls (the selecting launch clears what it read)
+    uint32_t *keys;   // [kFusedMaxTokens]
+    void *mem;        // the whole scratch block (select.hip)
+};
+kvs_status fused_scratch(FusedScratch *out);
+// where the counter of leading-bits value `bin` lives in the histogram: neighbouring bins are kept
+// 64 counters (256 bytes) apart, which spreads the few dozen bins that one launch's scores fall
+// into over the memory channels.  Measured on the 32k layer, time of the scoring kernel: no
+// histogram 22.9 us; bins side by side 47 us; 64 bytes apart 29 us; 128 to 512 bytes apart 25.5 us;
+// 1 KiB apart 30 us; 2 KiB apart 33 us.  Several copies of the histogram (a scoring workgroup adding
+// to copy = its index mod the copies, so that fewer atomics meet at one address) were slower: 2
+// copies +5 us, 4 copies +16 us on the whole call.
+constexpr int kKeyHistCopies = 1;
+__host__ __device__ constexpr uint32_t key_hist_slot(uint32_t bin) { return ((bin & 127u) << 6) | (bin >> 7); }
+static_assert(kKeyHistBits == 13, "the slot map is written for 8192 bins");
+kvs_status launch_select_from_hist(const FusedScratch &fs, int32_t n, int32_t k, int32_t *idx_out, hipStream_t stream);
+
 constexpr int kWave = 64;
+
+// monotone map fp32 -> uint32 (larger score <=> larger key); -0 is first folded onto +0.  Real
+// scores never map below 2^22 (-inf maps to 0x007fffff; only NaN patterns go lower).
+__device__ __forceinline__ uint32_t score_key(float s)
+{
+    const uint32_t u = __builtin_bit_cast(uint32_t, s + 0.0f);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+constexpr uint32_t kKeyNegInf = 0x007fffffu;
 
 // ---- wavefront primitives (64 lanes) ------------------------------------------------------
 

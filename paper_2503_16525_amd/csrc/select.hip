@@ -46,13 +46,6 @@ struct SelectRows {
     int32_t k[kMaxRowsPerLaunch];
 };
 
-// monotone map fp32 -> uint32 (larger score <=> larger key); -0 is first folded onto +0
-__device__ __forceinline__ uint32_t score_key(float s)
-{
-    const uint32_t u = __float_as_uint(s + 0.0f);
-    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-}
-
 // inclusive prefix sum over the 64 lanes with DPP row shifts and row broadcasts (no LDS round trips)
 __device__ __forceinline__ int wave_incl_scan(int v)
 {
@@ -249,6 +242,310 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const float *__rest
             base_sel += __popcll(m_gt);
             base_eq += __popcll(m_eq);
         });
+    }
+}
+
+// ---- top-k of one row whose leading-digit histogram already exists -------------------------------------
+// kvs_deviation_topk: the scoring kernel has left the row's keys and the histogram of their leading
+// kKeyHistBits bits (finite scores only; -inf entries, the non-candidates, are not counted and rank
+// below everything that is).  One workgroup per 1024 keys and two launches finish the selection:
+//   candidates  every workgroup reads the threshold's bin d1 off the histogram (the same answer in
+//               each), counts its keys above that bin and copies its keys inside it, in index order,
+//               to its segment of a candidate list;
+//   write       every workgroup resolves the remaining 19 bits on the (few hundred) candidates of the
+//               whole row in two small LDS histograms (10 + 9 bits), counts what the parts before it
+//               contribute -- keys above the threshold, and keys equal to it, which are taken in
+//               index order while the quota lasts -- and writes its own selection at that offset.
+// The launch boundary is the only synchronisation between workgroups.  The histogram is stored with
+// neighbouring bins 1 KiB apart (scores share their leading bits: the atomics of one scoring launch
+// fall on a few dozen neighbouring bins, which would otherwise share a few cache lines -- measured,
+// that layout more than doubles the scoring kernel's time); the write launch clears it for the next
+// call.
+constexpr int kFuThreads = 256;
+constexpr int kFuWaves = kFuThreads / kWave;
+constexpr int kFuKpt = 4;                          // keys per lane: one 16-byte load
+constexpr int kFuPart = kFuThreads * kFuKpt;       // keys per workgroup
+constexpr int kFuBinsPerThread = kKeyHistBins / kFuThreads;   // 32
+constexpr int kCandCap = 4096;                     // candidates kept in LDS by the write launch
+
+// Every thread holds the count `mine` of the bins it owns (bins ascending with the thread index).
+// The thread whose bins hold the remaining-th entry counted from the top calls resolve(rank from
+// the top inside its bins); returns the total over the workgroup.  Every thread must call this.
+template <typename F>
+__device__ __forceinline__ int fu_owner_from_top(int mine, int remaining, int *wave_tot, F resolve)
+{
+    const uint32_t tid = threadIdx.x, lane = tid & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
+    const int incl = wave_incl_scan(mine);
+    const int wtot = __builtin_amdgcn_readlane(incl, kWave - 1);
+    if (lane == 0) wave_tot[wave] = wtot;
+    __syncthreads();
+    int above = wtot - incl, total = 0;
+#pragma unroll
+    for (int w = 0; w < kFuWaves; ++w) {
+        const int t = wave_tot[w];
+        total += t;
+        if (w > wave) above += t;
+    }
+    if (above < remaining && remaining <= above + mine) resolve(remaining - above);
+    __syncthreads();
+    return total;
+}
+
+// this lane's four keys of part `part`: elements part * kFuPart + 4 * tid + j; slots past the row carry
+// key 0, below every real key
+__device__ __forceinline__ void fu_load_keys(const uint32_t *__restrict__ keys, int n, int part, uint32_t (&key)[kFuKpt])
+{
+    const int e = part * kFuPart + kFuKpt * (int)threadIdx.x;
+    if (e + kFuKpt <= n) {
+        const uint4 v = *reinterpret_cast<const uint4 *>(keys + e);
+        key[0] = v.x; key[1] = v.y; key[2] = v.z; key[3] = v.w;
+    } else {
+#pragma unroll
+        for (int j = 0; j < kFuKpt; ++j) key[j] = e + j < n ? keys[e + j] : 0u;
+    }
+}
+
+struct FusedRow {          // what the candidates launch leaves for the write launch
+    int d1;                // leading bits of the threshold key; -1: fewer finite scores than k
+    int rank;              // the threshold is the rank-th key of bin d1 from the top (d1 < 0: -inf entries to take)
+};
+
+__global__ __launch_bounds__(kFuThreads) void fused_cand_kernel(const uint32_t *__restrict__ keys, const uint32_t *__restrict__ hist,
+                                                                int n, int k, uint32_t *__restrict__ cand,
+                                                                int2 *__restrict__ part_rec /* (candidates, keys above d1) */,
+                                                                FusedRow *__restrict__ row_rec)
+{
+    __shared__ int wave_tot[kFuWaves], wave_tot2[kFuWaves], bcast[2], found[2], range_tot[kFuThreads];
+    const int part = blockIdx.x;
+    const uint32_t tid = threadIdx.x, lane = tid & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
+    uint32_t key[kFuKpt];
+    fu_load_keys(keys, n, part, key);
+    // Thread (wave w, lane l) owns the 32 bins of range rho = 4 l + w, bins 32 rho .. 32 rho + 31: bin
+    // 32 rho + i sits at (32 w + i) * 64 + l, so every load below is one coalesced 256-byte row per wave.
+    static_assert(kFuBinsPerThread == 32 && kFuWaves == 4, "matches key_hist_slot");
+    const int rho = 4 * (int)lane + wave;
+    int c[kFuBinsPerThread], quad[kFuBinsPerThread / 4], mine = 0;
+#pragma unroll
+    for (int i = 0; i < kFuBinsPerThread; ++i) {
+        c[i] = 0;
+#pragma unroll
+        for (int r = 0; r < kKeyHistCopies; ++r) c[i] += (int)hist[r * kKeyHistBins + (32 * wave + i) * 64 + (int)lane];
+    }
+#pragma unroll
+    for (int q = 0; q < kFuBinsPerThread / 4; ++q) {
+        quad[q] = (c[4 * q] + c[4 * q + 1]) + (c[4 * q + 2] + c[4 * q + 3]);
+        mine += quad[q];
+    }
+    // the scan runs over the ranges in bin order: thread t takes range t's total
+    range_tot[rho] = mine;
+    if (tid < 2) { bcast[tid] = -1; found[tid] = -1; }
+    __syncthreads();
+    const int n_finite = fu_owner_from_top(range_tot[tid], k, wave_tot, [&](int rank) { bcast[0] = (int)tid; bcast[1] = rank; });
+    if (bcast[0] == rho) {
+        // this thread holds the counts of the range the threshold falls into: from the top, first the
+        // group of four bins, then the bin inside it
+        int rank = bcast[1];
+        int q = kFuBinsPerThread / 4 - 1;
+#pragma unroll
+        for (int i = kFuBinsPerThread / 4 - 1; i > 0; --i)
+            if (q == i && rank > quad[i]) { rank -= quad[i]; q = i - 1; }
+        int c4[4] = {0, 0, 0, 0};
+#pragma unroll
+        for (int i = 0; i < kFuBinsPerThread / 4; ++i)
+            if (q == i) { c4[0] = c[4 * i]; c4[1] = c[4 * i + 1]; c4[2] = c[4 * i + 2]; c4[3] = c[4 * i + 3]; }
+        int b = 3;
+        if (rank > c4[3]) { rank -= c4[3]; b = 2; if (rank > c4[2]) { rank -= c4[2]; b = 1; if (rank > c4[1]) { rank -= c4[1]; b = 0; } } }
+        found[0] = rho * kFuBinsPerThread + 4 * q + b;
+        found[1] = rank;
+    }
+    __syncthreads();
+    const int d1 = found[0];
+    // this part's keys above the threshold's bin, and those inside it (index order kept)
+    int n_above = 0, n_in = 0;
+    bool in[kFuKpt];
+#pragma unroll
+    for (int j = 0; j < kFuKpt; ++j) {
+        const int bin = (int)(key[j] >> kKeyHistShift);
+        // without a threshold bin every finite score is taken: "above" then means finite
+        n_above += d1 >= 0 ? (bin > d1) : (key[j] > kKeyNegInf);
+        in[j] = d1 >= 0 && bin == d1;
+        n_in += in[j];
+    }
+    const int incl = wave_incl_scan(n_in);
+    const int wtot = __builtin_amdgcn_readlane(incl, kWave - 1);
+    n_above = wave_sum_i32(n_above);
+    if (lane == 0) { wave_tot[wave] = wtot; wave_tot2[wave] = n_above; }
+    __syncthreads();
+    int at = incl - n_in, total_in = 0, total_above = 0;
+#pragma unroll
+    for (int w = 0; w < kFuWaves; ++w) {
+        if (w < wave) at += wave_tot[w];
+        total_in += wave_tot[w];
+        total_above += wave_tot2[w];
+    }
+    uint32_t *__restrict__ seg = cand + (size_t)part * kFuPart;
+#pragma unroll
+    for (int j = 0; j < kFuKpt; ++j)
+        if (in[j]) seg[at++] = key[j];
+    if (tid == 0) {
+        part_rec[part] = make_int2(total_in, total_above);
+        if (part == 0) *row_rec = FusedRow{d1, d1 >= 0 ? found[1] : k - n_finite};
+    }
+}
+
+__global__ __launch_bounds__(kFuThreads) void fused_write_kernel(const uint32_t *__restrict__ keys, uint32_t *__restrict__ hist,
+                                                                 int n, int k, int n_parts, const uint32_t *__restrict__ cand,
+                                                                 const int2 *__restrict__ part_rec, const FusedRow *__restrict__ row_rec,
+                                                                 int32_t *__restrict__ out)
+{
+    __shared__ __align__(16) int h2[1024], h3[512];
+    __shared__ uint32_t list[kCandCap];
+    __shared__ int cand_begin[kFusedMaxParts + 1];     // candidates of the parts before q
+    __shared__ int above_begin[kFusedMaxParts + 1];    // keys above the threshold's bin in the parts before q
+    __shared__ int wave_tot[kFuWaves], wave_tot2[kFuWaves], bcast[2];
+    const int part = blockIdx.x;
+    const uint32_t tid = threadIdx.x, lane = tid & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
+    uint32_t key[kFuKpt];
+    fu_load_keys(keys, n, part, key);
+    const FusedRow row = *row_rec;
+    // Rows of up to kSpecParts parts fetch the first kSpec candidates of every part right away, together
+    // with the records that say how many there are: when no part has more (a few hundred candidates
+    // spread over the row) the list is complete without a second, dependent trip to memory.
+    constexpr int kSpec = 32, kSpecParts = 32, kSpecPerThread = kSpec * kSpecParts / kFuThreads;
+    const bool speculate = n_parts <= kSpecParts;       // uniform
+    uint32_t spec[kSpecPerThread];
+    if (speculate) {
+#pragma unroll
+        for (int r = 0; r < kSpecPerThread; ++r) {
+            const int flat = (int)tid + r * kFuThreads, q = flat / kSpec, i = flat % kSpec;
+            spec[r] = q < n_parts ? cand[(size_t)q * kFuPart + i] : 0u;
+        }
+    }
+    // the histogram has been read by every workgroup of the launch before: clear it for the next call
+    if (part == 0)
+        for (int i = tid; i < kKeyHistCopies * kKeyHistBins; i += kFuThreads) hist[i] = 0u;
+    // prefix sums over the parts (thread q holds part q; n_parts <= kFuThreads)
+    {
+        const int2 rec = (int)tid < n_parts ? part_rec[tid] : make_int2(0, 0);
+        const int ic = wave_incl_scan(rec.x), ia = wave_incl_scan(rec.y);
+        if (lane == kWave - 1) { wave_tot[wave] = ic; wave_tot2[wave] = ia; }
+        if (tid == 0) { cand_begin[0] = 0; above_begin[0] = 0; bcast[0] = 0; bcast[1] = 0; }
+        __syncthreads();
+        int bc = 0, ba = 0;
+        for (int w = 0; w < wave; ++w) { bc += wave_tot[w]; ba += wave_tot2[w]; }
+        if ((int)tid < n_parts) { cand_begin[tid + 1] = bc + ic; above_begin[tid + 1] = ba + ia; }
+        if (rec.x > kSpec) bcast[1] = 1;                // a part with more candidates than were fetched ahead (any writer)
+        for (int i = tid; i < 1024; i += kFuThreads) h2[i] = 0;
+        for (int i = tid; i < 512; i += kFuThreads) h3[i] = 0;
+        __syncthreads();
+    }
+    const int n_cand = cand_begin[n_parts];
+    const bool listed = n_cand <= kCandCap;            // uniform
+    const bool spec_ok = bcast[1] == 0;                // uniform
+    // candidate f of the row, in index order: entry f - cand_begin[q] of part q's segment
+    auto fetch = [&](int f) -> uint32_t {
+        int lo = 0, hi = n_parts;                       // largest q with cand_begin[q] <= f
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (cand_begin[mid] <= f) lo = mid; else hi = mid;
+        }
+        return cand[(size_t)lo * kFuPart + (f - cand_begin[lo])];
+    };
+    if (listed) {
+        if (speculate && spec_ok) {
+#pragma unroll
+            for (int r = 0; r < kSpecPerThread; ++r) {
+                const int flat = (int)tid + r * kFuThreads, q = flat / kSpec, i = flat % kSpec;
+                if (q < n_parts && i < cand_begin[q + 1] - cand_begin[q]) list[cand_begin[q] + i] = spec[r];
+            }
+        } else {
+            for (int f = tid; f < n_cand; f += kFuThreads) list[f] = fetch(f);
+        }
+        __syncthreads();
+    }
+    // g(key) over the candidates [0, upto) of the row
+    auto for_cands = [&](int upto, auto g) {
+        for (int f = tid; f < upto; f += kFuThreads) g(listed ? list[f] : fetch(f));
+    };
+    uint32_t T;
+    int quota_eq;
+    if (row.d1 < 0) {
+        T = kKeyNegInf;                                 // every finite score, then -inf entries, lowest indices first
+        quota_eq = row.rank;
+    } else {
+        int remaining = row.rank;
+        for_cands(n_cand, [&](uint32_t kk) { atomicAdd(&h2[(kk >> 9) & 1023u], 1); });
+        if (tid < 2) bcast[tid] = 0;                    // (stays defined if NaN scores leave a digit without an owner)
+        __syncthreads();
+        {
+            const int4 b = *reinterpret_cast<const int4 *>(&h2[4 * tid]);
+            fu_owner_from_top(b.x + b.y + b.z + b.w, remaining, wave_tot, [&](int rank) {
+                int bin = 3;
+                if (rank > b.w) { rank -= b.w; bin = 2; if (rank > b.z) { rank -= b.z; bin = 1; if (rank > b.y) { rank -= b.y; bin = 0; } } }
+                bcast[0] = 4 * (int)tid + bin;
+                bcast[1] = rank;
+            });
+        }
+        const uint32_t d2 = (uint32_t)bcast[0];
+        remaining = bcast[1];
+        __syncthreads();
+        for_cands(n_cand, [&](uint32_t kk) { if (((kk >> 9) & 1023u) == d2) atomicAdd(&h3[kk & 511u], 1); });
+        if (tid < 2) bcast[tid] = 0;
+        __syncthreads();
+        {
+            const int2 b = *reinterpret_cast<const int2 *>(&h3[2 * tid]);
+            fu_owner_from_top(b.x + b.y, remaining, wave_tot, [&](int rank) {
+                int bin = 1;
+                if (rank > b.y) { rank -= b.y; bin = 0; }
+                bcast[0] = 2 * (int)tid + bin;
+                bcast[1] = rank;
+            });
+        }
+        T = ((uint32_t)row.d1 << kKeyHistShift) | (d2 << 9) | (uint32_t)bcast[0];
+        quota_eq = bcast[1];
+    }
+    if (T == 0u) T = 1u;                                // only reachable with NaN scores: never select padding
+    quota_eq = max(quota_eq, 0);
+
+    // what the parts before this one contribute
+    int gt_before, eq_before;
+    if (row.d1 < 0) {
+        gt_before = above_begin[part];                  // their finite scores
+        eq_before = part * kFuPart - gt_before;         // and their -inf entries (earlier parts are full)
+    } else {
+        int g = 0, e = 0;
+        for_cands(cand_begin[part], [&](uint32_t kk) { g += kk > T; e += kk == T; });
+        g = wave_sum_i32(g);
+        e = wave_sum_i32(e);
+        if (lane == 0) { wave_tot[wave] = g; wave_tot2[wave] = e; }
+        __syncthreads();
+        gt_before = above_begin[part];
+        eq_before = 0;
+#pragma unroll
+        for (int w = 0; w < kFuWaves; ++w) { gt_before += wave_tot[w]; eq_before += wave_tot2[w]; }
+        __syncthreads();
+    }
+    // ---- ordered write of this part: { key > T } and the entries equal to T while the quota lasts ----
+    int n_gt = 0, n_eq = 0;
+#pragma unroll
+    for (int j = 0; j < kFuKpt; ++j) { n_gt += key[j] > T; n_eq += key[j] == T; }
+    const int ig = wave_incl_scan(n_gt), ie = wave_incl_scan(n_eq);
+    if (lane == kWave - 1) { wave_tot[wave] = ig; wave_tot2[wave] = ie; }
+    __syncthreads();
+    uint32_t gt = (uint32_t)(gt_before + ig - n_gt), eq = (uint32_t)(eq_before + ie - n_eq);
+    for (int w = 0; w < wave; ++w) { gt += wave_tot[w]; eq += wave_tot2[w]; }
+    const int32_t e0 = part * kFuPart + kFuKpt * (int)tid;
+#pragma unroll
+    for (int j = 0; j < kFuKpt; ++j) {
+        const bool is_gt = key[j] > T, is_eq = key[j] == T;
+        const uint32_t slot = gt + min(eq, (uint32_t)quota_eq);
+        // (with well-formed scores every slot is below k; the guard keeps NaN rows inside the output)
+        if ((is_gt || (is_eq && eq < (uint32_t)quota_eq)) && slot < (uint32_t)k) out[slot] = e0 + j;
+        gt += is_gt;
+        eq += is_eq;
     }
 }
 
@@ -655,6 +952,53 @@ kvs_status static_scratch(void **out)
     return KVS_OK;
 }
 
+// ---- the scratch of kvs_deviation_topk: key histogram (zero when the library is loaded, and left
+// zero by every selecting launch), the row's keys, the candidate segments and the per-part records ----
+struct FusedDeviceScratch {
+    uint32_t hist[kKeyHistCopies * kKeyHistBins];
+    uint32_t keys[kFusedMaxTokens];
+    uint32_t cand[kFusedMaxTokens];
+    int2 part_rec[kFusedMaxParts];
+    FusedRow row_rec;
+};
+static __device__ __align__(256) FusedDeviceScratch fused_mem;
+std::atomic<FusedDeviceScratch *> g_fused_mem[kMaxDevices];
+
+} // namespace
+
+kvs_status fused_scratch(FusedScratch *out)
+{
+    const int dev = current_device();
+    if (dev < 0 || dev >= kMaxDevices) return fail(KVS_EHIP, "kvs_deviation_topk: no current device, or more than %d devices", kMaxDevices);
+    FusedDeviceScratch *m = g_fused_mem[dev].load(std::memory_order_acquire);
+    if (!m) {
+        void *p = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(fused_mem));
+        if (e != hipSuccess || !p) return fail(KVS_EHIP, "kvs_deviation_topk: hipGetSymbolAddress: %s", hipGetErrorString(e));
+        m = (FusedDeviceScratch *)p;
+        g_fused_mem[dev].store(m, std::memory_order_release);
+    }
+    out->hist = m->hist;
+    out->keys = m->keys;
+    out->mem = m;
+    return KVS_OK;
+}
+
+kvs_status launch_select_from_hist(const FusedScratch &fs, int32_t n, int32_t k, int32_t *idx_out, hipStream_t hs)
+{
+    if (n > kFusedMaxTokens) return fail(KVS_EINVAL, "kvs_deviation_topk: %d tokens are more than the library's key scratch holds", n);
+    FusedDeviceScratch *m = (FusedDeviceScratch *)fs.mem;
+    const int parts = (n + kFuPart - 1) / kFuPart;
+    static_assert(kFusedMaxParts <= kFuThreads && kFusedMaxParts * kFuPart == kFusedMaxTokens, "one thread per part in the prefix sums");
+    hipLaunchKernelGGL(fused_cand_kernel, dim3(parts), dim3(kFuThreads), 0, hs, m->keys, m->hist, n, k, m->cand, m->part_rec, &m->row_rec);
+    kvs_status st = check_launch("kvs_deviation_topk(candidates)");
+    if (st != KVS_OK) return st;
+    hipLaunchKernelGGL(fused_write_kernel, dim3(parts), dim3(kFuThreads), 0, hs, m->keys, m->hist, n, k, parts, m->cand, m->part_rec,
+                       &m->row_rec, idx_out);
+    return check_launch("kvs_deviation_topk(write)");
+}
+
+namespace {
 } // namespace
 } // namespace kvs
 
