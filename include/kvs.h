@@ -97,11 +97,12 @@ KVS_API kvs_status kvs_deviation(const kvs_shape *shape, int64_t n_tokens,
  * to the two separate calls).  All arguments up to `score` are those of kvs_deviation.
  *
  * k        0 <= k <= n_tokens           idx_out [dev] int32[k]
- * score    [dev] fp32[n_tokens]; may be NULL for rows of at most 262144 tokens
- * workspace [dev] optional, as for kvs_select_topk: only used by rows above 262144 tokens, which
- *          run as the two separate calls
+ * score    [dev] fp32[n_tokens]; may be NULL only for rows of 12289 to 262144 tokens (outside that
+ *          range the ranking reads the scores back from it)
+ * workspace [dev] optional, as for kvs_select_topk: only used by rows above 262144 tokens
  *
- * Rows of at most 262144 tokens take three launches: the scoring kernel also stores every token's
+ * Rows of up to 12288 tokens (one workgroup ranks them as fast) and above 262144 run as the two
+ * separate calls.  Rows in between take three launches: the scoring kernel also stores every token's
  * order-preserving key and counts the keys' leading 13 bits into a histogram (integer atomics, so
  * the counts do not depend on arrival order and the result stays deterministic); then, with one
  * workgroup per 1024 keys, a launch that reads the threshold's bin off the histogram and sets the

@@ -220,7 +220,8 @@ extern "C" kvs_status kvs_deviation_topk(const kvs_shape *shape, int64_t n_token
     if (k > 0 && !idx_out) return fail(KVS_EINVAL, "%s: idx_out is NULL", who);
     if (workspace && (reinterpret_cast<uintptr_t>(workspace) & 255u)) return fail(KVS_EINVAL, "%s: workspace must be 256-byte aligned", who);
     hipStream_t hs = (hipStream_t)stream;
-    if (k > 0 && n_tokens <= kFusedMaxTokens) {
+    // (short rows: one workgroup ranks 8k scores in the time the two selecting launches take)
+    if (k > 0 && n_tokens > kFusedMinTokens && n_tokens <= kFusedMaxTokens) {
         // scores, keys and the key histogram in one pass; one more launch turns them into the list
         FusedScratch fs;
         kvs_status st = fused_scratch(&fs);
@@ -230,7 +231,7 @@ extern "C" kvs_status kvs_deviation_topk(const kvs_shape *shape, int64_t n_token
         return launch_select_from_hist(fs, (int32_t)n_tokens, k, idx_out, hs);
     }
     // longer rows (and k = 0): the two calls one after the other; the ranking needs the scores in memory
-    if (k > 0 && !score) return fail(KVS_EINVAL, "%s: rows above %d tokens need the score array", who, kFusedMaxTokens);
+    if (k > 0 && !score) return fail(KVS_EINVAL, "%s: rows of up to %d or above %d tokens need the score array", who, kFusedMinTokens, kFusedMaxTokens);
     kvs_status st = deviation_call(who, shape, n_tokens, k_fresh, v_fresh, k_cache, v_cache, reused, alpha, mode, dev_k, dev_v, score, nullptr, hs);
     if (st != KVS_OK || k == 0) return st;
     if (n_tokens > 0x7fffffffLL) return fail(KVS_EINVAL, "%s: row longer than 2^31-1", who);

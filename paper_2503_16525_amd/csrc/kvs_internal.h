@@ -69,6 +69,7 @@ constexpr int kKeyHistBins = 1 << kKeyHistBits;
 constexpr int kKeyHistShift = 32 - kKeyHistBits;
 constexpr int kFusedMaxParts = 256;              // selecting workgroups per row, 1024 keys each
 constexpr int kFusedMaxTokens = kFusedMaxParts * 1024;
+constexpr int kFusedMinTokens = 12 * 1024;       // up to here kvs_deviation_topk runs as the two separate calls
 struct FusedScratch {
     uint32_t *hist;   // [kKeyHistCopies][kKeyHistBins], all zero between calls (the selecting launch clears what it read)
     uint32_t *keys;   // [kFusedMaxTokens]

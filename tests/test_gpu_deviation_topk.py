@@ -58,6 +58,8 @@ CASES = [
     ("llama-63", synth.scaled(synth.LLAMA, 63, span_mean=8.0), 0.5),
     ("llama-1023", synth.scaled(synth.LLAMA, 1023, span_mean=64.0), 0.3),
     ("llama-1025", synth.scaled(synth.LLAMA, 1025, span_mean=64.0), 0.3),
+    ("llama-12288-two-calls", synth.scaled(synth.LLAMA, 12288), 0.3),
+    ("llama-12289", synth.scaled(synth.LLAMA, 12289), 0.3),
     ("llama-49153", synth.scaled(synth.LLAMA, 49153), 0.3),
     ("yi-131072", synth.YI, 0.10),
     ("one-head-262144", synth.scaled(synth.LLAMA, 262144, n_kv_heads=1, n_q_heads=1, head_dim=64), 0.1),
@@ -80,7 +82,7 @@ def test_deviation_topk_equals_the_two_calls(name, w, ratio):
     # weighted, key+value mode, and without the score output
     alpha = synth.synthetic_alpha(w)
     fused_and_separate(w, lay, k, alpha=alpha, mode=B.SCORE_KV)
-    fused_and_separate(w, lay, k, alpha=alpha, with_score=w.n_ctx > 262144)
+    fused_and_separate(w, lay, k, alpha=alpha, with_score=not (12288 < w.n_ctx <= 262144))
 
 
 def test_deviation_topk_ties_and_non_candidates():
@@ -112,7 +114,7 @@ def test_deviation_topk_ties_and_non_candidates():
 
 
 def test_deviation_topk_empty_and_zero_k():
-    w = synth.scaled(synth.LLAMA, 3000)
+    w = synth.scaled(synth.LLAMA, 13000)
     sh = B.shape_of(w)
     lay = synth.make_layer(w, with_q=False)
     g = {key: v.to(DEV) for key, v in lay.items()}
