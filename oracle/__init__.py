@@ -52,7 +52,8 @@ def lib() -> ctypes.CDLL:
     if _lib is None:
         _lib = ctypes.CDLL(build())
         for name in ("kvso_deviation", "kvso_alpha_prefill", "kvso_select_topk", "kvso_scatter_kv",
-                     "kvso_partial_attention", "kvso_decode_check", "kvso_max_threads"):
+                     "kvso_partial_attention", "kvso_decode_check", "kvso_first_order_impact", "kvso_exact_impact",
+                     "kvso_max_threads"):
             getattr(_lib, name).restype = ctypes.c_int
     return _lib
 
@@ -184,6 +185,37 @@ def partial_attention(q_sel, sel_pos, k_cache, v_cache, scale: float,
                                       _p(out), _p(lse))
     _check(rc, "partial_attention")
     return out, lse
+
+
+def first_order_impact(q, k_fresh, v_fresh, k_cache, v_cache, scale: float, reused=None):
+    """-> (impact_v, impact_k, impact_kv), float32 [N] each: the first-order movement of the attention
+    output that reusing token i causes, value direction, key direction and both (small N only)."""
+    qa = _as_np(q)
+    kf, vf, kc, vc = _as_np(k_fresh), _as_np(v_fresh), _as_np(k_cache), _as_np(v_cache)
+    n, hq, d = qa.shape
+    hk = kf.shape[1]
+    sh = _shape(hq, hk, d, _dtype_code(qa))
+    ru = _as_np(reused, np.uint8)
+    outs = [np.empty((n,), np.float32) for _ in range(3)]
+    rc = lib().kvso_first_order_impact(ctypes.byref(sh), ctypes.c_int64(n), _p(qa), _p(kf), _p(vf), _p(kc), _p(vc),
+                                       _p(ru), ctypes.c_double(scale), _p(outs[0]), _p(outs[1]), _p(outs[2]))
+    _check(rc, "first_order_impact")
+    return tuple(outs)
+
+
+def exact_impact(q, k_fresh, v_fresh, k_cache, v_cache, scale: float, reused=None) -> np.ndarray:
+    """-> float32 [N]: the true L1 change of the attention output when token i alone is reused (tiny N only)."""
+    qa = _as_np(q)
+    kf, vf, kc, vc = _as_np(k_fresh), _as_np(v_fresh), _as_np(k_cache), _as_np(v_cache)
+    n, hq, d = qa.shape
+    hk = kf.shape[1]
+    sh = _shape(hq, hk, d, _dtype_code(qa))
+    ru = _as_np(reused, np.uint8)
+    out = np.empty((n,), np.float32)
+    rc = lib().kvso_exact_impact(ctypes.byref(sh), ctypes.c_int64(n), _p(qa), _p(kf), _p(vf), _p(kc), _p(vc),
+                                 _p(ru), ctypes.c_double(scale), _p(out))
+    _check(rc, "exact_impact")
+    return out
 
 
 def decode_check(q_new, k_cache, dev_v, reused, scale: float, ctx_off, ctx_len, k_req,

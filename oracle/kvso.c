@@ -15,6 +15,11 @@
  *                          only the selected tokens are computed, the others' KV is reused)
  *   kvso_decode_check      Sec. 4.2: Alg. 1 with alpha taken from the decoding token's
  *                          current attention over the cache
+ *   kvso_first_order_impact Sec. 4.1, Eq. (2): the first-order expansion of the attention output's
+ *                          deviation, token by token, in the value direction, the key direction
+ *                          and both together
+ *   kvso_exact_impact      Sec. 4.1 / App. D.2 "ideal index": the true change of the attention
+ *                          output when one token's K/V alone is the reused one
  *
  * Arithmetic: inputs are converted exactly to double (bf16 and fp32 are both subsets of
  * double), every sum and product is carried in double in the natural index order, and a result
@@ -396,6 +401,162 @@ int kvso_decode_check(const kvso_shape *sh, int32_t batch, int64_t n_rows,
         if (rc) return rc;
         out_base += kk;
     }
+    return 0;
+}
+
+/* ---------------------------------------------------------------------------------------
+ * Full (fresh) causal attention of every row, helper of the two impact functions below:
+ * A[h][j][i] for i <= j (row softmax of scale * q[j,h] . k[i,g(h)]) and H[h][j][:] = sum_i A V.
+ * A is stored dense [hq][n][n] (zeros above the diagonal), so this is for small n only.
+ * ------------------------------------------------------------------------------------- */
+static int dense_attention(const kvso_shape *sh, int64_t n, const void *q, const void *k, const void *v,
+                           double scale, double *A, double *H)
+{
+    const int hq = sh->n_q_heads, hk = sh->n_kv_heads, d = sh->head_dim, dt = sh->dtype;
+    const int grp = hq / hk;
+#pragma omp parallel for collapse(2) schedule(dynamic, 4)
+    for (int h = 0; h < hq; ++h) {
+        for (int64_t j = 0; j < n; ++j) {
+            const int g = h / grp;
+            double *a = A + ((int64_t)h * n + j) * n;
+            double m = -INFINITY;
+            for (int64_t i = 0; i <= j; ++i) {
+                double acc = 0.0;
+                for (int c = 0; c < d; ++c) acc += ld(q, dt, (j * hq + h) * (int64_t)d + c) * ld(k, dt, (i * hk + g) * (int64_t)d + c);
+                a[i] = acc * scale;
+                if (a[i] > m) m = a[i];
+            }
+            double z = 0.0;
+            for (int64_t i = 0; i <= j; ++i) { a[i] = exp(a[i] - m); z += a[i]; }
+            for (int64_t i = 0; i <= j; ++i) a[i] /= z;
+            for (int64_t i = j + 1; i < n; ++i) a[i] = 0.0;
+            double *o = H + ((int64_t)h * n + j) * d;
+            for (int c = 0; c < d; ++c) o[c] = 0.0;
+            for (int64_t i = 0; i <= j; ++i)
+                for (int c = 0; c < d; ++c) o[c] += a[i] * ld(v, dt, (i * hk + g) * (int64_t)d + c);
+        }
+    }
+    return 0;
+}
+
+/* ---------------------------------------------------------------------------------------
+ * First-order impact of each reused token on the attention output (Sec. 4.1, Eq. (2)).
+ * H = A V is the correct attention (fresh K, V; causal); reusing token i's cache entry means
+ * K_i -> K_i + dK_i, V_i -> V_i + dV_i with dK = K_cache - K_fresh, dV = V_cache - V_fresh.
+ * To first order the output row j of query head h (KV head g) moves by
+ *     value direction   A[h,j,i] * dV[g,i]                                     (dH/dV = A)
+ *     key direction     A[h,j,i] * scale * (q[j,h] . dK[g,i]) * (V[g,i] - H[h,j])
+ * (the second line is the softmax Jacobian: d A[j,m] = A[j,m] (delta_mi - A[j,i]) d s[j,i],
+ * summed against V).  The impact of token i is the L1 norm of that movement over all rows j >= i,
+ * all query heads and all channels:
+ *     impact_v[i]  = sum_h sum_j | value term |_1   = sum_g alpha[g,i] * |dV[g,i]|_1   (Eq. (3))
+ *     impact_k[i]  = sum_h sum_j | key term |_1
+ *     impact_kv[i] = sum_h sum_j | value term + key term |_1
+ * Tokens with reused[i] == 0 get -inf in all three (reused == NULL: every token is rated).
+ * Each output is fp32 [n] and may be NULL.  O(n^2) memory: small n only.
+ * ------------------------------------------------------------------------------------- */
+int kvso_first_order_impact(const kvso_shape *sh, int64_t n, const void *q,
+                            const void *k_fresh, const void *v_fresh,
+                            const void *k_cache, const void *v_cache,
+                            const uint8_t *reused, double scale,
+                            float *impact_v, float *impact_k, float *impact_kv)
+{
+    if (!shape_ok(sh) || n < 0) return 1;
+    if (n == 0) return 0;
+    if (!q || !k_fresh || !v_fresh || !k_cache || !v_cache) return 1;
+    const int hq = sh->n_q_heads, hk = sh->n_kv_heads, d = sh->head_dim, dt = sh->dtype;
+    const int grp = hq / hk;
+    double *A = malloc(sizeof(double) * (size_t)hq * n * n);
+    double *H = malloc(sizeof(double) * (size_t)hq * n * d);
+    if (!A || !H) { free(A); free(H); return 1; }
+    dense_attention(sh, n, q, k_fresh, v_fresh, scale, A, H);
+#pragma omp parallel for schedule(dynamic, 4)
+    for (int64_t i = 0; i < n; ++i) {
+        double sv = 0.0, sk = 0.0, skv = 0.0;
+        for (int h = 0; h < hq; ++h) {
+            const int g = h / grp;
+            const int64_t cell = (i * hk + g) * (int64_t)d;
+            for (int64_t j = i; j < n; ++j) {
+                const double a = A[((int64_t)h * n + j) * n + i];
+                double ds = 0.0;
+                for (int c = 0; c < d; ++c)
+                    ds += ld(q, dt, (j * hq + h) * (int64_t)d + c) * (ld(k_cache, dt, cell + c) - ld(k_fresh, dt, cell + c));
+                ds *= scale;
+                const double *hj = H + ((int64_t)h * n + j) * d;
+                for (int c = 0; c < d; ++c) {
+                    const double dv = ld(v_cache, dt, cell + c) - ld(v_fresh, dt, cell + c);
+                    const double tv = a * dv;
+                    const double tk = a * ds * (ld(v_fresh, dt, cell + c) - hj[c]);
+                    sv += fabs(tv);
+                    sk += fabs(tk);
+                    skv += fabs(tv + tk);
+                }
+            }
+        }
+        const int cand = !reused || reused[i];
+        if (impact_v) impact_v[i] = cand ? (float)sv : -INFINITY;
+        if (impact_k) impact_k[i] = cand ? (float)sk : -INFINITY;
+        if (impact_kv) impact_kv[i] = cand ? (float)skv : -INFINITY;
+    }
+    free(A); free(H);
+    return 0;
+}
+
+/* ---------------------------------------------------------------------------------------
+ * Exact impact of each reused token (the "ideal index" of Sec. 4.1 / App. D.2): the attention
+ * is recomputed with token i's K and V taken from the cache and every other token fresh, and
+ *     impact[i] = sum_h sum_j | H_i'[h,j] - H[h,j] |_1
+ * is the true change of the output that reusing token i alone causes (no linearisation).
+ * Tokens with reused[i] == 0 get -inf.  O(n^3 d) time: tiny n only.
+ * ------------------------------------------------------------------------------------- */
+int kvso_exact_impact(const kvso_shape *sh, int64_t n, const void *q,
+                      const void *k_fresh, const void *v_fresh,
+                      const void *k_cache, const void *v_cache,
+                      const uint8_t *reused, double scale, float *impact)
+{
+    if (!shape_ok(sh) || n < 0) return 1;
+    if (n == 0) return 0;
+    if (!q || !k_fresh || !v_fresh || !k_cache || !v_cache || !impact) return 1;
+    const int hq = sh->n_q_heads, hk = sh->n_kv_heads, d = sh->head_dim, dt = sh->dtype;
+    const int grp = hq / hk;
+    double *A = malloc(sizeof(double) * (size_t)hq * n * n);
+    double *H = malloc(sizeof(double) * (size_t)hq * n * d);
+    if (!A || !H) { free(A); free(H); return 1; }
+    dense_attention(sh, n, q, k_fresh, v_fresh, scale, A, H);
+    free(A);
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t i = 0; i < n; ++i) {
+        if (reused && !reused[i]) { impact[i] = -INFINITY; continue; }
+        double total = 0.0;
+        double *logit = malloc(sizeof(double) * (size_t)n);
+        double *o = malloc(sizeof(double) * (size_t)d);
+        for (int h = 0; h < hq; ++h) {
+            const int g = h / grp;
+            for (int64_t j = i; j < n; ++j) {           /* rows before i do not see token i */
+                double m = -INFINITY;
+                for (int64_t t = 0; t <= j; ++t) {
+                    const void *kk = t == i ? k_cache : k_fresh;
+                    double acc = 0.0;
+                    for (int c = 0; c < d; ++c) acc += ld(q, dt, (j * hq + h) * (int64_t)d + c) * ld(kk, dt, (t * hk + g) * (int64_t)d + c);
+                    logit[t] = acc * scale;
+                    if (logit[t] > m) m = logit[t];
+                }
+                double z = 0.0;
+                for (int64_t t = 0; t <= j; ++t) { logit[t] = exp(logit[t] - m); z += logit[t]; }
+                for (int c = 0; c < d; ++c) o[c] = 0.0;
+                for (int64_t t = 0; t <= j; ++t) {
+                    const void *vv = t == i ? v_cache : v_fresh;
+                    const double wgt = logit[t] / z;
+                    for (int c = 0; c < d; ++c) o[c] += wgt * ld(vv, dt, (t * hk + g) * (int64_t)d + c);
+                }
+                const double *hj = H + ((int64_t)h * n + j) * d;
+                for (int c = 0; c < d; ++c) total += fabs(o[c] - hj[c]);
+            }
+        }
+        impact[i] = (float)total;
+        free(logit); free(o);
+    }
+    free(H);
     return 0;
 }
 
