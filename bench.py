@@ -512,6 +512,52 @@ def decode_first_step_flops() -> dict:
     return res
 
 
+def impact_config() -> dict:
+    """Beside the timed path: the full first-order impact (Sec. 4.1, Eq. (2), key and value direction)
+    on the Qwen-shaped 8k layer -- vector-unit work, n^2/2 * H_q * d channel terms -- and how far the
+    rankings by the key direction, the value direction and the plain deviation magnitude agree."""
+    w = synth.QWEN
+    sh = B.shape_of(w)
+    n, hk, hq, d = w.n_ctx, w.n_kv_heads, w.n_q_heads, w.head_dim
+    lay = synth.make_layer(w, device=DEV)
+    pos = torch.arange(n, dtype=torch.int32, device=DEV)
+    h = torch.empty((n, hq, d), dtype=torch.bfloat16, device=DEV)
+    lse = torch.empty((n, hq), device=DEV)
+    ws_a = torch.empty(B.kvs_workspace_size("partial_attention", sh, 1, n, n), dtype=torch.uint8, device=DEV)
+    B.kvs_partial_attention(sh, [0], [n], [0, n], lay["q"], pos, lay["k_fresh"], lay["v_fresh"], 1.0, h, lse, ws_a)
+    ws = torch.empty(B.kvs_workspace_size("first_order_impact", sh, 1, n), dtype=torch.uint8, device=DEV)
+    imp = [torch.empty((n,), device=DEV) for _ in range(3)]
+
+    def call():
+        B.kvs_first_order_impact(sh, n, lay["q"], lay["k_fresh"], lay["v_fresh"], lay["k_cache"], lay["v_cache"], h, lse,
+                                 lay["reused"], 1.0, imp[0], imp[1], imp[2], ws)
+    t, med = time_loop([call] * 2, reps=2)
+    # value direction = Eq. (3): the same numbers as kvs_deviation fed with kvs_attn_colsum's alpha
+    alpha = torch.empty((hk, n), device=DEV)
+    ws_cs = torch.empty(B.kvs_workspace_size("attn_colsum", sh, 1, n), dtype=torch.uint8, device=DEV)
+    B.kvs_attn_colsum(sh, n, lay["q"], lay["k_fresh"], 1.0, alpha, ws_cs)
+    score = torch.empty((n,), device=DEV)
+    mag = torch.empty((n,), device=DEV)
+    B.kvs_deviation(sh, n, None, lay["v_fresh"], None, lay["v_cache"], lay["reused"], alpha, B.SCORE_V, None, None, score)
+    B.kvs_deviation(sh, n, None, lay["v_fresh"], None, lay["v_cache"], lay["reused"], None, B.SCORE_V, None, None, mag)
+    cand = lay["reused"].bool()
+    rel = float(((imp[0][cand] - score[cand]).abs() / score[cand].abs().clamp_min(1e-20)).max())
+    k = synth.recompute_budget(int(cand.sum()), 0.10)
+    idx = torch.empty((k,), dtype=torch.int32, device=DEV)
+
+    def top(sc):
+        B.kvs_select_topk(sc.contiguous(), [0, n], [k], idx)
+        return set(idx.cpu().numpy().tolist())
+    sv, sk, skv, sm = top(imp[0]), top(imp[1]), top(imp[2]), top(mag)
+    terms = n * (n + 1) / 2 * hq * d
+    return {"workload": f"{w.name}: context {n}, top 10 % of the reused tokens", "ms": t / 1e3, "channel_terms": terms,
+            "G_terms_per_s": terms / (t * 1e-6) / 1e9,
+            "value_direction_vs_deviation_with_alpha_max_rel_diff": rel,
+            "top_set_overlap": {"key_vs_value_direction": len(sv & sk) / k, "value_vs_both_directions": len(sv & skv) / k,
+                                "magnitude_only_vs_both_directions": len(sm & skv) / k,
+                                "paper_key_vs_value": "80-90 % on its prompts (App. D.2); the synthetic cache draws one noise level per token for K and V alike"}}
+
+
 def measured_peaks(sh, w) -> dict:
     """What this machine reaches on plain work: a 256 MiB device copy (kvs_scatter_kv over every row of
     a layer: reads 2 x 64 MiB + indices, writes 2 x 64 MiB), a large bf16 library GEMM, and the
@@ -683,6 +729,7 @@ def main() -> int:
         "frac_mfma": flops_cs / (t_cs * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
         "flops": flops_cs, "check_sum_alpha_over_rows": [float(x) for x in row_sums.cpu()]}}
     del lay0, alpha_out, ws_cs
+    result["next_rows"]["first_order_impact"] = impact_config()
 
     if args.cpu_sample > 0:
         # (with --alpha gpu the oracle takes the alpha the GPU produced for layer 0: its own is O(N^2 d) on the CPU)

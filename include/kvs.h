@@ -271,8 +271,39 @@ KVS_API kvs_status kvs_attn_colsum(const kvs_shape *shape, int64_t n_tokens, con
                            void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * kvs_first_order_impact -- Sec. 4.1, Eq. (2): the first-order expansion of the attention output's
+ * deviation, dH ~ (dH/dK) dK + (dH/dV) dV, rated token by token.  With H = A V the correct (fresh,
+ * causal) attention, dK = k_cache - k_fresh and dV = v_cache - v_fresh, reusing token i's cache
+ * entry moves output row j >= i of query head h (KV head g) by
+ *     A[h,j,i] * dV[g,i]  +  A[h,j,i] * scale * (q[j,h] . dK[g,i]) * (V[g,i] - H[h,j])
+ * (value direction: dH/dV = A; key direction: the softmax Jacobian), and
+ *     impact_v[i]  = sum over h, j of the L1 norm of the first term  (= Eq. (3): alpha * |dV|_1)
+ *     impact_k[i]  = ... of the second term
+ *     impact_kv[i] = ... of their sum
+ * with -inf where reused[i] == 0.  The key direction is what the paper leaves out of Alg. 1 to save
+ * work (it costs n_tokens^2 / 2 * n_q_heads * head_dim vector operations and is no matrix product);
+ * this call exists to rank by it on check layers and to compare the two rankings (App. D.2).
+ *
+ * q        [dev] [n_tokens, n_q_heads, head_dim]
+ * h_fresh  [dev] [n_tokens, n_q_heads, head_dim] (shape dtype): the causal attention of every row over
+ *          the fresh K/V, e.g. from kvs_partial_attention with every token selected
+ * lse      [dev] fp32[n_tokens, n_q_heads]: that attention's log-sum-exp (natural log), same call
+ * reused   [dev] uint8[n_tokens] or NULL (every token is rated)
+ * impact_* [dev] fp32[n_tokens], each may be NULL
+ * workspace [dev] kvs_workspace_size("first_order_impact", shape, 1, n_tokens, 0) bytes, 256-byte aligned
+ * All arithmetic is fp32 on exactly widened inputs in a fixed order (bit-reproducible); up to 2^20 tokens.
+ */
+KVS_API kvs_status kvs_first_order_impact(const kvs_shape *shape, int64_t n_tokens, const void *q,
+                                  const void *k_fresh, const void *v_fresh,
+                                  const void *k_cache, const void *v_cache,
+                                  const void *h_fresh, const float *lse,
+                                  const uint8_t *reused, float scale,
+                                  float *impact_v, float *impact_k, float *impact_kv,
+                                  void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Workspace a call needs, in bytes, for the given problem.  `call` is "select_topk",
- * "partial_attention", "decode_check" or "attn_colsum" (anything else returns 0).  n_rows_total is the total
+ * "partial_attention", "decode_check", "attn_colsum" or "first_order_impact" (anything else returns 0).  n_rows_total is the total
  * number of score / cache rows the call will see, n_sel_total the total number of selected
  * tokens (partial_attention only).  The answer is an upper bound valid for any split of the
  * totals over `batch` requests.

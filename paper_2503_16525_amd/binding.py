@@ -22,7 +22,7 @@ SCORE_V, SCORE_KV = 0, 1
 OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP = 0, 1, 2, 3, 4
 
 EXPORTS = ("kvs_deviation", "kvs_deviation_topk", "kvs_select_topk", "kvs_select_topk_static", "kvs_scatter_kv", "kvs_partial_attention",
-           "kvs_decode_check", "kvs_attn_colsum", "kvs_workspace_size", "kvs_strerror", "kvs_last_error", "kvs_version")
+           "kvs_decode_check", "kvs_attn_colsum", "kvs_first_order_impact", "kvs_workspace_size", "kvs_strerror", "kvs_last_error", "kvs_version")
 
 
 class KvsError(RuntimeError):
@@ -60,9 +60,10 @@ def load(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.kvs_partial_attention.argtypes = [sp, i32, vp, vp, vp, vp, vp, vp, vp, f32, vp, vp, vp, sz, vp]
     lib.kvs_decode_check.argtypes = [sp, i32, i64, vp, vp, vp, vp, vp, vp, vp, f32, vp, vp, vp, vp, vp, sz, vp]
     lib.kvs_attn_colsum.argtypes = [sp, i64, vp, vp, f32, vp, vp, sz, vp]
+    lib.kvs_first_order_impact.argtypes = [sp, i64, vp, vp, vp, vp, vp, vp, vp, vp, f32, vp, vp, vp, vp, sz, vp]
     lib.kvs_workspace_size.argtypes = [ctypes.c_char_p, sp, i32, i64, i64]
     for n in ("kvs_deviation", "kvs_deviation_topk", "kvs_select_topk", "kvs_select_topk_static", "kvs_scatter_kv", "kvs_partial_attention",
-              "kvs_decode_check", "kvs_attn_colsum"):
+              "kvs_decode_check", "kvs_attn_colsum", "kvs_first_order_impact"):
         getattr(lib, n).restype = ctypes.c_int
     lib.kvs_workspace_size.restype = sz
     lib.kvs_strerror.argtypes = [ctypes.c_int]
@@ -205,6 +206,16 @@ def kvs_attn_colsum(shape: Shape, n_tokens: int, q, k, scale: float, alpha, work
     rc = load().kvs_attn_colsum(ctypes.byref(shape), n_tokens, _ptr(q), _ptr(k), scale, _ptr(alpha, torch.float32),
                                 _ptr(workspace), ws_bytes, _stream(stream))
     _check(rc, "kvs_attn_colsum")
+
+
+def kvs_first_order_impact(shape: Shape, n_tokens: int, q, k_fresh, v_fresh, k_cache, v_cache, h_fresh, lse, reused,
+                           scale: float, impact_v, impact_k, impact_kv, workspace, stream=None) -> None:
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    rc = load().kvs_first_order_impact(ctypes.byref(shape), n_tokens, _ptr(q), _ptr(k_fresh), _ptr(v_fresh), _ptr(k_cache),
+                                       _ptr(v_cache), _ptr(h_fresh), _ptr(lse, torch.float32), _ptr(reused, torch.uint8),
+                                       scale, _ptr(impact_v, torch.float32), _ptr(impact_k, torch.float32),
+                                       _ptr(impact_kv, torch.float32), _ptr(workspace), ws_bytes, _stream(stream))
+    _check(rc, "kvs_first_order_impact")
 
 
 def shape_of(workload) -> Shape:

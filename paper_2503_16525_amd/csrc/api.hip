@@ -73,6 +73,7 @@ extern "C" size_t kvs_workspace_size(const char *call, const kvs_shape *shape, i
     if (strcmp(call, "decode_check") == 0) return kvs::decode_workspace_bytes(shape, batch, n_rows_total);
     if (strcmp(call, "select_topk") == 0) return kvs::select_workspace_bytes(batch, n_rows_total);
     if (strcmp(call, "attn_colsum") == 0) return kvs::colsum_workspace_bytes(shape, n_rows_total);
+    if (strcmp(call, "first_order_impact") == 0) return kvs::impact_workspace_bytes(shape, n_rows_total);
     if (strcmp(call, "partial_attention") == 0)
         return kvs::attention_mfma_supports(shape) ? kvs::attention_workspace_bytes(shape, batch, n_rows_total, n_sel_total) : 256;
     return 0;

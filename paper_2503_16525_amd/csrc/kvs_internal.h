@@ -55,6 +55,7 @@ kvs_status launch_select(const float *scores, int32_t n_rows, const int64_t *beg
 size_t select_workspace_bytes(int32_t n_rows, int64_t n_scores);
 size_t decode_workspace_bytes(const kvs_shape *shape, int32_t batch, int64_t n_rows);
 size_t colsum_workspace_bytes(const kvs_shape *shape, int64_t n_tokens);
+size_t impact_workspace_bytes(const kvs_shape *shape, int64_t n_tokens);
 kvs_status launch_colsum_valu(const kvs_shape *shape, int64_t n, const void *q, const void *k, float scale,
                               float *lse, float *alpha, hipStream_t st);
 
