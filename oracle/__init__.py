@@ -53,7 +53,7 @@ def lib() -> ctypes.CDLL:
         _lib = ctypes.CDLL(build())
         for name in ("kvso_deviation", "kvso_alpha_prefill", "kvso_select_topk", "kvso_scatter_kv",
                      "kvso_partial_attention", "kvso_decode_check", "kvso_first_order_impact", "kvso_exact_impact",
-                     "kvso_max_threads"):
+                     "kvso_window_hash", "kvso_match_tokens", "kvso_schedule", "kvso_max_threads"):
             getattr(_lib, name).restype = ctypes.c_int
     return _lib
 
@@ -216,6 +216,36 @@ def exact_impact(q, k_fresh, v_fresh, k_cache, v_cache, scale: float, reused=Non
                                  _p(ru), ctypes.c_double(scale), _p(out))
     _check(rc, "exact_impact")
     return out
+
+
+def window_hash(tokens, window: int, base: int, modulus: int) -> np.ndarray:
+    """App. E Eq. (7) for every window of ``window`` tokens: uint32 [n - window + 1]."""
+    t = np.ascontiguousarray(np.asarray(tokens, dtype=np.int32))
+    out = np.zeros((max(0, t.shape[0] - window + 1),), dtype=np.uint32)
+    _check(lib().kvso_window_hash(_p(t), ctypes.c_int64(t.shape[0]), ctypes.c_int32(window), ctypes.c_uint32(base),
+                                  ctypes.c_uint32(modulus), _p(out)), "window_hash")
+    return out
+
+
+def match_tokens(target, candidate, window: int, base: int, modulus: int):
+    """App. E Alg. 3: (target_matches, candidate_matches) in the order of discovery, int32 each."""
+    t = np.ascontiguousarray(np.asarray(target, dtype=np.int32))
+    c = np.ascontiguousarray(np.asarray(candidate, dtype=np.int32))
+    tm = np.zeros((max(1, t.shape[0]),), dtype=np.int32)
+    cm = np.zeros((max(1, t.shape[0]),), dtype=np.int32)
+    n = ctypes.c_int64(0)
+    _check(lib().kvso_match_tokens(_p(t), ctypes.c_int64(t.shape[0]), _p(c), ctypes.c_int64(c.shape[0]),
+                                   ctypes.c_int32(window), ctypes.c_uint32(base), ctypes.c_uint32(modulus),
+                                   _p(tm), _p(cm), ctypes.byref(n)), "match_tokens")
+    return tm[:n.value].copy(), cm[:n.value].copy()
+
+
+def schedule(hit_rate) -> np.ndarray:
+    """Sec. 4.3 Alg. 2: request indices in the queue's order (hit rate descending, arrival order among equals)."""
+    h = np.ascontiguousarray(np.asarray(hit_rate, dtype=np.float32))
+    order = np.zeros((h.shape[0],), dtype=np.int32)
+    _check(lib().kvso_schedule(_p(h), ctypes.c_int32(h.shape[0]), _p(order)), "schedule")
+    return order
 
 
 def decode_check(q_new, k_cache, dev_v, reused, scale: float, ctx_off, ctx_len, k_req,

@@ -20,6 +20,12 @@
  *                          and both together
  *   kvso_exact_impact      Sec. 4.1 / App. D.2 "ideal index": the true change of the attention
  *                          output when one token's K/V alone is the reused one
+ *   kvso_window_hash       App. E Eq. (7): polynomial hash of every window of a token sequence
+ *   kvso_match_tokens      App. E Alg. 3: token-sequence matching over a hash index of the
+ *                          target's windows, candidate windows in ascending order, matches
+ *                          extended token by token, a target position matched at most once
+ *   kvso_schedule          Sec. 4.3 Alg. 2: the queue sorted by cache hit rate, descending; the
+ *                          first N requests form the next batch
  *
  * Arithmetic: inputs are converted exactly to double (bf16 and fp32 are both subsets of
  * double), every sum and product is carried in double in the natural index order, and a result
@@ -557,6 +563,111 @@ int kvso_exact_impact(const kvso_shape *sh, int64_t n, const void *q,
         free(logit); free(o);
     }
     free(H);
+    return 0;
+}
+
+/* ---------------------------------------------------------------------------------------------
+ * App. E, Eq. (7): H = (t_0 b^(w-1) + t_1 b^(w-2) + ... + t_(w-1) b^0) mod m for the window of w
+ * tokens that starts at every position i <= n - w.  The paper names neither b nor m: both are
+ * arguments (2 <= m < 2^32 or m = 1, b < 2^32).  Tokens are non-negative.  Every window is
+ * evaluated from its own definition (Horner over its w tokens): nothing rolls.
+ * hash_out: [n - w + 1] (nothing is written when n < w).
+ */
+int kvso_window_hash(const int32_t *tokens, int64_t n, int32_t w, uint32_t b, uint32_t m, uint32_t *hash_out)
+{
+    if (n < 0 || w <= 0 || m == 0 || (n > 0 && !tokens) || (n >= w && !hash_out)) return 1;
+    for (int64_t i = 0; i < n; ++i)
+        if (tokens[i] < 0) return 1;
+    for (int64_t i = 0; i + w <= n; ++i) {
+        uint64_t h = 0;
+        for (int32_t x = 0; x < w; ++x) h = (h * (uint64_t)b + (uint64_t)tokens[i + x]) % (uint64_t)m;
+        hash_out[i] = (uint32_t)h;
+    }
+    return 0;
+}
+
+typedef struct { uint32_t h; int64_t i; } kvso_index_entry;
+
+static int index_entry_cmp(const void *a, const void *b)
+{
+    const kvso_index_entry *x = (const kvso_index_entry *)a, *y = (const kvso_index_entry *)b;
+    if (x->h != y->h) return x->h < y->h ? -1 : 1;
+    return x->i < y->i ? -1 : (x->i > y->i ? 1 : 0);
+}
+
+/* ---------------------------------------------------------------------------------------------
+ * App. E, Alg. 3.  Step 2: an index from hash value to the list of target window starts with
+ * that hash, in ascending order (here: the (hash, start) pairs sorted, a list being a stretch of
+ * equal hashes).  Step 3: candidate window starts j in ascending order; for every target start
+ * i listed under the candidate window's hash, k runs from 0 while both positions exist and the
+ * tokens agree; a target position i+k that has not been matched before is recorded together
+ * with j+k and marked.  The algorithm compares hashes only, then tokens one at a time: two
+ * windows that collide in the hash still contribute the stretch of equal tokens they start with.
+ *
+ * target_matches, candidate_matches: [n_target] each, filled in the order of discovery;
+ * *n_matches: how many pairs were recorded.
+ */
+int kvso_match_tokens(const int32_t *target, int64_t n_target, const int32_t *candidate, int64_t n_candidate,
+                      int32_t w, uint32_t b, uint32_t m,
+                      int32_t *target_matches, int32_t *candidate_matches, int64_t *n_matches)
+{
+    if (n_target < 0 || n_candidate < 0 || w <= 0 || m == 0 || !n_matches) return 1;
+    if (n_target > 0x7fffffff || n_candidate > 0x7fffffff) return 1;
+    *n_matches = 0;
+    const int64_t nt = n_target - w + 1, nc = n_candidate - w + 1;     /* window starts */
+    for (int64_t i = 0; i < n_target; ++i) if (target[i] < 0) return 1;
+    for (int64_t j = 0; j < n_candidate; ++j) if (candidate[j] < 0) return 1;
+    if (nt <= 0 || nc <= 0) return 0;
+    uint32_t *ht = (uint32_t *)malloc((size_t)nt * sizeof(uint32_t));
+    uint32_t *hc = (uint32_t *)malloc((size_t)nc * sizeof(uint32_t));
+    kvso_index_entry *index = (kvso_index_entry *)malloc((size_t)nt * sizeof(kvso_index_entry));
+    unsigned char *matched = (unsigned char *)calloc((size_t)n_target, 1);
+    if (!ht || !hc || !index || !matched) { free(ht); free(hc); free(index); free(matched); return 1; }
+    kvso_window_hash(target, n_target, w, b, m, ht);
+    kvso_window_hash(candidate, n_candidate, w, b, m, hc);
+    for (int64_t i = 0; i < nt; ++i) { index[i].h = ht[i]; index[i].i = i; }
+    qsort(index, (size_t)nt, sizeof(kvso_index_entry), index_entry_cmp);
+    int64_t count = 0;
+    for (int64_t j = 0; j < nc; ++j) {
+        const uint32_t h = hc[j];
+        /* first entry of the list under h */
+        int64_t lo = 0, hi = nt;
+        while (lo < hi) { const int64_t mid = (lo + hi) / 2; if (index[mid].h < h) lo = mid + 1; else hi = mid; }
+        for (int64_t e = lo; e < nt && index[e].h == h; ++e) {
+            const int64_t i = index[e].i;
+            int64_t k = 0;
+            while (i + k < n_target && j + k < n_candidate && target[i + k] == candidate[j + k]) {
+                if (!matched[i + k]) {
+                    target_matches[count] = (int32_t)(i + k);
+                    candidate_matches[count] = (int32_t)(j + k);
+                    ++count;
+                    matched[i + k] = 1;
+                }
+                ++k;
+            }
+        }
+    }
+    *n_matches = count;
+    free(ht); free(hc); free(index); free(matched);
+    return 0;
+}
+
+/* ---------------------------------------------------------------------------------------------
+ * Sec. 4.3, Alg. 2: the queue sorted by cache hit rate, descending (requests of equal rate stay
+ * in their order of arrival, which is their index), and the first N of it sent on as a batch.
+ * order: [n] the whole queue after the sort; the batch is its first min(N, n) entries.
+ */
+int kvso_schedule(const float *hit_rate, int32_t n, int32_t *order)
+{
+    if (n < 0 || (n > 0 && (!hit_rate || !order))) return 1;
+    for (int32_t r = 0; r < n; ++r) order[r] = r;
+    /* insertion sort: stable, and the queue of Alg. 2 is built by insertions */
+    for (int32_t r = 1; r < n; ++r) {
+        const int32_t x = order[r];
+        int32_t q = r;
+        while (q > 0 && hit_rate[order[q - 1]] < hit_rate[x]) { order[q] = order[q - 1]; --q; }
+        order[q] = x;
+    }
     return 0;
 }
 

@@ -226,3 +226,42 @@ def make_decode_batch(w: Workload, batch: int, len_lo: int, len_hi: int, n_steps
     v_new = _randn((n_steps, batch, hkv, d), gen, dev).to(dt)
     return dict(k_fresh=k_fresh, v_fresh=v_fresh, k_cache=k_cache, v_cache=v_cache, reused=reused,
                 ctx_off=off, ctx_len=lens, q_new=q_new, k_new=k_new, v_new=v_new)
+
+
+def make_token_streams(w: Workload, seed: int = 0, window: int = 16, unique_candidate: bool = True,
+                       vocab: int = 128256) -> Dict[str, np.ndarray]:
+    """A target token sequence assembled from stretches of an earlier request (the candidate) and fresh text.
+
+    The reused stretches are those of ``make_spans`` (the same span structure the K/V workloads use);
+    each is copied from a random place in the candidate, the rest of the target is fresh.  With
+    ``unique_candidate`` the candidate's tokens are all different and the fresh tokens come from a
+    disjoint range, so the only common stretches are the copied ones and each has one source; otherwise
+    both are drawn from one Zipf-like distribution over ``vocab`` ids, where frequent tokens repeat and
+    short accidental stretches occur, as in text.
+
+    Returns int32 ``target`` [n_ctx], ``candidate`` [n_ctx], and per target position ``source`` (the
+    candidate position it was copied from, -1 for fresh text) and ``span_len`` (length of the copied
+    stretch it belongs to, 0 for fresh text).
+    """
+    n = w.n_ctx
+    rng = _np_rng(layer_seed(w, 0, salt=seed) ^ 0x70C3)
+    if unique_candidate:
+        candidate = rng.permutation(2 * n)[:n].astype(np.int32)
+        fresh = (2 * n + rng.integers(0, n, size=n)).astype(np.int32)
+    else:
+        ranks = np.minimum(rng.zipf(1.2, size=2 * n), vocab) - 1
+        ids = rng.permutation(vocab)
+        candidate = ids[ranks[:n]].astype(np.int32)
+        fresh = ids[ranks[n:]].astype(np.int32)
+    reused = make_spans(w, layer_seed(w, 0, salt=seed))
+    target = fresh.copy()
+    source = np.full(n, -1, dtype=np.int64)
+    span_len = np.zeros(n, dtype=np.int64)
+    edges = np.flatnonzero(np.diff(np.concatenate([[0], reused, [0]])))
+    for a, e in zip(edges[0::2], edges[1::2]):
+        L = int(e - a)
+        c = int(rng.integers(0, n - L + 1))
+        target[a:e] = candidate[c:c + L]
+        source[a:e] = np.arange(c, c + L)
+        span_len[a:e] = L
+    return dict(target=target, candidate=candidate, source=source, span_len=span_len)
