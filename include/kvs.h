@@ -302,10 +302,45 @@ KVS_API kvs_status kvs_first_order_impact(const kvs_shape *shape, int64_t n_toke
                                   void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Token-sequence matching of the KV Retriever (Sec. 5.1; App. E Alg. 3 with the polynomial window
+ * hash of Eq. (7)): which tokens of a new request (the target) also stand, in stretches that start
+ * with a whole window of `window` equal-hash tokens, in an earlier request (the candidate), and where.
+ * The result is the one the algorithm's sequential scan produces: a target position is matched once,
+ * by the first pair of window starts (candidate window ascending, then target window ascending)
+ * whose stretch of equal tokens reaches it; windows are compared by hash only, then token by
+ * token, so two different windows with one hash contribute the equal tokens they begin with.
+ * The paper names neither the base, the modulus nor the window: all three are arguments.
+ *
+ * target, candidate [dev] int32 token ids, non-negative (an id is hashed as an unsigned 32-bit number)
+ * window            > 0; sequences shorter than the window match nothing
+ * hash_base         b of Eq. (7), any 32-bit value
+ * hash_modulus      m of Eq. (7), 1 .. 2^32-1
+ * match_cand        [dev] int32[n_target] out: candidate position matched to each target position, -1: none
+ * target_matches, candidate_matches
+ *                   [dev] int32[n_target] out, each may be NULL: the matched pairs in the algorithm's
+ *                   order of discovery (its two output lists); entries from *n_matches on are not written
+ * n_matches         [dev] int64 out: number of matched target positions (hit rate = n_matches / n_target)
+ * workspace         [dev] kvs_workspace_size("match_tokens", NULL, 1, n_target, n_candidate) bytes,
+ *                   256-byte aligned (not needed when a sequence is shorter than the window)
+ * Up to 2^26 tokens per sequence.  Integer work: the outputs are exact and do not depend on the
+ * order in which the device's atomics arrive.  Six launches, no host synchronisation.  Cost grows
+ * with the matched tokens, except for degenerate inputs (one token repeated throughout both
+ * sequences makes every pair of windows a candidate: n_target x n_candidate steps).
+ * The scheduler of Sec. 4.3 Alg. 2 needs no call of its own: the batch it sends on is
+ * kvs_select_topk over the requests' hit rates (ties to the request that arrived first).
+ */
+KVS_API kvs_status kvs_match_tokens(const int32_t *target, int64_t n_target,
+                                    const int32_t *candidate, int64_t n_candidate,
+                                    int32_t window, uint32_t hash_base, uint32_t hash_modulus,
+                                    int32_t *match_cand, int32_t *target_matches, int32_t *candidate_matches,
+                                    int64_t *n_matches, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Workspace a call needs, in bytes, for the given problem.  `call` is "select_topk",
- * "partial_attention", "decode_check", "attn_colsum" or "first_order_impact" (anything else returns 0).  n_rows_total is the total
- * number of score / cache rows the call will see, n_sel_total the total number of selected
- * tokens (partial_attention only).  The answer is an upper bound valid for any split of the
+ * "partial_attention", "decode_check", "attn_colsum", "first_order_impact" or "match_tokens" (anything else
+ * returns 0).  n_rows_total is the total number of score / cache rows the call will see (match_tokens: the
+ * target's tokens), n_sel_total the total number of selected tokens (partial_attention) or the candidate's
+ * tokens (match_tokens, which ignores shape: it may be NULL there).  The answer is an upper bound valid for any split of the
  * totals over `batch` requests.
  */
 KVS_API size_t kvs_workspace_size(const char *call, const kvs_shape *shape, int32_t batch,

@@ -22,7 +22,7 @@ SCORE_V, SCORE_KV = 0, 1
 OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP = 0, 1, 2, 3, 4
 
 EXPORTS = ("kvs_deviation", "kvs_deviation_topk", "kvs_select_topk", "kvs_select_topk_static", "kvs_scatter_kv", "kvs_partial_attention",
-           "kvs_decode_check", "kvs_attn_colsum", "kvs_first_order_impact", "kvs_workspace_size", "kvs_strerror", "kvs_last_error", "kvs_version")
+           "kvs_decode_check", "kvs_attn_colsum", "kvs_first_order_impact", "kvs_match_tokens", "kvs_workspace_size", "kvs_strerror", "kvs_last_error", "kvs_version")
 
 
 class KvsError(RuntimeError):
@@ -61,9 +61,10 @@ def load(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.kvs_decode_check.argtypes = [sp, i32, i64, vp, vp, vp, vp, vp, vp, vp, f32, vp, vp, vp, vp, vp, sz, vp]
     lib.kvs_attn_colsum.argtypes = [sp, i64, vp, vp, f32, vp, vp, sz, vp]
     lib.kvs_first_order_impact.argtypes = [sp, i64, vp, vp, vp, vp, vp, vp, vp, vp, f32, vp, vp, vp, vp, sz, vp]
+    lib.kvs_match_tokens.argtypes = [vp, i64, vp, i64, i32, ctypes.c_uint32, ctypes.c_uint32, vp, vp, vp, vp, vp, sz, vp]
     lib.kvs_workspace_size.argtypes = [ctypes.c_char_p, sp, i32, i64, i64]
     for n in ("kvs_deviation", "kvs_deviation_topk", "kvs_select_topk", "kvs_select_topk_static", "kvs_scatter_kv", "kvs_partial_attention",
-              "kvs_decode_check", "kvs_attn_colsum", "kvs_first_order_impact"):
+              "kvs_decode_check", "kvs_attn_colsum", "kvs_first_order_impact", "kvs_match_tokens"):
         getattr(lib, n).restype = ctypes.c_int
     lib.kvs_workspace_size.restype = sz
     lib.kvs_strerror.argtypes = [ctypes.c_int]
@@ -120,8 +121,9 @@ def make_shape(n_q_heads: int, n_kv_heads: int, head_dim: int, dtype: int) -> Sh
     return Shape(n_q_heads, n_kv_heads, head_dim, dtype)
 
 
-def kvs_workspace_size(call: str, shape: Shape, batch: int, n_rows_total: int, n_sel_total: int = 0) -> int:
-    return int(load().kvs_workspace_size(call.encode(), ctypes.byref(shape), batch, n_rows_total, n_sel_total))
+def kvs_workspace_size(call: str, shape: Optional[Shape], batch: int, n_rows_total: int, n_sel_total: int = 0) -> int:
+    return int(load().kvs_workspace_size(call.encode(), ctypes.byref(shape) if shape is not None else None, batch,
+                                         n_rows_total, n_sel_total))
 
 
 def kvs_deviation(shape: Shape, n_tokens: int, k_fresh, v_fresh, k_cache, v_cache, reused, alpha,
@@ -216,6 +218,17 @@ def kvs_first_order_impact(shape: Shape, n_tokens: int, q, k_fresh, v_fresh, k_c
                                        scale, _ptr(impact_v, torch.float32), _ptr(impact_k, torch.float32),
                                        _ptr(impact_kv, torch.float32), _ptr(workspace), ws_bytes, _stream(stream))
     _check(rc, "kvs_first_order_impact")
+
+
+def kvs_match_tokens(target, candidate, window: int, hash_base: int, hash_modulus: int, match_cand,
+                     target_matches, candidate_matches, n_matches, workspace, stream=None) -> None:
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    rc = load().kvs_match_tokens(_ptr(target, torch.int32), target.numel() if target is not None else 0,
+                                 _ptr(candidate, torch.int32), candidate.numel() if candidate is not None else 0,
+                                 window, hash_base, hash_modulus, _ptr(match_cand, torch.int32),
+                                 _ptr(target_matches, torch.int32), _ptr(candidate_matches, torch.int32),
+                                 _ptr(n_matches, torch.int64), _ptr(workspace), ws_bytes, _stream(stream))
+    _check(rc, "kvs_match_tokens")
 
 
 def shape_of(workload) -> Shape:

@@ -69,7 +69,9 @@ extern "C" const char *kvs_version(void) { return "kvshare-hip gfx950 1"; }
 extern "C" size_t kvs_workspace_size(const char *call, const kvs_shape *shape, int32_t batch,
                                      int64_t n_rows_total, int64_t n_sel_total)
 {
-    if (!call || !shape || batch < 0 || n_rows_total < 0) return 0;
+    if (!call || batch < 0 || n_rows_total < 0) return 0;
+    if (strcmp(call, "match_tokens") == 0) return kvs::match_workspace_bytes(n_rows_total, n_sel_total);
+    if (!shape) return 0;
     if (strcmp(call, "decode_check") == 0) return kvs::decode_workspace_bytes(shape, batch, n_rows_total);
     if (strcmp(call, "select_topk") == 0) return kvs::select_workspace_bytes(batch, n_rows_total);
     if (strcmp(call, "attn_colsum") == 0) return kvs::colsum_workspace_bytes(shape, n_rows_total);

@@ -56,6 +56,7 @@ size_t select_workspace_bytes(int32_t n_rows, int64_t n_scores);
 size_t decode_workspace_bytes(const kvs_shape *shape, int32_t batch, int64_t n_rows);
 size_t colsum_workspace_bytes(const kvs_shape *shape, int64_t n_tokens);
 size_t impact_workspace_bytes(const kvs_shape *shape, int64_t n_tokens);
+size_t match_workspace_bytes(int64_t n_target, int64_t n_candidate);
 kvs_status launch_colsum_valu(const kvs_shape *shape, int64_t n, const void *q, const void *k, float scale,
                               float *lse, float *alpha, hipStream_t st);
 

@@ -1,0 +1,118 @@
+"""kvs_match_tokens (App. E Alg. 3, Eq. (7)) against the oracle, bit for bit: the partner of every
+target position, the two lists in the algorithm's order of discovery and the match count; and the
+batch of Sec. 4.3 Alg. 2 (kvs_select_topk over hit rates) against the oracle's sorted queue."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2503_16525_amd import binding as B
+from paper_2503_16525_amd import synth
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+BASE, MOD = 1000003, 4294967291
+
+
+def say(msg):
+    print(f"[case] {msg}", flush=True)
+    sys.stdout.flush()
+
+
+def gpu_match(target, candidate, w, b, m, lists=True):
+    t = torch.from_numpy(np.asarray(target, dtype=np.int32)).to(DEV)
+    c = torch.from_numpy(np.asarray(candidate, dtype=np.int32)).to(DEV)
+    nt = t.numel()
+    partner = torch.full((max(nt, 1),), -7, dtype=torch.int32, device=DEV)
+    tm = torch.full((max(nt, 1),), -7, dtype=torch.int32, device=DEV) if lists else None
+    cm = torch.full((max(nt, 1),), -7, dtype=torch.int32, device=DEV) if lists else None
+    n = torch.full((1,), -7, dtype=torch.int64, device=DEV)
+    ws = torch.empty(B.kvs_workspace_size("match_tokens", None, 1, nt, c.numel()), dtype=torch.uint8, device=DEV)
+    B.kvs_match_tokens(t if nt else None, c if c.numel() else None, w, b, m, partner if nt else None, tm, cm, n, ws)
+    torch.cuda.synchronize()
+    k = int(n.item())
+    return (partner[:nt].cpu().numpy(), tm[:k].cpu().numpy() if lists else None, cm[:k].cpu().numpy() if lists else None, k,
+            (tm[k:].cpu().numpy(), cm[k:].cpu().numpy()) if lists else None)
+
+
+def check(target, candidate, w, b=BASE, m=MOD):
+    ref_t, ref_c = oracle.match_tokens(target, candidate, w, b, m)
+    partner, tm, cm, k, rest = gpu_match(target, candidate, w, b, m)
+    want = np.full(len(target), -1, dtype=np.int32)
+    want[ref_t] = ref_c
+    assert k == ref_t.size
+    assert np.array_equal(partner, want)
+    assert np.array_equal(tm, ref_t) and np.array_equal(cm, ref_c)
+    assert np.all(rest[0] == -7) and np.all(rest[1] == -7)            # nothing written past the count
+    partner2, _, _, k2, _ = gpu_match(target, candidate, w, b, m, lists=False)
+    assert k2 == k and np.array_equal(partner2, want)
+    return k
+
+
+@pytest.mark.parametrize("n,unique", [(4096, True), (4096, False), (5000, False), (32768, True), (32768, False)])
+def test_match_planted_streams(n, unique):
+    say(f"match llama-shaped streams n={n} unique={unique}")
+    s = synth.make_token_streams(synth.scaled(synth.LLAMA, n), seed=1, unique_candidate=unique)
+    k = check(s["target"], s["candidate"], 16)
+    say(f"  matched {k} of {n}")
+    assert k >= int((s["span_len"] >= 16).sum())
+
+
+def test_match_yi_131k():
+    say("match yi-shaped streams n=131072")
+    s = synth.make_token_streams(synth.YI, seed=2, unique_candidate=False)
+    check(s["target"], s["candidate"], 32)
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_match_collisions_and_repeats(seed):
+    """tiny vocabularies (stretches overlap and repeat) and tiny moduli (different windows share a hash)"""
+    rng = np.random.default_rng(300 + seed)
+    vocab = (2, 3, 4, 7, 30)[seed % 5]
+    w = (1, 2, 3, 5, 8)[(seed // 2) % 5]
+    m = (1, 2, 7, 251, MOD)[seed % 5]
+    nt, nc = int(rng.integers(1, 3000)), int(rng.integers(1, 3000))
+    say(f"match collisions seed={seed} vocab={vocab} w={w} m={m} n_target={nt} n_candidate={nc}")
+    check(rng.integers(0, vocab, size=nt), rng.integers(0, vocab, size=nc), w, 31, m)
+
+
+def test_match_degenerate_inputs():
+    say("match: one repeated token")
+    check([4] * 700, [4] * 500, 3)
+    check([4] * 300, [4] * 900, 16, 2, 1)
+    say("match: identical sequences")
+    t = np.random.default_rng(1).integers(0, 50000, size=5000)
+    assert check(t, t, 16) == 5000
+    say("match: shorter than the window, empty")
+    assert check(t[:15], t, 16) == 0
+    assert check(t, t[:15], 16) == 0
+    assert check([], t, 16) == 0
+    assert check(t[:100], [], 16) == 0
+    say("match: window as long as a sequence")
+    assert check(t[:16], t[:16], 16) == 16
+    assert check(t[:300], t[100:116], 16) == 16
+
+
+def test_match_periodic_text():
+    """a phrase repeated many times in both sequences: many equal windows per hash, long chains"""
+    say("match: periodic sequences")
+    rng = np.random.default_rng(9)
+    phrase = rng.integers(0, 1000, size=37)
+    t = np.concatenate([np.tile(phrase, 40), rng.integers(0, 1000, size=100), np.tile(phrase, 11)])
+    c = np.concatenate([rng.integers(0, 1000, size=50), np.tile(phrase, 25), rng.integers(0, 1000, size=33)])
+    check(t, c, 8)
+    check(c, t, 8)
+
+
+def test_schedule_batch_is_topk_of_hit_rates():
+    """Sec. 4.3 Alg. 2: the N requests of highest hit rate (earlier arrival among equals) as kvs_select_topk finds them"""
+    say("schedule: top-N by hit rate")
+    rng = np.random.default_rng(4)
+    for n, batch in ((1, 1), (37, 8), (1000, 64), (5000, 5000)):
+        h = np.round(rng.random(n), 2).astype(np.float32)
+        idx = torch.empty((batch,), dtype=torch.int32, device=DEV)
+        B.kvs_select_topk(torch.from_numpy(h).to(DEV), [0, n], [batch], idx)
+        torch.cuda.synchronize()
+        assert sorted(idx.cpu().tolist()) == sorted(oracle.schedule(h)[:batch].tolist())
