@@ -558,6 +558,37 @@ def impact_config() -> dict:
                                 "paper_key_vs_value": "80-90 % on its prompts (App. D.2); the synthetic cache draws one noise level per token for K and V alike"}}
 
 
+def match_config(with_oracle: bool) -> dict:
+    """Before the timed path: the retriever's token matching (App. E Alg. 3, Eq. (7)) of a 32k-token
+    request against an earlier one, on token streams with the span structure of the K/V workload
+    (tokens from a Zipf-like distribution, reused stretches copied from the candidate)."""
+    w = synth.LLAMA
+    n = w.n_ctx
+    window, base, modulus = 16, 1000003, 4294967291
+    streams = [synth.make_token_streams(w, seed=s, window=window, unique_candidate=False) for s in range(4)]
+    dev = [(torch.from_numpy(s["target"]).to(DEV), torch.from_numpy(s["candidate"]).to(DEV)) for s in streams]
+    partner = torch.empty((n,), dtype=torch.int32, device=DEV)
+    tm, cm = torch.empty((n,), dtype=torch.int32, device=DEV), torch.empty((n,), dtype=torch.int32, device=DEV)
+    cnt = torch.zeros((1,), dtype=torch.int64, device=DEV)
+    ws = torch.empty(B.kvs_workspace_size("match_tokens", None, 1, n, n), dtype=torch.uint8, device=DEV)
+    t, med = time_loop([lambda t_=t_, c_=c_: B.kvs_match_tokens(t_, c_, window, base, modulus, partner, tm, cm, cnt, ws) for t_, c_ in dev] * 4)
+    t_map, _ = time_loop([lambda t_=t_, c_=c_: B.kvs_match_tokens(t_, c_, window, base, modulus, partner, None, None, cnt, ws) for t_, c_ in dev] * 4)
+    B.kvs_match_tokens(dev[0][0], dev[0][1], window, base, modulus, partner, tm, cm, cnt, ws)
+    torch.cuda.synchronize()
+    k = int(cnt.item())
+    out = {"workload": f"{w.name} token streams: target and candidate of {n} tokens, window {window}, base {base}, modulus {modulus}",
+           "us": t, "median_us": med, "us_partners_only": t_map, "matched_tokens": k, "hit_rate": k / n,
+           "Mtokens_per_s": 2 * n / t, "launches": 6,
+           "note": "latency-bound: six short dependent launches over 0.26 MB of tokens"}
+    if with_oracle:
+        import oracle
+        t0 = time.perf_counter()
+        ref_t, ref_c = oracle.match_tokens(streams[0]["target"], streams[0]["candidate"], window, base, modulus)
+        out["oracle_cpu_ms"] = (time.perf_counter() - t0) * 1e3
+        out["parity"] = bool(np.array_equal(tm[:k].cpu().numpy(), ref_t) and np.array_equal(cm[:k].cpu().numpy(), ref_c))
+    return out
+
+
 def measured_peaks(sh, w) -> dict:
     """What this machine reaches on plain work: a 256 MiB device copy (kvs_scatter_kv over every row of
     a layer: reads 2 x 64 MiB + indices, writes 2 x 64 MiB), a large bf16 library GEMM, and the
@@ -730,6 +761,7 @@ def main() -> int:
         "flops": flops_cs, "check_sum_alpha_over_rows": [float(x) for x in row_sums.cpu()]}}
     del lay0, alpha_out, ws_cs
     result["next_rows"]["first_order_impact"] = impact_config()
+    result["next_rows"]["match_tokens"] = match_config(with_oracle=args.cpu_sample > 0)
 
     if args.cpu_sample > 0:
         # (with --alpha gpu the oracle takes the alpha the GPU produced for layer 0: its own is O(N^2 d) on the CPU)

@@ -16,7 +16,7 @@
 //   3. match_seed_kernel    a lane per candidate window walks its chain.  A pair (i, j) whose
 //                           predecessor (i-1, j-1) is an equal-hash pair with equal tokens is skipped:
 //                           the predecessor reaches everything (i, j) reaches and comes earlier in
-//                           the order.  Each remaining pair is extended by its whole wavefront, 256
+//                           the order.  Each remaining pair is extended by its whole wavefront, 1024
 //                           positions per trip, and claims the positions it reaches with a 64-bit
 //                           atomic minimum on (j, i).  A stretch of R equal tokens costs R atomics
 //                           instead of the scan's R^2 / 2 comparisons.
@@ -79,27 +79,63 @@ inline size_t carve(MatchWs *ws, char *base, int64_t n_t, int64_t n_c, int bits)
     return (size_t)off;
 }
 
-__device__ __forceinline__ uint32_t window_hash(const int32_t *__restrict__ tok, int64_t i, int w, uint32_t b, uint32_t m)
+// x mod m for any 64-bit x without a division: with r = floor((2^64 - 1) / m), the estimate
+// q = floor(x r / 2^64) falls short of floor(x / m) by at most 2, so two conditional subtractions finish.
+// (q <= x/m because r <= 2^64/m; and x/m - q < x (2^64/m - r) / 2^64 + 1 <= x (1 + 1/m) / 2^64 + 1 < 3.)
+struct Modulus {
+    uint64_t m, r;
+};
+__device__ __forceinline__ uint64_t reduce(uint64_t x, const Modulus &md)
+{
+    uint64_t rem = x - __umul64hi(x, md.r) * md.m;
+    rem = rem >= md.m ? rem - md.m : rem;
+    rem = rem >= md.m ? rem - md.m : rem;
+    return rem;
+}
+template <typename Tokens>
+__device__ __forceinline__ uint32_t window_hash(Tokens tok, int64_t i, int w, uint32_t b, const Modulus &md)
 {
     uint64_t h = 0;
-    for (int x = 0; x < w; ++x) h = (h * (uint64_t)b + (uint64_t)(uint32_t)tok[i + x]) % (uint64_t)m;
+    for (int x = 0; x < w; ++x) h = reduce(h * (uint64_t)b + (uint64_t)(uint32_t)tok[i + x], md);   // h < m < 2^32: no overflow
     return (uint32_t)h;
 }
 __device__ __forceinline__ uint32_t slot_of(uint32_t h, int bits) { return (h * 2654435761u) >> (32 - bits); }
 
+// Windows up to this long are hashed out of LDS: a workgroup's 256 windows overlap in all but 255
+// tokens, and a Horner chain over global memory would pay one memory latency per token.
+constexpr int kHashLdsWindow = 768;
+
+// hashes of the windows that start at base .. base+255 (those below n_windows) of one sequence
+__device__ __forceinline__ void hash_block(const int32_t *__restrict__ tok, int64_t n, int64_t n_windows, int64_t base, int w, uint32_t b,
+                                           const Modulus &md, int32_t *tile, uint32_t *__restrict__ out)
+{
+    const int64_t i = base + threadIdx.x;
+    if (w <= kHashLdsWindow) {
+        const int64_t span = min((int64_t)kMatchThreads + w - 1, n - base);
+        __syncthreads();                                   // the tile's previous readers are done
+        for (int64_t x = threadIdx.x; x < span; x += kMatchThreads) tile[x] = tok[base + x];
+        __syncthreads();
+        if (i < n_windows) out[i] = window_hash(tile, (int64_t)threadIdx.x, w, b, md);
+    } else if (i < n_windows) {
+        out[i] = window_hash(tok, i, w, b, md);
+    }
+}
+
 __global__ __launch_bounds__(kMatchThreads) void match_hash_kernel(
     const int32_t *__restrict__ target, int64_t n_t, const int32_t *__restrict__ cand, int64_t n_c,
-    int w, uint32_t b, uint32_t m, int bits, MatchWs ws)
+    int w, uint32_t b, Modulus md, int bits, MatchWs ws)
 {
+    __shared__ int32_t tile[kMatchThreads + kHashLdsWindow];
     const int64_t tid = (int64_t)blockIdx.x * kMatchThreads + threadIdx.x, nth = (int64_t)gridDim.x * kMatchThreads;
     const int64_t wt = n_t - w + 1, wc = n_c - w + 1, table = (int64_t)1 << bits;
-    for (int64_t i = tid; i < n_t; i += nth) {
-        ws.best[i] = kNoMatch;
-        if (i < wt) ws.ht[i] = window_hash(target, i, w, b, m);
-    }
-    for (int64_t j = tid; j < wc; j += nth) ws.hc[j] = window_hash(cand, j, w, b, m);
+    for (int64_t i = tid; i < n_t; i += nth) ws.best[i] = kNoMatch;
     for (int64_t s = tid; s < table; s += nth) ws.head[s] = -1;
     if (tid < 4) ws.counters[tid] = 0u;
+    // the first blocks_t workgroups hash the target's windows, the others the candidate's (one block of
+    // 256 windows each; every thread of a workgroup takes part in staging its block's tokens)
+    const int64_t blocks_t = (wt + kMatchThreads - 1) / kMatchThreads;
+    if ((int64_t)blockIdx.x < blocks_t) hash_block(target, n_t, wt, (int64_t)blockIdx.x * kMatchThreads, w, b, md, tile, ws.ht);
+    else hash_block(cand, n_c, wc, ((int64_t)blockIdx.x - blocks_t) * kMatchThreads, w, b, md, tile, ws.hc);
 }
 
 __global__ __launch_bounds__(kMatchThreads) void match_insert_kernel(int64_t wt, int bits, MatchWs ws)
@@ -111,25 +147,30 @@ __global__ __launch_bounds__(kMatchThreads) void match_insert_kernel(int64_t wt,
 
 // the whole wavefront extends the pair of window starts (i, j): positions i+k while both sequences
 // last and the tokens agree; each reached position keeps the smallest key.  Ends at the first
-// disagreement or at the end of a sequence, whichever comes first.
+// disagreement or at the end of a sequence, whichever comes first.  A trip compares 1024 positions,
+// all of its loads in flight together: the loop pays one memory latency per trip, and the
+// atomics return nothing to wait for.
+constexpr int kClaimUnroll = 16;
 __device__ __forceinline__ void claim_stretch(const int32_t *__restrict__ target, int64_t n_t, const int32_t *__restrict__ cand,
                                               int64_t n_c, int32_t i, int32_t j, uint64_t *__restrict__ best, int lane)
 {
     const uint64_t key = ((uint64_t)(uint32_t)j << 32) | (uint32_t)i;
     const int64_t room = min(n_t - i, n_c - j);
-    for (int64_t k0 = 0; k0 < room; k0 += 4 * kWave) {
-        bool ok[4];
+    for (int64_t k0 = 0; k0 < room; k0 += kClaimUnroll * kWave) {
+        int32_t a[kClaimUnroll], c[kClaimUnroll];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int64_t k = k0 + u * kWave + lane;
-            ok[u] = k < room && target[i + k] == cand[j + k];
+        for (int u = 0; u < kClaimUnroll; ++u) {
+            const int64_t k = min(k0 + u * kWave + lane, room - 1);     // clamped: every load is inside both sequences
+            a[u] = target[i + k];
+            c[u] = cand[j + k];
         }
         bool open = true;                       // uniform: no disagreement so far in this trip
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const unsigned long long agree = __ballot(ok[u]);
+        for (int u = 0; u < kClaimUnroll; ++u) {
+            const int64_t k = k0 + u * kWave + lane;
+            const unsigned long long agree = __ballot(k < room && a[u] == c[u]);
             const int first_bad = ~agree ? __ffsll((long long)~agree) - 1 : kWave;
-            if (open && lane < first_bad) atomicMin((unsigned long long *)&best[i + k0 + u * kWave + lane], (unsigned long long)key);
+            if (open && lane < first_bad) atomicMin((unsigned long long *)&best[i + k], (unsigned long long)key);
             open = open && first_bad == kWave;
         }
         if (!open) break;
@@ -151,9 +192,16 @@ __global__ __launch_bounds__(kMatchThreads) void match_seed_kernel(
     const int32_t tok_prev = has_prev ? cand[j - 1] : -1;
     int32_t cur = live ? ws.head[slot_of(hj, bits)] : -1;
     while (__any(cur >= 0)) {
+        // everything one chain step needs, requested together: one memory latency per step
+        const bool on = cur >= 0;
+        const int32_t prev = on && cur > 0 ? cur - 1 : 0;
+        const uint32_t h_cur = on ? ws.ht[cur] : 0u;
+        const uint32_t h_before = on ? ws.ht[prev] : 0u;
+        const int32_t tok_before = on ? target[prev] : -1;
+        const int32_t nxt = on ? ws.next[cur] : -1;
         bool first_of_its_stretch = false;
-        if (cur >= 0 && ws.ht[cur] == hj) {
-            const bool shadowed = has_prev && cur > 0 && ws.ht[cur - 1] == hj_prev && target[cur - 1] == tok_prev;
+        if (on && h_cur == hj) {
+            const bool shadowed = has_prev && cur > 0 && h_before == hj_prev && tok_before == tok_prev;
             first_of_its_stretch = !shadowed;
         }
         unsigned long long todo = __ballot(first_of_its_stretch);
@@ -164,7 +212,7 @@ __global__ __launch_bounds__(kMatchThreads) void match_seed_kernel(
             const int32_t sj = (int32_t)(j - lane + src);
             claim_stretch(target, n_t, cand, n_c, si, sj, ws.best, lane);
         }
-        cur = cur >= 0 ? ws.next[cur] : -1;
+        cur = nxt;
     }
 }
 
@@ -333,11 +381,10 @@ extern "C" kvs_status kvs_match_tokens(const int32_t *target, int64_t n_target, 
     MatchWs ws;
     const size_t need = carve(&ws, (char *)workspace, n_target, n_candidate, bits);
     if (workspace_bytes < need) return fail(KVS_EWORKSPACE, "kvs_match_tokens: workspace of %zu bytes, %zu needed", workspace_bytes, need);
-    const int64_t biggest = n_target > n_candidate ? n_target : n_candidate;
-    const int64_t table = (int64_t)1 << bits;
-    const unsigned hash_blocks = (unsigned)(((biggest > table ? biggest : table) + kMatchThreads - 1) / kMatchThreads);
+    const Modulus md = {(uint64_t)hash_modulus, ~0ull / (uint64_t)hash_modulus};
+    const unsigned hash_blocks = (unsigned)((wt + kMatchThreads - 1) / kMatchThreads + (wc + kMatchThreads - 1) / kMatchThreads);
     hipLaunchKernelGGL(match_hash_kernel, dim3(hash_blocks), dim3(kMatchThreads), 0, hs, target, n_target, candidate, n_candidate,
-                       (int)window, hash_base, hash_modulus, bits, ws);
+                       (int)window, hash_base, md, bits, ws);
     hipLaunchKernelGGL(match_insert_kernel, dim3((unsigned)((wt + kMatchThreads - 1) / kMatchThreads)), dim3(kMatchThreads), 0, hs, wt, bits, ws);
     hipLaunchKernelGGL(match_seed_kernel, dim3((unsigned)((wc + kMatchThreads - 1) / kMatchThreads)), dim3(kMatchThreads), 0, hs,
                        target, n_target, candidate, n_candidate, (int)window, bits, ws);

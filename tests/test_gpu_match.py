@@ -95,6 +95,17 @@ def test_match_degenerate_inputs():
     assert check(t[:300], t[100:116], 16) == 16
 
 
+def test_match_long_windows():
+    """windows of 700 and 800 tokens: the hash is taken out of staged tiles up to 768 tokens, straight from memory beyond"""
+    rng = np.random.default_rng(12)
+    c = rng.integers(0, 1000, size=3000)
+    t = rng.integers(0, 1000, size=2500)
+    t[300:1400] = c[1500:2600]
+    for w in (700, 768, 769, 800):
+        say(f"match: window {w}")
+        assert check(t, c, w) == 1100
+
+
 def test_match_periodic_text():
     """a phrase repeated many times in both sequences: many equal windows per hash, long chains"""
     say("match: periodic sequences")
