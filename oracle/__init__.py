@@ -53,7 +53,7 @@ def lib() -> ctypes.CDLL:
         _lib = ctypes.CDLL(build())
         for name in ("kvso_deviation", "kvso_alpha_prefill", "kvso_select_topk", "kvso_scatter_kv",
                      "kvso_partial_attention", "kvso_decode_check", "kvso_first_order_impact", "kvso_exact_impact",
-                     "kvso_window_hash", "kvso_match_tokens", "kvso_schedule", "kvso_max_threads"):
+                     "kvso_window_hash", "kvso_match_tokens", "kvso_schedule", "kvso_project_qkv", "kvso_max_threads"):
             getattr(_lib, name).restype = ctypes.c_int
     return _lib
 
@@ -246,6 +246,29 @@ def schedule(hit_rate) -> np.ndarray:
     order = np.zeros((h.shape[0],), dtype=np.int32)
     _check(lib().kvso_schedule(_p(h), ctypes.c_int32(h.shape[0]), _p(order)), "schedule")
     return order
+
+
+def project_qkv(x, w, n_q_heads: int, n_kv_heads: int, head_dim: int, rows=None, pos=None, rope=None):
+    """App. D.1: a layer's Q, K, V of the selected tokens (hidden states ``x`` [n_tokens, hidden], weight
+    ``w`` [(n_q_heads + 2 n_kv_heads) head_dim, hidden]), rotary factors from ``rope`` [positions, head_dim/2, 2]
+    applied to Q and K when given.  Returns fp64 arrays (q, k, v), unrounded."""
+    xa, wa = _as_np(x), _as_np(w)
+    code = _dtype_code(xa)
+    if _dtype_code(wa) != code:
+        raise TypeError("x and w must have one dtype")
+    n_tokens, hidden = xa.shape
+    ra = None if rows is None else np.ascontiguousarray(np.asarray(rows, dtype=np.int32))
+    pa = None if pos is None else np.ascontiguousarray(np.asarray(pos, dtype=np.int32))
+    n_sel = n_tokens if ra is None else ra.shape[0]
+    rp = None if rope is None else np.ascontiguousarray(np.asarray(rope, dtype=np.float32))
+    q = np.zeros((n_sel, n_q_heads, head_dim), dtype=np.float64)
+    k = np.zeros((n_sel, n_kv_heads, head_dim), dtype=np.float64)
+    v = np.zeros((n_sel, n_kv_heads, head_dim), dtype=np.float64)
+    sh = _shape(n_q_heads, n_kv_heads, head_dim, code)
+    _check(lib().kvso_project_qkv(ctypes.byref(sh), ctypes.c_int32(hidden), _p(xa), ctypes.c_int64(n_tokens), _p(ra), _p(pa),
+                                  ctypes.c_int64(n_sel), _p(wa), _p(rp), ctypes.c_int64(0 if rp is None else rp.shape[0]),
+                                  _p(q), _p(k), _p(v)), "project_qkv")
+    return q, k, v
 
 
 def decode_check(q_new, k_cache, dev_v, reused, scale: float, ctx_off, ctx_len, k_req,

@@ -24,6 +24,10 @@
  *   kvso_match_tokens      App. E Alg. 3: token-sequence matching over a hash index of the
  *                          target's windows, candidate windows in ascending order, matches
  *                          extended token by token, a target position matched at most once
+ *   kvso_project_qkv       App. D.1 (the tokens selected in an early layer are the ones recomputed in
+ *                          the later layers): a later layer's Q/K/V of the selected tokens, i.e. its
+ *                          projection of their hidden states, with the rotary position factors of
+ *                          the models the paper evaluates applied to Q and K
  *   kvso_schedule          Sec. 4.3 Alg. 2: the queue sorted by cache hit rate, descending; the
  *                          first N requests form the next batch
  *
@@ -650,6 +654,71 @@ int kvso_match_tokens(const int32_t *target, int64_t n_target, const int32_t *ca
     *n_matches = count;
     free(ht); free(hc); free(index); free(matched);
     return 0;
+}
+
+/* ---------------------------------------------------------------------------------------------
+ * Recomputing the selected tokens in a later layer (App. D.1): row m of the output is the layer's
+ * projection of the hidden state of selected token m,
+ *     y[m, f] = sum_c x[rows[m], c] * w[f, c]          f over (n_q_heads + 2 n_kv_heads) * head_dim features,
+ * (w is stored as PyTorch stores a Linear weight: one row per output feature), split into Q, K, V by
+ * heads.  With a rotary table, channel pair (c, c + head_dim/2) of every Q and K head is turned by the
+ * angle the table holds for the token's position p = pos[m] and frequency c:
+ *     out[c]              = y[c] cos - y[c + head_dim/2] sin
+ *     out[c + head_dim/2] = y[c + head_dim/2] cos + y[c] sin,      (cos, sin) = rope[p, c, 0..1];
+ * V is not turned.  The table is an input (the caller decides base and scaling of the frequencies).
+ *
+ * x [n_tokens, hidden], w [(n_q_heads + 2 n_kv_heads) * head_dim, hidden]: dtype of the shape
+ * rows [n_sel] int32 or NULL (row m of x is token m), pos [n_sel] int32 (read only with a table)
+ * rope [rope_positions, head_dim/2, 2] fp32 or NULL
+ * q_out [n_sel, n_q_heads, head_dim], k_out, v_out [n_sel, n_kv_heads, head_dim]: fp64, not rounded
+ */
+int kvso_project_qkv(const kvso_shape *sh, int32_t hidden, const void *x, int64_t n_tokens,
+                     const int32_t *rows, const int32_t *pos, int64_t n_sel, const void *w,
+                     const float *rope, int64_t rope_positions,
+                     double *q_out, double *k_out, double *v_out)
+{
+    if (!shape_ok(sh) || hidden <= 0 || n_tokens < 0 || n_sel < 0 || (sh->head_dim & 1)) return 1;
+    if (n_sel == 0) return 0;
+    if (!x || !w || !q_out || !k_out || !v_out || (rope && !pos)) return 1;
+    const int d = sh->head_dim, hq = sh->n_q_heads, hk = sh->n_kv_heads, half = d / 2;
+    const int64_t features = (int64_t)(hq + 2 * hk) * d;
+    for (int64_t m = 0; m < n_sel; ++m) {
+        const int64_t r = rows ? rows[m] : m;
+        if (r < 0 || r >= n_tokens) return 1;
+        if (rope && (pos[m] < 0 || pos[m] >= rope_positions)) return 1;
+    }
+    int bad = 0;
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < n_sel; ++m) {
+        const int64_t r = rows ? rows[m] : m;
+        double *y = (double *)malloc((size_t)features * sizeof(double));
+        if (!y) { bad = 1; continue; }
+        for (int64_t f = 0; f < features; ++f) {
+            double acc = 0.0;
+            for (int32_t c = 0; c < hidden; ++c) acc += ld(x, sh->dtype, r * hidden + c) * ld(w, sh->dtype, f * hidden + c);
+            y[f] = acc;
+        }
+        for (int h = 0; h < hq + 2 * hk; ++h) {
+            double *yh = y + (int64_t)h * d;
+            double *dst = h < hq ? q_out + (m * hq + h) * d
+                        : h < hq + hk ? k_out + (m * hk + (h - hq)) * d
+                                      : v_out + (m * hk + (h - hq - hk)) * d;
+            const int turned = rope && h < hq + hk;
+            for (int c = 0; c < half; ++c) {
+                if (turned) {
+                    const double cs = (double)rope[((int64_t)pos[m] * half + c) * 2 + 0];
+                    const double sn = (double)rope[((int64_t)pos[m] * half + c) * 2 + 1];
+                    dst[c] = yh[c] * cs - yh[c + half] * sn;
+                    dst[c + half] = yh[c + half] * cs + yh[c] * sn;
+                } else {
+                    dst[c] = yh[c];
+                    dst[c + half] = yh[c + half];
+                }
+            }
+        }
+        free(y);
+    }
+    return bad;
 }
 
 /* ---------------------------------------------------------------------------------------------

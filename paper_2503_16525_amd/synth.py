@@ -265,3 +265,24 @@ def make_token_streams(w: Workload, seed: int = 0, window: int = 16, unique_cand
         source[a:e] = np.arange(c, c + L)
         span_len[a:e] = L
     return dict(target=target, candidate=candidate, source=source, span_len=span_len)
+
+
+def make_rope_table(n_positions: int, head_dim: int, theta: float = 500000.0) -> np.ndarray:
+    """fp32 [n_positions, head_dim/2, 2]: cos and sin of position * theta^(-2c/head_dim), the rotary factors
+    of the Llama / Qwen / Yi families (angles taken in fp64, rounded once).  An input table, as serving
+    stacks keep it; the projection call and the oracle both read it."""
+    half = head_dim // 2
+    inv_freq = theta ** (-np.arange(half, dtype=np.float64) * 2.0 / head_dim)
+    ang = np.arange(n_positions, dtype=np.float64)[:, None] * inv_freq[None, :]
+    return np.stack([np.cos(ang), np.sin(ang)], axis=-1).astype(np.float32)
+
+
+def make_projection(w: Workload, hidden: int, layer: int = 0, device: str = "cpu"):
+    """Hidden states [n_ctx, hidden] ~ N(0,1) and a fused QKV weight [(H_q + 2 H_kv) d, hidden] ~ N(0, 1/hidden)
+    in the workload's dtype (the marginals of the projected Q/K/V are those of the other generators)."""
+    gen = torch.Generator(device=device)
+    gen.manual_seed(layer_seed(w, layer, salt=23))
+    x = torch.randn((w.n_ctx, hidden), generator=gen, device=device).to(w.torch_dtype)
+    feats = (w.n_q_heads + 2 * w.n_kv_heads) * w.head_dim
+    wt = (torch.randn((feats, hidden), generator=gen, device=device) / math.sqrt(hidden)).to(w.torch_dtype)
+    return x, wt
