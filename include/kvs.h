@@ -336,6 +336,36 @@ KVS_API kvs_status kvs_match_tokens(const int32_t *target, int64_t n_target,
                                     int64_t *n_matches, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * A later layer's Q, K and V of the selected tokens (App. D.1: the tokens picked in an early layer are
+ * the ones recomputed in the layers after it; their index list is simply passed on to this call,
+ * kvs_scatter_kv and kvs_partial_attention of those layers).  Recomputing a token in a layer starts with
+ * the layer's projection of its hidden state:
+ *     y[m, f] = sum_c x[x_rows[m], c] * w_qkv[f, c],   f over (n_q_heads + 2 n_kv_heads) * head_dim features
+ * in the order all Q heads, all K heads, all V heads.  With a rotary table, channel pair
+ * (c, c + head_dim/2) of every Q and K head is turned by the table's angle for position sel_pos[m]:
+ *     out[c] = y[c] cos - y[c + head_dim/2] sin,   out[c + head_dim/2] = y[c + head_dim/2] cos + y[c] sin
+ * (the convention of the Llama / Qwen / Yi families the paper evaluates; the paper itself takes Q, K, V
+ * as given).  One launch: gather, bf16 matrix product with fp32 accumulation, rotation in fp32, one
+ * rounding to bf16 on the way out.
+ *
+ * x        [dev] bf16 [n_tokens, hidden] hidden states
+ * x_rows   [dev] int32[n_sel] row of x for each selected token, or NULL (row m of x is selected token m:
+ *          from the second recomputed layer on only the selected tokens have hidden states)
+ * sel_pos  [dev] int32[n_sel] positions of the selected tokens (read only with a rotary table)
+ * w_qkv    [dev] bf16 [(n_q_heads + 2 n_kv_heads) * head_dim, hidden], one row per output feature
+ * rope     [dev] fp32 [rope_positions, head_dim/2, 2] = (cos, sin) per position and channel pair, or NULL
+ * q_out    [dev] bf16 [n_sel, n_q_heads, head_dim]; k_out, v_out [dev] bf16 [n_sel, n_kv_heads, head_dim]:
+ *          the layouts kvs_partial_attention and kvs_scatter_kv take
+ * Built for bf16, head_dim 128, hidden a multiple of 32, an even number of heads in all, x and w below
+ * 4 GiB each (KVS_EUNSUPPORTED otherwise).  Tensors 16-byte aligned.  No workspace.  Row indices and
+ * positions outside their ranges are clamped (memory safety only).
+ */
+KVS_API kvs_status kvs_project_qkv(const kvs_shape *shape, int32_t hidden, const void *x, int64_t n_tokens,
+                                   const int32_t *x_rows, const int32_t *sel_pos, int64_t n_sel,
+                                   const void *w_qkv, const float *rope, int64_t rope_positions,
+                                   void *q_out, void *k_out, void *v_out, void *stream);
+
+/*
  * Workspace a call needs, in bytes, for the given problem.  `call` is "select_topk",
  * "partial_attention", "decode_check", "attn_colsum", "first_order_impact" or "match_tokens" (anything else
  * returns 0).  n_rows_total is the total number of score / cache rows the call will see (match_tokens: the

@@ -22,7 +22,7 @@ SCORE_V, SCORE_KV = 0, 1
 OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP = 0, 1, 2, 3, 4
 
 EXPORTS = ("kvs_deviation", "kvs_deviation_topk", "kvs_select_topk", "kvs_select_topk_static", "kvs_scatter_kv", "kvs_partial_attention",
-           "kvs_decode_check", "kvs_attn_colsum", "kvs_first_order_impact", "kvs_match_tokens", "kvs_workspace_size", "kvs_strerror", "kvs_last_error", "kvs_version")
+           "kvs_decode_check", "kvs_attn_colsum", "kvs_first_order_impact", "kvs_match_tokens", "kvs_project_qkv", "kvs_workspace_size", "kvs_strerror", "kvs_last_error", "kvs_version")
 
 
 class KvsError(RuntimeError):
@@ -62,9 +62,10 @@ def load(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.kvs_attn_colsum.argtypes = [sp, i64, vp, vp, f32, vp, vp, sz, vp]
     lib.kvs_first_order_impact.argtypes = [sp, i64, vp, vp, vp, vp, vp, vp, vp, vp, f32, vp, vp, vp, vp, sz, vp]
     lib.kvs_match_tokens.argtypes = [vp, i64, vp, i64, i32, ctypes.c_uint32, ctypes.c_uint32, vp, vp, vp, vp, vp, sz, vp]
+    lib.kvs_project_qkv.argtypes = [sp, i32, vp, i64, vp, vp, i64, vp, vp, i64, vp, vp, vp, vp]
     lib.kvs_workspace_size.argtypes = [ctypes.c_char_p, sp, i32, i64, i64]
     for n in ("kvs_deviation", "kvs_deviation_topk", "kvs_select_topk", "kvs_select_topk_static", "kvs_scatter_kv", "kvs_partial_attention",
-              "kvs_decode_check", "kvs_attn_colsum", "kvs_first_order_impact", "kvs_match_tokens"):
+              "kvs_decode_check", "kvs_attn_colsum", "kvs_first_order_impact", "kvs_match_tokens", "kvs_project_qkv"):
         getattr(lib, n).restype = ctypes.c_int
     lib.kvs_workspace_size.restype = sz
     lib.kvs_strerror.argtypes = [ctypes.c_int]
@@ -229,6 +230,13 @@ def kvs_match_tokens(target, candidate, window: int, hash_base: int, hash_modulu
                                  _ptr(target_matches, torch.int32), _ptr(candidate_matches, torch.int32),
                                  _ptr(n_matches, torch.int64), _ptr(workspace), ws_bytes, _stream(stream))
     _check(rc, "kvs_match_tokens")
+
+
+def kvs_project_qkv(shape: Shape, x, x_rows, sel_pos, n_sel: int, w_qkv, rope, q_out, k_out, v_out, stream=None) -> None:
+    rc = load().kvs_project_qkv(ctypes.byref(shape), x.shape[1], _ptr(x), x.shape[0], _ptr(x_rows, torch.int32),
+                                _ptr(sel_pos, torch.int32), n_sel, _ptr(w_qkv), _ptr(rope, torch.float32),
+                                rope.shape[0] if rope is not None else 0, _ptr(q_out), _ptr(k_out), _ptr(v_out), _stream(stream))
+    _check(rc, "kvs_project_qkv")
 
 
 def shape_of(workload) -> Shape:

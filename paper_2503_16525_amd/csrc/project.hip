@@ -1,0 +1,251 @@
+// kvs_project_qkv: a later layer's Q, K and V of the selected tokens (App. D.1: the tokens picked in an
+// early layer are the ones recomputed in the layers after it).  Recomputing a token's Q/K/V in a layer is
+// that layer's projection of its hidden state; the models the paper evaluates turn Q and K by rotary
+// position factors, which are applied here from a caller-supplied table while the results are still in
+// registers.  One launch: gather of the selected hidden rows, the bf16 matrix product on the matrix
+// cores, the rotation, the split into the Q / K / V tensors.
+//
+// Shape of the product: out[token, feature] = sum_c x[rows[token], c] * w[feature, c].  Both operands
+// are contiguous along c, the contraction index, which is what the matrix core wants from both sides
+// (8 consecutive c per lane): neither needs a transposing read.
+//
+// Tiling.  A workgroup owns 256 features x 256 tokens; its four waves 128 x 128 each (one wave per
+// SIMD, the 16 accumulator tiles of 32 x 32 fill the accumulation registers), so every 16-byte
+// operand fetched from LDS feeds four MFMAs.  The contraction runs in steps of 32; a step's two
+// tiles (256 rows x 64 bytes each) are staged from global memory straight into LDS by buffer loads
+// with the LDS flag -- the gather costs nothing, every lane supplies the address of its own row --
+// into a ring of four stages, three steps ahead of their use, one barrier per step.  Rows are 64
+// bytes in LDS; the 16-byte piece p of row r sits at position p ^ ((r >> 1) & 3), so the eight lanes
+// an operand read serves together hit eight different 16-byte columns.
+//
+// The features are the MFMA's rows and the tokens its columns: a lane then ends up with four
+// consecutive features of one token per accumulator quad, so the rotation pairs (c, c + 64) sit in
+// the same lane (feature blocks fb and fb + 2 of the wave's head) and the results leave as 8-byte
+// stores.
+//
+// Launch order.  Workgroup b runs on XCD b % 8; tiles are numbered feature-tile-major and XCD x takes
+// a contiguous eighth of them, so the workgroups that share an L2 share weight tiles.
+#include "kvs_internal.h"
+
+namespace kvs {
+namespace {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
+
+constexpr int PD = 128;                 // head_dim
+constexpr int PBM = 256;                // tokens per workgroup tile
+constexpr int PBN = 256;                // features per workgroup tile (two heads)
+constexpr int PBK = 32;                 // contraction step
+constexpr int PSTAGES = 4;
+constexpr int PNT = 256;
+constexpr int PROW_B = PBK * 2;         // bytes of a tile row in LDS
+constexpr int PTILE_B = 256 * PROW_B;   // one operand tile: 16 KiB
+constexpr int PSTAGE_B = 2 * PTILE_B;   // weights, then tokens
+constexpr int PLDS_BYTES = PSTAGES * PSTAGE_B;
+constexpr int PXCDS = 8;
+
+__device__ __forceinline__ bf16x8 as_frag(u32x4_t v) { return __builtin_bit_cast(bf16x8, v); }
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
+{
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    f32x2 f = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));
+}
+
+__global__ __launch_bounds__(PNT, 1) void project_qkv_kernel(
+    int n_q_heads, int n_kv_heads, int hidden, const uint16_t *__restrict__ x, int64_t n_tokens,
+    const int32_t *__restrict__ x_rows, const int32_t *__restrict__ sel_pos, int n_sel,
+    const uint16_t *__restrict__ w, const float *__restrict__ rope, int rope_positions,
+    uint16_t *__restrict__ q_out, uint16_t *__restrict__ k_out, uint16_t *__restrict__ v_out,
+    int tiles_m, int total_tiles, int tiles_per_xcd)
+{
+    extern __shared__ __attribute__((aligned(16))) char plds[];
+    const int tid = threadIdx.x, lane = tid & 63, ln = lane & 31, hf = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wf = wave & 1, wt = wave >> 1;      // which 128 features / 128 tokens of the tile
+    const int tile = (int)(blockIdx.x % PXCDS) * tiles_per_xcd + (int)(blockIdx.x / PXCDS);
+    if (tile >= total_tiles) return;              // uniform: the padding of the last XCD's range
+    const int tile_n = tile / tiles_m, tile_m = tile - tile_n * tiles_m;
+    const int m0 = tile_m * PBM, n0 = tile_n * PBN;
+    const int nk = hidden / PBK;
+
+    // ---- staging: one instruction moves 64 x 16 bytes = 16 tile rows; a wave stages rows
+    // 64 w .. 64 w + 63 of the weight tile and of the token tile, 8 instructions per step
+    const uint32_t row_bytes = (uint32_t)hidden * 2u;
+    const int st_row = lane >> 2, st_pos = lane & 3;
+    uint32_t voff_w[4], voff_x[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int r = 64 * wave + 16 * i + st_row;                   // row of the tile
+        const uint32_t piece = (uint32_t)(st_pos ^ ((r >> 1) & 3)) * 16u;
+        voff_w[i] = (uint32_t)(n0 + r) * row_bytes + piece;
+        const int t = min(m0 + r, n_sel - 1);                         // rows past the end repeat the last token (never stored)
+        int64_t xr = x_rows ? (int64_t)x_rows[t] : (int64_t)t;
+        xr = min(max(xr, (int64_t)0), n_tokens - 1);                  // memory safety; the caller guarantees the range
+        voff_x[i] = (uint32_t)xr * row_bytes + piece;
+    }
+    const int n_features = (n_q_heads + 2 * n_kv_heads) * PD;
+    auto make_rsrc = [&](const uint16_t *base, uint64_t bytes) -> u32x4_t {
+        const uint64_t a = reinterpret_cast<uint64_t>(base);
+        u32x4_t r = {(uint32_t)a, (uint32_t)(a >> 32) & 0xffffu, (uint32_t)bytes, 0x00020000u};
+        r.x = __builtin_amdgcn_readfirstlane(r.x);
+        r.y = __builtin_amdgcn_readfirstlane(r.y);
+        r.z = __builtin_amdgcn_readfirstlane(r.z);
+        return r;
+    };
+    const u32x4_t wrs = make_rsrc(w, (uint64_t)n_features * row_bytes);
+    const u32x4_t xrs = make_rsrc(x, (uint64_t)n_tokens * row_bytes);
+    const uint32_t lds_base = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)plds);
+    // the offsets above came through ordinary loads: none may be outstanding when the counted waits begin
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    auto stage_1k = [&](const u32x4_t &rs, uint32_t lds_dst, uint32_t voff, uint32_t soff) {
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                     :: "s"(lds_dst), "v"(voff), "s"(rs), "s"(soff));
+    };
+    // contraction step `step` into ring slot step % PSTAGES; steps past the end repeat the last one (their slot is never read)
+    auto stage = [&](int step) {
+        const int ks = min(step, nk - 1);
+        const uint32_t soff = __builtin_amdgcn_readfirstlane((uint32_t)ks * (uint32_t)(PBK * 2));
+        const uint32_t slot = lds_base + (uint32_t)((step & (PSTAGES - 1)) * PSTAGE_B) + (uint32_t)(64 * wave) * PROW_B;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            stage_1k(wrs, __builtin_amdgcn_readfirstlane(slot + (uint32_t)(16 * i * PROW_B)), voff_w[i], soff);
+            stage_1k(xrs, __builtin_amdgcn_readfirstlane(slot + (uint32_t)(PTILE_B + 16 * i * PROW_B)), voff_x[i], soff);
+        }
+    };
+
+    // ---- operand reads: lane (ln, hf) reads piece 2 ks + hf of row (block base + ln)
+    const uint32_t rd_off = (uint32_t)(ln * PROW_B + ((hf ^ ((ln >> 1) & 3)) * 16));
+    auto read_frag = [&](uint32_t tile_off, int block, int ks) -> u32x4_t {      // tile_off: byte offset of the operand tile
+        return *reinterpret_cast<const u32x4_t *>(plds + tile_off + (uint32_t)(block * 32 * PROW_B) + (rd_off ^ (uint32_t)(32 * ks)));
+    };
+
+    floatx16 acc[4][4];     // [feature block][token block]
+#pragma unroll
+    for (int fb = 0; fb < 4; ++fb)
+#pragma unroll
+        for (int tb = 0; tb < 4; ++tb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[fb][tb][r] = 0.f;
+
+    stage(0);
+    stage(1);
+    stage(2);
+    for (int j = 0; j < nk; ++j) {
+        // this wave's loads of step j have landed (two younger steps, 8 instructions each, may be in flight);
+        // after the barrier every wave's have, and every wave is done reading the slot step j+3 goes to
+        asm volatile("s_waitcnt vmcnt(16)\n\ts_barrier" ::: "memory");
+        const uint32_t so = (uint32_t)((j & (PSTAGES - 1)) * PSTAGE_B);
+        const uint32_t w_tile = so + (uint32_t)(wf * 128 * PROW_B), x_tile = so + (uint32_t)(PTILE_B + wt * 128 * PROW_B);
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            u32x4_t a[4], b[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { a[i] = read_frag(w_tile, i, ks); b[i] = read_frag(x_tile, i, ks); }
+            if (ks == 0) stage(j + 3);
+#pragma unroll
+            for (int fb = 0; fb < 4; ++fb)
+#pragma unroll
+                for (int tb = 0; tb < 4; ++tb)
+                    acc[fb][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(a[fb]), as_frag(b[tb]), acc[fb][tb], 0, 0, 0);
+        }
+    }
+    // nothing may still be on its way into LDS when the workgroup ends
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+
+    // ---- epilogue: rotate, convert, store -----------------------------------------------------------
+    // entry r of acc[fb][tb]: feature 32 fb + 8 (r >> 2) + 4 hf + (r & 3) of the wave's head, token 32 tb + ln
+    const int head = n0 / PD + wf;
+    uint16_t *dst;
+    int heads_of_dst, h_local;
+    if (head < n_q_heads) { dst = q_out; heads_of_dst = n_q_heads; h_local = head; }
+    else if (head < n_q_heads + n_kv_heads) { dst = k_out; heads_of_dst = n_kv_heads; h_local = head - n_q_heads; }
+    else { dst = v_out; heads_of_dst = n_kv_heads; h_local = head - n_q_heads - n_kv_heads; }
+    const bool turned = rope != nullptr && head < n_q_heads + n_kv_heads;
+#pragma unroll
+    for (int tb = 0; tb < 4; ++tb) {
+        const int t = m0 + 128 * wt + 32 * tb + ln;
+        if (t >= n_sel) continue;
+        uint16_t *orow = dst + ((int64_t)t * heads_of_dst + h_local) * PD;
+        if (turned) {
+            int p = sel_pos[t];
+            p = min(max(p, 0), rope_positions - 1);          // memory safety; the caller guarantees the range
+            const float *tab = rope + (int64_t)p * PD;       // [64][2]
+#pragma unroll
+            for (int fb = 0; fb < 2; ++fb)
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    const int c0 = 32 * fb + 8 * r4 + 4 * hf;
+                    const float4 cs01 = *reinterpret_cast<const float4 *>(tab + 2 * c0);
+                    const float4 cs23 = *reinterpret_cast<const float4 *>(tab + 2 * c0 + 4);
+                    const float cs[4] = {cs01.x, cs01.z, cs23.x, cs23.z}, sn[4] = {cs01.y, cs01.w, cs23.y, cs23.w};
+                    float lo[4], hi[4];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const float y1 = acc[fb][tb][4 * r4 + i], y2 = acc[fb + 2][tb][4 * r4 + i];
+                        lo[i] = y1 * cs[i] - y2 * sn[i];
+                        hi[i] = y2 * cs[i] + y1 * sn[i];
+                    }
+                    *reinterpret_cast<uint2 *>(orow + c0) = make_uint2(pack_bf16x2(lo[0], lo[1]), pack_bf16x2(lo[2], lo[3]));
+                    *reinterpret_cast<uint2 *>(orow + c0 + 64) = make_uint2(pack_bf16x2(hi[0], hi[1]), pack_bf16x2(hi[2], hi[3]));
+                }
+        } else {
+#pragma unroll
+            for (int fb = 0; fb < 4; ++fb)
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    const int c0 = 32 * fb + 8 * r4 + 4 * hf;
+                    *reinterpret_cast<uint2 *>(orow + c0) = make_uint2(pack_bf16x2(acc[fb][tb][4 * r4 + 0], acc[fb][tb][4 * r4 + 1]),
+                                                                       pack_bf16x2(acc[fb][tb][4 * r4 + 2], acc[fb][tb][4 * r4 + 3]));
+                }
+        }
+    }
+}
+
+} // namespace
+} // namespace kvs
+
+extern "C" kvs_status kvs_project_qkv(const kvs_shape *shape, int32_t hidden, const void *x, int64_t n_tokens,
+                                      const int32_t *x_rows, const int32_t *sel_pos, int64_t n_sel,
+                                      const void *w_qkv, const float *rope, int64_t rope_positions,
+                                      void *q_out, void *k_out, void *v_out, void *stream)
+{
+    using namespace kvs;
+    kvs_status st = check_shape(shape);
+    if (st != KVS_OK) return st;
+    if (n_tokens < 0 || n_sel < 0) return fail(KVS_EINVAL, "kvs_project_qkv: negative size");
+    if (shape->dtype != KVS_BF16 || shape->head_dim != PD)
+        return fail(KVS_EUNSUPPORTED, "kvs_project_qkv: bf16 with head_dim 128 is built");
+    if ((shape->n_q_heads + 2 * shape->n_kv_heads) % 2 != 0)
+        return fail(KVS_EUNSUPPORTED, "kvs_project_qkv: an odd number of heads in all (a workgroup takes two)");
+    if (hidden < PBK || hidden % PBK != 0) return fail(KVS_EUNSUPPORTED, "kvs_project_qkv: hidden size %d (multiples of %d)", hidden, PBK);
+    if (n_sel == 0) return KVS_OK;
+    if (n_tokens == 0) return fail(KVS_EINVAL, "kvs_project_qkv: tokens selected from an empty x");
+    if (!x_rows && n_sel > n_tokens) return fail(KVS_EINVAL, "kvs_project_qkv: n_sel %lld exceeds the rows of x", (long long)n_sel);
+    if (!x || !w_qkv || !q_out || !k_out || !v_out) return fail(KVS_EINVAL, "kvs_project_qkv: NULL tensor pointer");
+    if (rope && (!sel_pos || rope_positions <= 0)) return fail(KVS_EINVAL, "kvs_project_qkv: a rotary table needs sel_pos and its own length");
+    if (!aligned16(x) || !aligned16(w_qkv) || !aligned16(q_out) || !aligned16(k_out) || !aligned16(v_out) || (rope && !aligned16(rope)))
+        return fail(KVS_EINVAL, "kvs_project_qkv: tensors must be 16-byte aligned");
+    const int64_t features = (int64_t)(shape->n_q_heads + 2 * shape->n_kv_heads) * PD;
+    // rows are addressed with 32-bit byte offsets
+    if (n_tokens * hidden * 2 >= ((int64_t)1 << 32) || features * hidden * 2 >= ((int64_t)1 << 32))
+        return fail(KVS_EUNSUPPORTED, "kvs_project_qkv: x or w of 4 GiB or more");
+    if (n_sel > 0x7fffffff || rope_positions > 0x7fffffff) return fail(KVS_EUNSUPPORTED, "kvs_project_qkv: too many tokens");
+    static DeviceOnce attr_once;
+    st = once_per_device(attr_once, [] {
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&project_qkv_kernel),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, PLDS_BYTES);
+        return e == hipSuccess ? KVS_OK : fail(KVS_EHIP, "kvs_project_qkv: hipFuncSetAttribute: %s", hipGetErrorString(e));
+    });
+    if (st != KVS_OK) return st;
+    const int64_t tiles_m = (n_sel + PBM - 1) / PBM, tiles_n = features / PBN, total = tiles_m * tiles_n;
+    const int64_t per_xcd = (total + PXCDS - 1) / PXCDS;
+    if (per_xcd * PXCDS > 0x7fffffff) return fail(KVS_EUNSUPPORTED, "kvs_project_qkv: too many tiles");
+    hipLaunchKernelGGL(project_qkv_kernel, dim3((unsigned)(per_xcd * PXCDS)), dim3(PNT), PLDS_BYTES, (hipStream_t)stream,
+                       shape->n_q_heads, shape->n_kv_heads, (int)hidden, (const uint16_t *)x, n_tokens, x_rows, sel_pos, (int)n_sel,
+                       (const uint16_t *)w_qkv, rope, (int)rope_positions, (uint16_t *)q_out, (uint16_t *)k_out, (uint16_t *)v_out,
+                       (int)tiles_m, (int)total, (int)per_xcd);
+    return check_launch("kvs_project_qkv");
+}
