@@ -356,7 +356,7 @@ KVS_API kvs_status kvs_match_tokens(const int32_t *target, int64_t n_target,
  * rope     [dev] fp32 [rope_positions, head_dim/2, 2] = (cos, sin) per position and channel pair, or NULL
  * q_out    [dev] bf16 [n_sel, n_q_heads, head_dim]; k_out, v_out [dev] bf16 [n_sel, n_kv_heads, head_dim]:
  *          the layouts kvs_partial_attention and kvs_scatter_kv take
- * Built for bf16, head_dim 128, hidden a multiple of 32, an even number of heads in all, x and w below
+ * Built for bf16, head_dim 128, hidden a multiple of 64, an even number of heads in all, x and w below
  * 4 GiB each (KVS_EUNSUPPORTED otherwise).  Tensors 16-byte aligned.  No workspace.  Row indices and
  * positions outside their ranges are clamped (memory safety only).
  */

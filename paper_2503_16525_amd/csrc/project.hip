@@ -14,9 +14,10 @@
 // operand fetched from LDS feeds four MFMAs.  The contraction runs in steps of 32; a step's two
 // tiles (256 rows x 64 bytes each) are staged from global memory straight into LDS by buffer loads
 // with the LDS flag -- the gather costs nothing, every lane supplies the address of its own row --
-// into a ring of four stages, three steps ahead of their use, one barrier per step.  Rows are 64
-// bytes in LDS; the 16-byte piece p of row r sits at position p ^ ((r >> 1) & 3), so the eight lanes
-// an operand read serves together hit eight different 16-byte columns.
+// into a ring of five stages, two to four steps ahead of their use, one barrier per step.  Rows are 64
+// bytes in LDS; the 16-byte pieces of a row are permuted per row (row_swizzle) so that the lanes an operand
+// read serves together never share a bank (the plain layout and a swizzle by (r >> 1) & 3 both measured
+// one conflict cycle per active LDS cycle).
 //
 // The features are the MFMA's rows and the tokens its columns: a lane then ends up with four
 // consecutive features of one token per accumulator quad, so the rotation pairs (c, c + 64) sit in
@@ -26,6 +27,8 @@
 // Launch order.  Workgroup b runs on XCD b % 8; tiles are numbered feature-tile-major and XCD x takes
 // a contiguous eighth of them, so the workgroups that share an L2 share weight tiles.
 #include "kvs_internal.h"
+
+#include <type_traits>
 
 namespace kvs {
 namespace {
@@ -37,13 +40,25 @@ constexpr int PD = 128;                 // head_dim
 constexpr int PBM = 256;                // tokens per workgroup tile
 constexpr int PBN = 256;                // features per workgroup tile (two heads)
 constexpr int PBK = 32;                 // contraction step
-constexpr int PSTAGES = 4;
+#ifndef KVS_PROJ_STAGES
+#define KVS_PROJ_STAGES 5
+#endif
+#ifndef KVS_PROJ_CACHE
+#define KVS_PROJ_CACHE ""
+#endif
+constexpr int PSTAGES = KVS_PROJ_STAGES;   // ring slots of 32 KiB: 5 fill the 160 KiB of a compute unit
 constexpr int PNT = 256;
 constexpr int PROW_B = PBK * 2;         // bytes of a tile row in LDS
 constexpr int PTILE_B = 256 * PROW_B;   // one operand tile: 16 KiB
 constexpr int PSTAGE_B = 2 * PTILE_B;   // weights, then tokens
 constexpr int PLDS_BYTES = PSTAGES * PSTAGE_B;
 constexpr int PXCDS = 8;
+
+// position of the 16-byte piece p of tile row r inside the row's 64 bytes: p ^ row_swizzle(r).  Rows are 64
+// bytes apart, so rows r, r+4, r+8, r+12 meet in the same quarter of a 256-byte bank line and rows r, r+2,
+// r+4, r+6 in the same half of a 128-byte one: the two bits below are a one-to-one image of (r3, r2) and of
+// (r2, r1) alike, so lanes reading the same piece of neighbouring rows never share a bank either way.
+__device__ __forceinline__ int row_swizzle(int r) { return ((r >> 2) & 1) | ((((r >> 3) ^ (r >> 1)) & 1) << 1); }
 
 __device__ __forceinline__ bf16x8 as_frag(u32x4_t v) { return __builtin_bit_cast(bf16x8, v); }
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
@@ -68,7 +83,11 @@ __global__ __launch_bounds__(PNT, 1) void project_qkv_kernel(
     const int tile = (int)(blockIdx.x % PXCDS) * tiles_per_xcd + (int)(blockIdx.x / PXCDS);
     if (tile >= total_tiles) return;              // uniform: the padding of the last XCD's range
     const int tile_n = tile / tiles_m, tile_m = tile - tile_n * tiles_m;
+#ifdef KVS_PROJ_SAMETILE      /* timing experiment: every workgroup multiplies the same tile */
+    const int m0 = 0, n0 = 0;
+#else
     const int m0 = tile_m * PBM, n0 = tile_n * PBN;
+#endif
     const int nk = hidden / PBK;
 
     // ---- staging: one instruction moves 64 x 16 bytes = 16 tile rows; a wave stages rows
@@ -79,7 +98,7 @@ __global__ __launch_bounds__(PNT, 1) void project_qkv_kernel(
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int r = 64 * wave + 16 * i + st_row;                   // row of the tile
-        const uint32_t piece = (uint32_t)(st_pos ^ ((r >> 1) & 3)) * 16u;
+        const uint32_t piece = (uint32_t)(st_pos ^ row_swizzle(r)) * 16u;
         voff_w[i] = (uint32_t)(n0 + r) * row_bytes + piece;
         const int t = min(m0 + r, n_sel - 1);                         // rows past the end repeat the last token (never stored)
         int64_t xr = x_rows ? (int64_t)x_rows[t] : (int64_t)t;
@@ -101,23 +120,24 @@ __global__ __launch_bounds__(PNT, 1) void project_qkv_kernel(
     // the offsets above came through ordinary loads: none may be outstanding when the counted waits begin
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     auto stage_1k = [&](const u32x4_t &rs, uint32_t lds_dst, uint32_t voff, uint32_t soff) {
-        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen " KVS_PROJ_CACHE " lds"
                      :: "s"(lds_dst), "v"(voff), "s"(rs), "s"(soff));
     };
-    // contraction step `step` into ring slot step % PSTAGES; steps past the end repeat the last one (their slot is never read)
-    auto stage = [&](int step) {
-        const int ks = min(step, nk - 1);
+    // Contraction steps 2t and 2t+1 are the two halves of the same 128-byte lines of global memory and are
+    // requested as a pair, a row group's first half right before its second.  Load k of a pair (0..15): row
+    // group k / 4; weights for k % 4 < 2, tokens otherwise; first step of the pair for even k.  Steps
+    // past the end repeat the last one (their slots are never read).
+    auto stage_one = [&](int first_step, int slot_a, int slot_b, int k) {
+        const int i = k >> 2, second = k & 1, tokens = (k >> 1) & 1;
+        const int ks = min(first_step + second, nk - 1);
         const uint32_t soff = __builtin_amdgcn_readfirstlane((uint32_t)ks * (uint32_t)(PBK * 2));
-        const uint32_t slot = lds_base + (uint32_t)((step & (PSTAGES - 1)) * PSTAGE_B) + (uint32_t)(64 * wave) * PROW_B;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            stage_1k(wrs, __builtin_amdgcn_readfirstlane(slot + (uint32_t)(16 * i * PROW_B)), voff_w[i], soff);
-            stage_1k(xrs, __builtin_amdgcn_readfirstlane(slot + (uint32_t)(PTILE_B + 16 * i * PROW_B)), voff_x[i], soff);
-        }
+        const uint32_t dst = lds_base + (uint32_t)((second ? slot_b : slot_a) * PSTAGE_B) + (uint32_t)(64 * wave + 16 * i) * PROW_B
+                             + (uint32_t)(tokens ? PTILE_B : 0);
+        stage_1k(tokens ? xrs : wrs, __builtin_amdgcn_readfirstlane(dst), tokens ? voff_x[i] : voff_w[i], soff);
     };
 
     // ---- operand reads: lane (ln, hf) reads piece 2 ks + hf of row (block base + ln)
-    const uint32_t rd_off = (uint32_t)(ln * PROW_B + ((hf ^ ((ln >> 1) & 3)) * 16));
+    const uint32_t rd_off = (uint32_t)(ln * PROW_B + ((hf ^ row_swizzle(ln)) * 16));
     auto read_frag = [&](uint32_t tile_off, int block, int ks) -> u32x4_t {      // tile_off: byte offset of the operand tile
         return *reinterpret_cast<const u32x4_t *>(plds + tile_off + (uint32_t)(block * 32 * PROW_B) + (rd_off ^ (uint32_t)(32 * ks)));
     };
@@ -130,27 +150,70 @@ __global__ __launch_bounds__(PNT, 1) void project_qkv_kernel(
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[fb][tb][r] = 0.f;
 
-    stage(0);
-    stage(1);
-    stage(2);
-    for (int j = 0; j < nk; ++j) {
-        // this wave's loads of step j have landed (two younger steps, 8 instructions each, may be in flight);
-        // after the barrier every wave's have, and every wave is done reading the slot step j+3 goes to
-        asm volatile("s_waitcnt vmcnt(16)\n\ts_barrier" ::: "memory");
-        const uint32_t so = (uint32_t)((j & (PSTAGES - 1)) * PSTAGE_B);
-        const uint32_t w_tile = so + (uint32_t)(wf * 128 * PROW_B), x_tile = so + (uint32_t)(PTILE_B + wt * 128 * PROW_B);
+    // Software pipeline.  Step j multiplies with the first half of its operands (read from LDS during step
+    // j-1) while it fetches the second half, passes the step's one barrier, fetches the first half of
+    // step j+1 and multiplies with the second half: the matrix pipe has work on both sides of the barrier.
+    // Everything is issued in order, so what must overlap is interleaved in program order and pinned there
+    // with scheduling fences: per 4 MFMAs two LDS fetches and one global -> LDS load.  (LDS takes one 16-byte
+    // fetch per ~9 clocks from the four waves together and the texture path one 1 KiB load per ~23: issued in
+    // bursts they hold up the MFMAs behind them -- fetches in a block cost 1760 clocks per step against 1024 of
+    // matrix work, a step's loads in a block another 40 %.)
+    //
+    // Slots and waits.  The slot of step s is read from the barrier of step s-1 to the barrier of step s.
+    // The pair (e+4, e+5), e even, takes the slots of steps e-1 and e and goes out in four quarters
+    // after the barrier of step e: second half of e, both halves of e+1, first half of e+2; it is needed at
+    // the barriers of e+3 (first step) and e+4 (second), a full step after its last load.  So at an even
+    // step's barrier the youngest pair (16 loads) is complete behind the one needed, and at an odd step's
+    // barrier 8 loads of the next pair plus the last load of the needed pair (which belongs to its second
+    // step) may be in flight.  Each wave waits for its own loads and LDS fetches, the barrier covers the
+    // others'.
+    static_assert(PSTAGES == 5, "the waits below are counted for five slots");
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
-            u32x4_t a[4], b[4];
+    for (int k = 0; k < 16; ++k) stage_one(0, 0, 1, k);
 #pragma unroll
-            for (int i = 0; i < 4; ++i) { a[i] = read_frag(w_tile, i, ks); b[i] = read_frag(x_tile, i, ks); }
-            if (ks == 0) stage(j + 3);
+    for (int k = 0; k < 12; ++k) stage_one(2, 2, 3, k);                 // (its last quarter goes out in step 0, as in every even step)
+    asm volatile("s_waitcnt vmcnt(13)\n\ts_barrier" ::: "memory");      // step 0 has landed
+    u32x4_t a0[4], b0[4];
+    {
+        const uint32_t w_tile = (uint32_t)(wf * 128 * PROW_B), x_tile = (uint32_t)(PTILE_B + wt * 128 * PROW_B);
 #pragma unroll
-            for (int fb = 0; fb < 4; ++fb)
+        for (int i = 0; i < 4; ++i) { a0[i] = read_frag(w_tile, i, 0); b0[i] = read_frag(x_tile, i, 0); }
+    }
+    // one half of a step: 16 MFMAs with (a_use, b_use); the fetches of (a_get, b_get) from the given tiles, ks;
+    // loads quarter*4 .. quarter*4+3 of the pair that starts at `pair_step`
+    auto half = [&](const u32x4_t (&a_use)[4], const u32x4_t (&b_use)[4], u32x4_t (&a_get)[4], u32x4_t (&b_get)[4],
+                    uint32_t w_from, uint32_t x_from, int ks, int pair_step, int slot_a, int slot_b, int quarter) {
 #pragma unroll
-                for (int tb = 0; tb < 4; ++tb)
-                    acc[fb][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(a[fb]), as_frag(b[tb]), acc[fb][tb], 0, 0, 0);
+        for (int g = 0; g < 8; ++g) {
+            const int fb = g >> 1, tb0 = 2 * (g & 1);
+            acc[fb][tb0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(a_use[fb]), as_frag(b_use[tb0]), acc[fb][tb0], 0, 0, 0);
+            acc[fb][tb0 + 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(a_use[fb]), as_frag(b_use[tb0 + 1]), acc[fb][tb0 + 1], 0, 0, 0);
+#ifndef KVS_PROJ_X_NOREAD
+            if (g < 4) b_get[g] = read_frag(x_from, g, ks);      // the token operands first: the next half's first MFMAs
+            else a_get[g - 4] = read_frag(w_from, g - 4, ks);    // need all four of them and one weight operand
+#endif
+#ifndef KVS_PROJ_X_NOSTAGE
+            if (g & 1) stage_one(pair_step, slot_a, slot_b, 4 * quarter + (g >> 1));
+#endif
+            __builtin_amdgcn_sched_barrier(0);
         }
+    };
+    auto wrap = [](int s) { return s >= PSTAGES ? s - PSTAGES : s; };
+    int slot = 0;           // ring slot of step e
+    for (int e = 0; e < nk; e += 2) {      // nk is even
+        const int s1 = wrap(slot + 1), s2 = wrap(slot + 2), s3 = wrap(slot + 3), s4 = wrap(slot + 4);
+        auto w_of = [&](int sl) { return (uint32_t)(sl * PSTAGE_B) + (uint32_t)(wf * 128 * PROW_B); };
+        auto x_of = [&](int sl) { return (uint32_t)(sl * PSTAGE_B) + (uint32_t)(PTILE_B + wt * 128 * PROW_B); };
+        u32x4_t a1[4], b1[4];
+        // even step e: pair (e+2, e+3) sits in slots s2, s3; pair (e+4, e+5) goes to slots s4 and `slot`
+        half(a0, b0, a1, b1, w_of(slot), x_of(slot), 1, e + 2, s2, s3, 3);
+        asm volatile("s_waitcnt vmcnt(16) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        half(a1, b1, a0, b0, w_of(s1), x_of(s1), 0, e + 4, s4, slot, 0);
+        // odd step e+1
+        half(a0, b0, a1, b1, w_of(s1), x_of(s1), 1, e + 4, s4, slot, 1);
+        asm volatile("s_waitcnt vmcnt(9) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        half(a1, b1, a0, b0, w_of(s2), x_of(s2), 0, e + 4, s4, slot, 2);
+        slot = s2;
     }
     // nothing may still be on its way into LDS when the workgroup ends
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -220,7 +283,7 @@ extern "C" kvs_status kvs_project_qkv(const kvs_shape *shape, int32_t hidden, co
         return fail(KVS_EUNSUPPORTED, "kvs_project_qkv: bf16 with head_dim 128 is built");
     if ((shape->n_q_heads + 2 * shape->n_kv_heads) % 2 != 0)
         return fail(KVS_EUNSUPPORTED, "kvs_project_qkv: an odd number of heads in all (a workgroup takes two)");
-    if (hidden < PBK || hidden % PBK != 0) return fail(KVS_EUNSUPPORTED, "kvs_project_qkv: hidden size %d (multiples of %d)", hidden, PBK);
+    if (hidden < 2 * PBK || hidden % (2 * PBK) != 0) return fail(KVS_EUNSUPPORTED, "kvs_project_qkv: hidden size %d (multiples of %d)", hidden, 2 * PBK);
     if (n_sel == 0) return KVS_OK;
     if (n_tokens == 0) return fail(KVS_EINVAL, "kvs_project_qkv: tokens selected from an empty x");
     if (!x_rows && n_sel > n_tokens) return fail(KVS_EINVAL, "kvs_project_qkv: n_sel %lld exceeds the rows of x", (long long)n_sel);

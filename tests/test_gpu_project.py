@@ -52,7 +52,7 @@ CASES = [
     ("qwen-heads-513", 28, 4, 512, 900, 513, True, True),
     ("dense-rows-no-rope", 8, 4, 128, 256, 256, False, False),
     ("one-token", 4, 2, 64, 50, 1, True, True),
-    ("257-rope-no-gather", 6, 1, 96, 257, 257, False, True),
+    ("257-rope-no-gather", 6, 1, 192, 257, 257, False, True),
     ("llama-heads-hidden-1024", 32, 8, 1024, 2000, 640, True, True),
 ]
 
@@ -114,7 +114,7 @@ def test_project_qkv_rejects_what_is_not_built():
     sh = B.shape_of(w)
     q = torch.empty((64, 4, 128), dtype=torch.bfloat16, device=DEV)
     k = torch.empty((64, 2, 128), dtype=torch.bfloat16, device=DEV)
-    with pytest.raises(B.KvsError):      # hidden not a multiple of 32
+    with pytest.raises(B.KvsError):      # hidden not a multiple of 64
         B.kvs_project_qkv(sh, x[:, :48].contiguous().to(DEV), None, None, 64, wt[:, :48].contiguous().to(DEV), None, q, k, k.clone())
     with pytest.raises(B.KvsError):      # more tokens selected than x has rows, without a row list
         B.kvs_project_qkv(sh, x.to(DEV), None, None, 65, wt.to(DEV), None, q, k, k.clone())
