@@ -589,6 +589,56 @@ def match_config(with_oracle: bool) -> dict:
     return out
 
 
+def later_layer_config() -> dict:
+    """After the timed path (App. D.1): a layer that reuses the index list picked in an earlier layer.  Per layer:
+    kvs_project_qkv (gather of the selected hidden states, QKV projection, rotary factors) -> kvs_scatter_kv ->
+    kvs_partial_attention, on the Llama-shaped 32k layer at ratio 0.15 with per-layer weights and hidden states;
+    the library's bf16 GEMM on the same gathered rows (no rotation, no split) is timed beside the projection."""
+    w = synth.LLAMA
+    sh = B.shape_of(w)
+    n, hk, hq, d, hidden = w.n_ctx, w.n_kv_heads, w.n_q_heads, w.head_dim, w.hidden
+    n_layers = 6
+    lay0 = synth.make_layer(w, layer=0, device=DEV)
+    k = synth.recompute_budget(int(lay0["reused"].sum()), 0.15)
+    idx = torch.empty((k,), dtype=torch.int32, device=DEV)
+    dev_v = torch.empty((hk, n), device=DEV)
+    B.kvs_deviation_topk(sh, n, None, lay0["v_fresh"], None, lay0["v_cache"], lay0["reused"], None, B.SCORE_V, None, dev_v, None, k, idx)
+    rope = torch.from_numpy(synth.make_rope_table(n, d)).to(DEV)
+    layers = []
+    for l in range(n_layers):
+        x, wt = synth.make_projection(w, hidden, layer=l, device=DEV)
+        lay = synth.make_layer(w, layer=l, device=DEV, with_q=False)
+        layers.append(dict(x=x, w=wt, kc=lay["k_cache"], vc=lay["v_cache"],
+                           q=torch.empty((k, hq, d), dtype=torch.bfloat16, device=DEV),
+                           kn=torch.empty((k, hk, d), dtype=torch.bfloat16, device=DEV),
+                           vn=torch.empty((k, hk, d), dtype=torch.bfloat16, device=DEV),
+                           out=torch.empty((k, hq, d), dtype=torch.bfloat16, device=DEV)))
+    ws = torch.empty(B.kvs_workspace_size("partial_attention", sh, 1, n, k), dtype=torch.uint8, device=DEV)
+    scale = 1.0 / math.sqrt(d)
+
+    def proj(L):
+        B.kvs_project_qkv(sh, L["x"], idx, idx, k, L["w"], rope, L["q"], L["kn"], L["vn"])
+
+    def layer(L):
+        proj(L)
+        B.kvs_scatter_kv(sh, n, L["kn"], L["vn"], idx, k, L["kc"], L["vc"], None, None)
+        B.kvs_partial_attention(sh, [0], [n], [0, k], L["q"], idx, L["kc"], L["vc"], scale, L["out"], None, ws)
+    li = idx.long()
+    t_proj, med_proj = time_loop([lambda L=L: proj(L) for L in layers])
+    t_lib, _ = time_loop([lambda L=L: torch.mm(L["x"][li], L["w"].t()) for L in layers])
+    t_layer, med_layer = time_loop([lambda L=L: layer(L) for L in layers])
+    flops_proj = 2.0 * k * hidden * (hq + 2 * hk) * d
+    flops_attn = 4.0 * d * hq * float((li + 1).sum().item())
+    return {"workload": f"{w.name}: context {n}, hidden {hidden}, {k} tokens selected once (ratio 0.15) and recomputed in {n_layers} later layers",
+            "project_qkv": {"us": t_proj, "median_us": med_proj, "TFLOPs": flops_proj / t_proj / 1e6,
+                            "frac_mfma": flops_proj / t_proj / 1e6 / MFMA_BF16_PEAK_TFLOPS, "flops": flops_proj,
+                            "library_gather_plus_gemm_us": t_lib,
+                            "note": "one launch: gather, GEMM, rotary factors, split into Q/K/V; the library figure is torch index + mm (hipBLASLt) without rotation or split"},
+            "layer_us": t_layer, "layer_median_us": med_layer,
+            "layer_TFLOPs": (flops_proj + flops_attn) / t_layer / 1e6,
+            "layer_calls": "kvs_project_qkv -> kvs_scatter_kv -> kvs_partial_attention, index list from the check layer"}
+
+
 def measured_peaks(sh, w) -> dict:
     """What this machine reaches on plain work: a 256 MiB device copy (kvs_scatter_kv over every row of
     a layer: reads 2 x 64 MiB + indices, writes 2 x 64 MiB), a large bf16 library GEMM, and the
@@ -762,6 +812,8 @@ def main() -> int:
     del lay0, alpha_out, ws_cs
     result["next_rows"]["first_order_impact"] = impact_config()
     result["next_rows"]["match_tokens"] = match_config(with_oracle=args.cpu_sample > 0)
+    result["next_rows"]["later_layers"] = later_layer_config()
+    torch.cuda.empty_cache()
 
     if args.cpu_sample > 0:
         # (with --alpha gpu the oracle takes the alpha the GPU produced for layer 0: its own is O(N^2 d) on the CPU)

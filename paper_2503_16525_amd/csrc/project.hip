@@ -21,8 +21,8 @@
 //
 // The features are the MFMA's rows and the tokens its columns: a lane then ends up with four
 // consecutive features of one token per accumulator quad, so the rotation pairs (c, c + 64) sit in
-// the same lane (feature blocks fb and fb + 2 of the wave's head) and the results leave as 8-byte
-// stores.
+// the same lane (feature blocks fb and fb + 2 of the wave's head).  The rotary table rows come in and
+// the results go out through LDS, as whole rows.
 //
 // Launch order.  Workgroup b runs on XCD b % 8; tiles are numbered feature-tile-major and XCD x takes
 // a contiguous eighth of them, so the workgroups that share an L2 share weight tiles.
@@ -40,13 +40,7 @@ constexpr int PD = 128;                 // head_dim
 constexpr int PBM = 256;                // tokens per workgroup tile
 constexpr int PBN = 256;                // features per workgroup tile (two heads)
 constexpr int PBK = 32;                 // contraction step
-#ifndef KVS_PROJ_STAGES
-#define KVS_PROJ_STAGES 5
-#endif
-#ifndef KVS_PROJ_CACHE
-#define KVS_PROJ_CACHE ""
-#endif
-constexpr int PSTAGES = KVS_PROJ_STAGES;   // ring slots of 32 KiB: 5 fill the 160 KiB of a compute unit
+constexpr int PSTAGES = 5;              // ring slots of 32 KiB: 5 fill the 160 KiB of a compute unit
 constexpr int PNT = 256;
 constexpr int PROW_B = PBK * 2;         // bytes of a tile row in LDS
 constexpr int PTILE_B = 256 * PROW_B;   // one operand tile: 16 KiB
@@ -83,11 +77,7 @@ __global__ __launch_bounds__(PNT, 1) void project_qkv_kernel(
     const int tile = (int)(blockIdx.x % PXCDS) * tiles_per_xcd + (int)(blockIdx.x / PXCDS);
     if (tile >= total_tiles) return;              // uniform: the padding of the last XCD's range
     const int tile_n = tile / tiles_m, tile_m = tile - tile_n * tiles_m;
-#ifdef KVS_PROJ_SAMETILE      /* timing experiment: every workgroup multiplies the same tile */
-    const int m0 = 0, n0 = 0;
-#else
     const int m0 = tile_m * PBM, n0 = tile_n * PBN;
-#endif
     const int nk = hidden / PBK;
 
     // ---- staging: one instruction moves 64 x 16 bytes = 16 tile rows; a wave stages rows
@@ -120,7 +110,7 @@ __global__ __launch_bounds__(PNT, 1) void project_qkv_kernel(
     // the offsets above came through ordinary loads: none may be outstanding when the counted waits begin
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     auto stage_1k = [&](const u32x4_t &rs, uint32_t lds_dst, uint32_t voff, uint32_t soff) {
-        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen " KVS_PROJ_CACHE " lds"
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
                      :: "s"(lds_dst), "v"(voff), "s"(rs), "s"(soff));
     };
     // Contraction steps 2t and 2t+1 are the two halves of the same 128-byte lines of global memory and are
@@ -188,13 +178,9 @@ __global__ __launch_bounds__(PNT, 1) void project_qkv_kernel(
             const int fb = g >> 1, tb0 = 2 * (g & 1);
             acc[fb][tb0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(a_use[fb]), as_frag(b_use[tb0]), acc[fb][tb0], 0, 0, 0);
             acc[fb][tb0 + 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(a_use[fb]), as_frag(b_use[tb0 + 1]), acc[fb][tb0 + 1], 0, 0, 0);
-#ifndef KVS_PROJ_X_NOREAD
             if (g < 4) b_get[g] = read_frag(x_from, g, ks);      // the token operands first: the next half's first MFMAs
             else a_get[g - 4] = read_frag(w_from, g - 4, ks);    // need all four of them and one weight operand
-#endif
-#ifndef KVS_PROJ_X_NOSTAGE
             if (g & 1) stage_one(pair_step, slot_a, slot_b, 4 * quarter + (g >> 1));
-#endif
             __builtin_amdgcn_sched_barrier(0);
         }
     };
@@ -219,7 +205,11 @@ __global__ __launch_bounds__(PNT, 1) void project_qkv_kernel(
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
     // ---- epilogue: rotate, convert, store -----------------------------------------------------------
-    // entry r of acc[fb][tb]: feature 32 fb + 8 (r >> 2) + 4 hf + (r & 3) of the wave's head, token 32 tb + ln
+    // entry r of acc[fb][tb]: feature 32 fb + 8 (r >> 2) + 4 hf + (r & 3) of the wave's head, token 32 tb + ln.
+    // A lane's results are 8-byte pieces of 128 different rows and the rotary factors it needs are 32-byte
+    // pieces of its tokens' table rows: written and read that way, a tile spent as long in its epilogue as
+    // in 50 contraction steps.  Both go through LDS instead (the ring is free now): the table rows of the
+    // tile's 256 tokens come in as whole rows, the results leave as whole rows.
     const int head = n0 / PD + wf;
     uint16_t *dst;
     int heads_of_dst, h_local;
@@ -227,43 +217,78 @@ __global__ __launch_bounds__(PNT, 1) void project_qkv_kernel(
     else if (head < n_q_heads + n_kv_heads) { dst = k_out; heads_of_dst = n_kv_heads; h_local = head - n_q_heads; }
     else { dst = v_out; heads_of_dst = n_kv_heads; h_local = head - n_q_heads - n_kv_heads; }
     const bool turned = rope != nullptr && head < n_q_heads + n_kv_heads;
-#pragma unroll
-    for (int tb = 0; tb < 4; ++tb) {
-        const int t = m0 + 128 * wt + 32 * tb + ln;
-        if (t >= n_sel) continue;
-        uint16_t *orow = dst + ((int64_t)t * heads_of_dst + h_local) * PD;
-        if (turned) {
-            int p = sel_pos[t];
-            p = min(max(p, 0), rope_positions - 1);          // memory safety; the caller guarantees the range
-            const float *tab = rope + (int64_t)p * PD;       // [64][2]
-#pragma unroll
-            for (int fb = 0; fb < 2; ++fb)
-#pragma unroll
-                for (int r4 = 0; r4 < 4; ++r4) {
-                    const int c0 = 32 * fb + 8 * r4 + 4 * hf;
-                    const float4 cs01 = *reinterpret_cast<const float4 *>(tab + 2 * c0);
-                    const float4 cs23 = *reinterpret_cast<const float4 *>(tab + 2 * c0 + 4);
-                    const float cs[4] = {cs01.x, cs01.z, cs23.x, cs23.z}, sn[4] = {cs01.y, cs01.w, cs23.y, cs23.w};
-                    float lo[4], hi[4];
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const float y1 = acc[fb][tb][4 * r4 + i], y2 = acc[fb + 2][tb][4 * r4 + i];
-                        lo[i] = y1 * cs[i] - y2 * sn[i];
-                        hi[i] = y2 * cs[i] + y1 * sn[i];
-                    }
-                    *reinterpret_cast<uint2 *>(orow + c0) = make_uint2(pack_bf16x2(lo[0], lo[1]), pack_bf16x2(lo[2], lo[3]));
-                    *reinterpret_cast<uint2 *>(orow + c0 + 64) = make_uint2(pack_bf16x2(hi[0], hi[1]), pack_bf16x2(hi[2], hi[3]));
-                }
-        } else {
-#pragma unroll
-            for (int fb = 0; fb < 4; ++fb)
-#pragma unroll
-                for (int r4 = 0; r4 < 4; ++r4) {
-                    const int c0 = 32 * fb + 8 * r4 + 4 * hf;
-                    *reinterpret_cast<uint2 *>(orow + c0) = make_uint2(pack_bf16x2(acc[fb][tb][4 * r4 + 0], acc[fb][tb][4 * r4 + 1]),
-                                                                       pack_bf16x2(acc[fb][tb][4 * r4 + 2], acc[fb][tb][4 * r4 + 3]));
-                }
+    const bool tile_turned = rope != nullptr && n0 / PD < n_q_heads + n_kv_heads;      // uniform over the workgroup
+    __syncthreads();                                   // every wave is done with the ring
+    if (tile_turned) {
+        // table rows of tokens 64 w .. 64 w + 63 of the tile, two rows (2 x 512 bytes) per instruction, straight
+        // into LDS; the 16-byte piece p of token T's row sits at position p ^ (T & 31), so that the 32 lanes of
+        // a half-wave, which hold 32 consecutive tokens and want the same piece, read 32 different columns
+        const int t_mine = min(m0 + 64 * wave + lane, n_sel - 1);
+        int p_mine = sel_pos[t_mine];
+        p_mine = min(max(p_mine, 0), rope_positions - 1);          // memory safety; the caller guarantees the range
+        const uint64_t ra = reinterpret_cast<uint64_t>(rope);
+        u32x4_t rrs = {(uint32_t)ra, (uint32_t)(ra >> 32) & 0xffffu, (uint32_t)rope_positions * (uint32_t)(PD * 4), 0x00020000u};
+        rrs.x = __builtin_amdgcn_readfirstlane(rrs.x);
+        rrs.y = __builtin_amdgcn_readfirstlane(rrs.y);
+        rrs.z = __builtin_amdgcn_readfirstlane(rrs.z);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll 4
+        for (int i = 0; i < 32; ++i) {
+            const int tok = 2 * i + hf;                             // token of the wave's 64 this lane fetches a piece of
+            const int p = __shfl(p_mine, tok);
+            const uint32_t voff = (uint32_t)p * (uint32_t)(PD * 4) + (uint32_t)((ln ^ (tok & 31)) * 16);
+            stage_1k(rrs, __builtin_amdgcn_readfirstlane(lds_base + (uint32_t)((64 * wave + 2 * i) * (PD * 4))), voff, 0u);
         }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (turned) {
+#pragma unroll
+            for (int tb = 0; tb < 4; ++tb) {
+                const int T = 128 * wt + 32 * tb + ln;              // token of the tile; T & 31 == ln
+                const char *row = plds + T * (PD * 4);
+#pragma unroll
+                for (int fb = 0; fb < 2; ++fb)
+#pragma unroll
+                    for (int r4 = 0; r4 < 4; ++r4) {
+                        const int piece = (32 * fb + 8 * r4 + 4 * hf) / 2;      // (cos, sin) of channels c0, c0+1; the next piece: c0+2, c0+3
+                        const float4 cs01 = *reinterpret_cast<const float4 *>(row + ((piece ^ ln) * 16));
+                        const float4 cs23 = *reinterpret_cast<const float4 *>(row + (((piece + 1) ^ ln) * 16));
+                        const float cs[4] = {cs01.x, cs01.z, cs23.x, cs23.z}, sn[4] = {cs01.y, cs01.w, cs23.y, cs23.w};
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const float y1 = acc[fb][tb][4 * r4 + i], y2 = acc[fb + 2][tb][4 * r4 + i];
+                            acc[fb][tb][4 * r4 + i] = y1 * cs[i] - y2 * sn[i];
+                            acc[fb + 2][tb][4 * r4 + i] = y2 * cs[i] + y1 * sn[i];
+                        }
+                    }
+            }
+        }
+        __syncthreads();                               // the table rows have been read: LDS is free again
+    }
+    // results -> this wave's LDS region [128 tokens][264 bytes] (the 8 bytes of padding spread a half-wave's
+    // 32 rows over all banks) -> whole rows of 256 bytes to global memory, four rows per store instruction
+    constexpr int OROW_B = PD * 2 + 8;
+    char *region = plds + wave * (128 * OROW_B);
+#pragma unroll
+    for (int tb = 0; tb < 4; ++tb)
+#pragma unroll
+        for (int fb = 0; fb < 4; ++fb)
+#pragma unroll
+            for (int r4 = 0; r4 < 4; ++r4) {
+                const int c0 = 32 * fb + 8 * r4 + 4 * hf;
+                *reinterpret_cast<uint2 *>(region + (32 * tb + ln) * OROW_B + 2 * c0) =
+                    make_uint2(pack_bf16x2(acc[fb][tb][4 * r4 + 0], acc[fb][tb][4 * r4 + 1]), pack_bf16x2(acc[fb][tb][4 * r4 + 2], acc[fb][tb][4 * r4 + 3]));
+            }
+    // (same wave wrote and reads: LDS handles a wave's requests in order, no barrier)
+    const int sub = lane >> 4, chunk = lane & 15;
+#pragma unroll 4
+    for (int i = 0; i < 32; ++i) {
+        const int tok = 4 * i + sub;
+        const int t = m0 + 128 * wt + tok;
+        const uint2 lo = *reinterpret_cast<const uint2 *>(region + tok * OROW_B + 16 * chunk);
+        const uint2 hi = *reinterpret_cast<const uint2 *>(region + tok * OROW_B + 16 * chunk + 8);
+        if (t < n_sel)
+            *reinterpret_cast<uint4 *>(dst + ((int64_t)t * heads_of_dst + h_local) * PD + 8 * chunk) = make_uint4(lo.x, lo.y, hi.x, hi.y);
     }
 }
 
