@@ -761,7 +761,7 @@ def main() -> int:
         call_scatter(s, sh)
     t, med = time_loop([lambda s=s: call_check(s, sh) for s in slots])
     comp["decode_check_one_context"] = dict(frac_hbm(bytes_dec, t), median_us=med,
-                                            note="one 32k context: four short launches, latency-bound; the 64-request batch is under configs")
+                                            note="one 32k context: five short launches (logits, softmax statistics, scores + key histogram, two selecting launches), latency-bound; the 64-request batch is under configs")
     t1, _ = time_loop([f for s in slots for f in (lambda s=s: call_dec_scatter(s, sh), lambda s=s: call_dec_attn(s, sh))], reps=1)
     comp["decode_recompute_scatter_plus_attention"] = {"us": 2 * t1, "attention_TFLOP": flops_dec / 1e12,
                                                        "TFLOPs": flops_dec / (2 * t1 * 1e-6) / 1e12}

@@ -238,6 +238,10 @@ KVS_API kvs_status kvs_partial_attention(const kvs_shape *shape, int32_t batch,
  * k_req     [host] int32[batch], 0 <= k_req[b] <= ctx_len[b]
  * score_out [dev] fp32[n_rows] or NULL; rows outside the contexts are not written
  * attn_out  [dev] [batch, n_q_heads, head_dim] (shape dtype) or NULL: sum_i a[h,i] * V_i
+ * A call with one context of 12289..262144 rows selects the way kvs_deviation_topk does (keys and their
+ * histogram from the scoring launch, two short selecting launches, same index list bit for bit) and, like it,
+ * uses 2.1 MB of device memory that belongs to the library: such calls and kvs_deviation_topk calls on one
+ * device must not overlap (one stream, or ordered by events).
  */
 KVS_API kvs_status kvs_decode_check(const kvs_shape *shape, int32_t batch, int64_t n_rows,
                             const int64_t *ctx_off, const int64_t *ctx_len,

@@ -365,11 +365,14 @@ __global__ __launch_bounds__(kThreads) void decode_stats_kernel(
 // One wave per kTok-token tile, lane = token: every load is 64 consecutive floats, there is no
 // LDS and no barrier, and the sum over the KV heads runs in head order.  GRP > 0: the group size
 // is a compile-time constant, so the loads of two KV heads are in flight together.
-template <int GRP>
+// HIST (one context whose top-k then runs from the histogram, as in kvs_deviation_topk): the token's
+// order-preserving key goes to keys_out[token index in the context] and is counted by its leading bits.
+template <int GRP, bool HIST>
 __global__ __launch_bounds__(kThreads) void decode_score_kernel(
     const DecodeBatch bd, int n_tiles, int n_q_heads, int n_kv_heads, int64_t n_rows,
     const float *__restrict__ logits, const float2 *__restrict__ stats,
-    const float *__restrict__ dev_v, const uint8_t *__restrict__ reused, float *__restrict__ score)
+    const float *__restrict__ dev_v, const uint8_t *__restrict__ reused, float *__restrict__ score,
+    uint32_t *__restrict__ keys_out, uint32_t *__restrict__ key_hist)
 {
     static_assert(kTok == 64, "one token per lane");
     const int lane = threadIdx.x & 63;
@@ -421,7 +424,16 @@ __global__ __launch_bounds__(kThreads) void decode_score_kernel(
     }
     if (live) {
         const bool cand = reused ? reused[row] != 0 : true;
-        score[row] = cand ? s : -INFINITY;
+        const float sc = cand ? s : -INFINITY;
+        score[row] = sc;
+        if (HIST) {
+            const uint32_t key = score_key(sc);
+            keys_out[i] = key;
+            // integer counts: the histogram does not depend on the order in which the atomics land
+            if (sc != -INFINITY)
+                __hip_atomic_fetch_add(key_hist + (blockIdx.x % kKeyHistCopies) * kKeyHistBins + key_hist_slot(key >> kKeyHistShift), 1u,
+                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
     }
 }
 
@@ -634,6 +646,15 @@ extern "C" kvs_status kvs_decode_check(const kvs_shape *shape, int32_t batch, in
     ws += align_up(sizeof(float) * ((size_t)n_rows / kAttTok + (size_t)batch + 1) * (size_t)hq * (size_t)d, 256);
     void *select_ws = ws;
     const int lph = (int)(d * elem_bytes(shape->dtype) / 16);
+    // One context of a length the histogram-driven selection covers: the score kernel also leaves the keys and
+    // their leading-bits histogram in the library's own device scratch (the one kvs_deviation_topk uses: calls on
+    // one device that use it must not overlap), and two short launches replace the one-workgroup top-k.
+    const bool from_hist = batch == 1 && k_req[0] > 0 && ctx_len[0] > kFusedMinTokens && ctx_len[0] <= kFusedMaxTokens;
+    FusedScratch fs = {nullptr, nullptr, nullptr};
+    if (from_hist) {
+        const kvs_status fst = fused_scratch(&fs);
+        if (fst != KVS_OK) return fst;
+    }
 
     for (int32_t b0 = 0; b0 < batch; b0 += kMaxReq) {
         const int nr = (batch - b0) < kMaxReq ? (batch - b0) : kMaxReq;
@@ -696,7 +717,15 @@ extern "C" kvs_status kvs_decode_check(const kvs_shape *shape, int32_t batch, in
         hipLaunchKernelGGL(decode_stats_kernel, dim3((unsigned)(nr * hq)), block, 0, hs, bd_tok, hq, part_l, stats);
         if ((st = check_launch("kvs_decode_check(stats)")) != KVS_OK) return st;
         const dim3 sgrid((unsigned)((tiles_tok + kThreads / 64 - 1) / (kThreads / 64)));
-#define KVS_DEC_SCORE(G) hipLaunchKernelGGL(decode_score_kernel<G>, sgrid, block, 0, hs, bd_tok, (int)tiles_tok, hq, hk, n_rows, logits, stats, dev_v, reused, score)
+#define KVS_DEC_SCORE(G)                                                                                                          \
+    do {                                                                                                                          \
+        if (from_hist)                                                                                                            \
+            hipLaunchKernelGGL((decode_score_kernel<G, true>), sgrid, block, 0, hs, bd_tok, (int)tiles_tok, hq, hk, n_rows, logits, \
+                               stats, dev_v, reused, score, fs.keys, fs.hist);                                                    \
+        else                                                                                                                      \
+            hipLaunchKernelGGL((decode_score_kernel<G, false>), sgrid, block, 0, hs, bd_tok, (int)tiles_tok, hq, hk, n_rows, logits, \
+                               stats, dev_v, reused, score, (uint32_t *)nullptr, (uint32_t *)nullptr);                            \
+    } while (0)
         if (grp == 1) KVS_DEC_SCORE(1);
         else if (grp == 2) KVS_DEC_SCORE(2);
         else if (grp == 4) KVS_DEC_SCORE(4);
@@ -727,5 +756,6 @@ extern "C" kvs_status kvs_decode_check(const kvs_shape *shape, int32_t batch, in
         }
     }
     if (total_k == 0) return KVS_OK;
+    if (from_hist) return launch_select_from_hist(fs, (int32_t)ctx_len[0], k_req[0], idx_out, hs);
     return launch_select(score, batch, ctx_off, ctx_len, k_req, idx_out, select_ws, select_workspace_bytes(batch, n_rows), hs);
 }

@@ -842,6 +842,34 @@ def test_decode_check_long_context():
     np.testing.assert_array_equal(ix, own)
 
 
+@pytest.mark.parametrize("n", [12288, 12289, 32769, 70000])
+def test_decode_check_single_context_selection_paths(n):
+    """one context on both sides of the length from which the top-k runs from the scoring launch's key histogram
+    (12289 .. 262144 rows); with many never-reused rows, ties (dev_v on a coarse grid) and k from 1 to every candidate"""
+    w = synth.scaled(synth.DECODE, 0, n_q_heads=8, n_kv_heads=2)
+    say(f"decode check, one context of {n} rows")
+    hk, hq, d = w.n_kv_heads, w.n_q_heads, w.head_dim
+    g = torch.Generator().manual_seed(n)
+    kc = torch.randn((n, hk, d), generator=g).to(w.torch_dtype)
+    q_new = (torch.randn((1, hq, d), generator=g) / math.sqrt(d)).to(w.torch_dtype)
+    dev_v = torch.round(torch.rand((hk, n), generator=g) * 8) / 8            # coarse grid: many equal scores are possible
+    reused = (torch.rand((n,), generator=g) < 0.7).to(torch.uint8)
+    off, lens = np.array([0], dtype=np.int64), np.array([n], dtype=np.int64)
+    sh = shape_for(w)
+    ws = torch.empty(B.kvs_workspace_size("decode_check", sh, 1, n), dtype=torch.uint8, device=DEV)
+    n_cand = int(reused.sum())
+    for k in (1, 37, n // 50, n_cand):
+        ref_idx, ref_score, _ = oracle.decode_check(q_new, oracle._as_np(kc), dev_v.numpy(), reused.numpy(), 1.0, off, lens, [k])
+        idx = torch.full((k,), -1, dtype=torch.int32, device=DEV)
+        score = torch.full((n,), float("nan"), device=DEV)
+        B.kvs_decode_check(sh, n, off, lens, q_new.to(DEV), kc.to(DEV), None, dev_v.to(DEV), reused.to(DEV), 1.0, [k], idx, score, None, ws)
+        torch.cuda.synchronize()
+        sc, ix = score.cpu().numpy(), idx.cpu().numpy()
+        assert_scores_close(sc, ref_score)
+        check_topk_band(ix, ref_score, k)
+        np.testing.assert_array_equal(ix, oracle.select_topk(sc, [0, n], [k]))      # exactly the top-k of the GPU's own scores
+
+
 # --------------------------------------------------------------------------------- whole path
 
 @pytest.mark.parametrize("w", [synth.TINY, synth.scaled(synth.QWEN, 1024, span_mean=64.0)], ids=["tiny", "qwen-1024"])
