@@ -361,7 +361,7 @@ KVS_API kvs_status kvs_match_tokens(const int32_t *target, int64_t n_target,
  * q_out    [dev] bf16 [n_sel, n_q_heads, head_dim]; k_out, v_out [dev] bf16 [n_sel, n_kv_heads, head_dim]:
  *          the layouts kvs_partial_attention and kvs_scatter_kv take
  * Built for bf16, head_dim 128, hidden a multiple of 64, an even number of heads in all, x and w below
- * 4 GiB each (KVS_EUNSUPPORTED otherwise).  Tensors 16-byte aligned.  No workspace.  Row indices and
+ * 4 GiB each, a rotary table below 4 GiB (KVS_EUNSUPPORTED otherwise).  Tensors 16-byte aligned.  No workspace.  Row indices and
  * positions outside their ranges are clamped (memory safety only).
  */
 KVS_API kvs_status kvs_project_qkv(const kvs_shape *shape, int32_t hidden, const void *x, int64_t n_tokens,

@@ -320,7 +320,8 @@ extern "C" kvs_status kvs_project_qkv(const kvs_shape *shape, int32_t hidden, co
     // rows are addressed with 32-bit byte offsets
     if (n_tokens * hidden * 2 >= ((int64_t)1 << 32) || features * hidden * 2 >= ((int64_t)1 << 32))
         return fail(KVS_EUNSUPPORTED, "kvs_project_qkv: x or w of 4 GiB or more");
-    if (n_sel > 0x7fffffff || rope_positions > 0x7fffffff) return fail(KVS_EUNSUPPORTED, "kvs_project_qkv: too many tokens");
+    if (n_sel > 0x7fffffff) return fail(KVS_EUNSUPPORTED, "kvs_project_qkv: too many tokens");
+    if (rope && rope_positions * (int64_t)(PD * 4) >= ((int64_t)1 << 32)) return fail(KVS_EUNSUPPORTED, "kvs_project_qkv: rotary table of 4 GiB or more");
     static DeviceOnce attr_once;
     st = once_per_device(attr_once, [] {
         const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&project_qkv_kernel),
