@@ -133,10 +133,7 @@ __global__ __launch_bounds__(kDevThreads) void deviation_kernel(
         if (HIST) {
             const uint32_t key = score_key(sc);
             keys_out[i] = key;
-            // integer counts: the histogram does not depend on the order in which the atomics land
-            if (sc != -INFINITY)
-                __hip_atomic_fetch_add(key_hist + (blockIdx.x % kKeyHistCopies) * kKeyHistBins + key_hist_slot(key >> kKeyHistShift), 1u,
-                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            key_hist_count<false>(key_hist, key, sc != -INFINITY);
         }
     }
 }
