@@ -552,12 +552,11 @@ def impact_config() -> dict:
     terms = n * (n + 1) / 2 * hq * d
     return {"workload": f"{w.name}: context {n}, top 10 % of the reused tokens", "ms": t / 1e3, "channel_terms": terms,
             "G_terms_per_s": terms / (t * 1e-6) / 1e9,
-            # per channel term: two fma for the dots (q.k, q.dK), subtract + |.|-add for the key direction's norm,
-            # fma + |.|-add for the joint norm: 6 vector instructions, none of them a contraction the matrix cores take
-            # as it stands; against 256 CUs x 64 lanes x 2.4 GHz of unpacked fp32 issue (the library is built
-            # without packed fp32)
-            "roofline": {"bound": "alu", "achieved": 6 * terms / (t * 1e-6) / 1e12, "peak": 256 * 64 * 2.4e9 / 1e12,
-                         "unit": "T vector lane-ops/s", "frac": 6 * terms / (t * 1e-6) / (256 * 64 * 2.4e9)},
+            # per channel term the vector units spend a subtraction, an fma and two |.|-adds (the two dot products per
+            # (row, token) pair run on the matrix cores); against 256 CUs x 64 lanes x 2.4 GHz of unpacked fp32
+            # issue (the library is built without packed fp32)
+            "roofline": {"bound": "alu", "achieved": 4 * terms / (t * 1e-6) / 1e12, "peak": 256 * 64 * 2.4e9 / 1e12,
+                         "unit": "T vector lane-ops/s", "frac": 4 * terms / (t * 1e-6) / (256 * 64 * 2.4e9)},
             "value_direction_vs_deviation_with_alpha_max_rel_diff": rel,
             "top_set_overlap": {"key_vs_value_direction": len(sv & sk) / k, "value_vs_both_directions": len(sv & skv) / k,
                                 "magnitude_only_vs_both_directions": len(sm & skv) / k,
