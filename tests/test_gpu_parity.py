@@ -922,13 +922,16 @@ def test_prefill_path_end_to_end(w):
 
 # --------------------------------------------------------------------------------- graph capture
 
-def test_path_replays_from_a_captured_graph():
+@pytest.mark.parametrize("n_ctx,fused", [(1500, False), (16384, True)], ids=["two-calls-1500", "histogram-paths-16384"])
+def test_path_replays_from_a_captured_graph(n_ctx, fused):
     """Every entry point only enqueues kernels on the caller's stream (no allocation, no
     synchronisation, no memset node), so the whole chain can be captured once and replayed.  The
     chain is captured on static buffers and replayed three times with different cache contents and
-    eager work in between; each replay must give bit for bit what the eager calls give."""
-    w = synth.scaled(synth.LLAMA, 1500, span_mean=64.0)
-    say("prefill + decode chain from a captured graph")
+    eager work in between; each replay must give bit for bit what the eager calls give.  The longer context
+    takes kvs_deviation_topk and the single-context decode check through their histogram-driven selection, whose
+    scratch lives in the library and is cleared by the kernels themselves."""
+    w = synth.scaled(synth.LLAMA, n_ctx, span_mean=64.0)
+    say(f"prefill + decode chain from a captured graph, {n_ctx} tokens")
     lay = synth.make_layer(w)
     g = to_dev(lay)
     sh = shape_for(w)
@@ -950,8 +953,11 @@ def test_path_replays_from_a_captured_graph():
                     ws_dec=torch.empty(B.kvs_workspace_size("decode_check", sh, 1, n), dtype=torch.uint8, device=DEV))
 
     def chain(b):
-        B.kvs_deviation(sh, n, None, g["v_fresh"], None, b["vc"], b["ru"], None, B.SCORE_V, None, b["dev_v"], b["score"])
-        B.kvs_select_topk(b["score"], [0, n], [k], b["idx"])
+        if fused:
+            B.kvs_deviation_topk(sh, n, None, g["v_fresh"], None, b["vc"], b["ru"], None, B.SCORE_V, None, b["dev_v"], b["score"], k, b["idx"])
+        else:
+            B.kvs_deviation(sh, n, None, g["v_fresh"], None, b["vc"], b["ru"], None, B.SCORE_V, None, b["dev_v"], b["score"])
+            B.kvs_select_topk(b["score"], [0, n], [k], b["idx"])
         li = b["idx"].long()
         B.kvs_scatter_kv(sh, n, g["k_fresh"][li], g["v_fresh"][li], b["idx"], k, b["kc"], b["vc"], b["ru"], b["dev_v"])
         B.kvs_partial_attention(sh, [0], [n], [0, k], g["q"][li], b["idx"], b["kc"], b["vc"], 1.0, b["out"], workspace=b["ws"])
