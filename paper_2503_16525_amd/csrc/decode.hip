@@ -177,6 +177,11 @@ __global__ __launch_bounds__(kThreads) void decode_logits_kernel(
 // are conflict-free).  A workgroup is still one 64-token tile; wave w takes KV heads w, w+4, ..,
 // each as two units of 32 tokens that it stages and consumes by itself through its own two LDS
 // slots, so there is no barrier anywhere: a wave only waits for its own loads.
+// workgroups of the matrix-core logits launch at most: beyond that each takes several 64-token tiles (64-request
+// batch, 10.9k tiles: 335 us per check with 1024 workgroups against 344 us with one per tile; 512 and 2048: 340, 339)
+#ifndef KVS_DEC_PERSIST
+#define KVS_DEC_PERSIST 1024
+#endif
 constexpr int kMmaUnitBytes = 32 * 256;            // 32 tokens x 256 bytes
 constexpr int kMmaSlots = 2;
 constexpr int kMmaLds = (kThreads / 64) * kMmaSlots * kMmaUnitBytes;
@@ -202,13 +207,16 @@ __device__ __forceinline__ float half_sum(float v)
 __global__ __launch_bounds__(kThreads) void decode_logits_mfma_kernel(
     const DecodeBatch bd, int n_q_heads, int n_kv_heads, int64_t n_rows,
     const uint16_t *__restrict__ q_new, const uint16_t *__restrict__ k_cache, float scale,
-    float *__restrict__ logits, float2 *__restrict__ partial /* [tile][n_q_heads] (max, sum exp) */)
+    float *__restrict__ logits, float2 *__restrict__ partial /* [tile][n_q_heads] (max, sum exp) */, int n_tiles)
 {
     constexpr int D = 128, ROW_B = 256;
     extern __shared__ __attribute__((aligned(16))) char lds_mma[];
+    // a workgroup takes tiles blockIdx.x, blockIdx.x + gridDim.x, ...: nothing below synchronises the waves, and
+    // every wave leaves a tile with its own loads and LDS reads complete
+    for (int tile_id = blockIdx.x; tile_id < n_tiles; tile_id += gridDim.x) {
     int b = 0;
-    while (b + 1 < bd.n_req && (int)blockIdx.x >= bd.tile_begin[b + 1]) ++b;
-    const int tile = blockIdx.x - bd.tile_begin[b];
+    while (b + 1 < bd.n_req && tile_id >= bd.tile_begin[b + 1]) ++b;
+    const int tile = tile_id - bd.tile_begin[b];
     const int len = bd.ctx_len[b];
     const int tok0 = tile * kTok;
     const int tile_tok = min(kTok, len - tok0);
@@ -319,12 +327,13 @@ __global__ __launch_bounds__(kThreads) void decode_logits_mfma_kernel(
                         }
                         const float m = half_max(fmaxf(v[0], v[1]));
                         const float z = half_sum(__expf(v[0] - m) + __expf(v[1] - m));
-                        if (ln == 0) partial[(int64_t)blockIdx.x * n_q_heads + h] = make_float2(m, z);
+                        if (ln == 0) partial[(int64_t)tile_id * n_q_heads + h] = make_float2(m, z);
                     }
                 }
             }
         }
     }
+    }   // tiles of this workgroup
 }
 
 // ---- 2. softmax statistics per (request, head): merge the tile partials ------------------------------
@@ -700,8 +709,8 @@ extern "C" kvs_status kvs_decode_check(const kvs_shape *shape, int32_t batch, in
                 return e == hipSuccess ? KVS_OK : fail(KVS_EHIP, "kvs_decode_check: hipFuncSetAttribute: %s", hipGetErrorString(e));
             });
             if (st != KVS_OK) return st;
-            hipLaunchKernelGGL(decode_logits_mfma_kernel, dim3((unsigned)tiles_tok), block, kMmaLds, hs, bd_tok, hq, hk, n_rows,
-                               (const uint16_t *)q_new, (const uint16_t *)k_cache, scale, logits, part_l);
+            hipLaunchKernelGGL(decode_logits_mfma_kernel, dim3((unsigned)(KVS_DEC_PERSIST > 0 && tiles_tok > KVS_DEC_PERSIST ? KVS_DEC_PERSIST : tiles_tok)), block, kMmaLds, hs, bd_tok, hq, hk, n_rows,
+                               (const uint16_t *)q_new, (const uint16_t *)k_cache, scale, logits, part_l, (int)tiles_tok);
         }
         else if (shape->dtype == KVS_BF16 && lph == 16) KVS_DEC_CASE(KVS_BF16, 16);
         else if (shape->dtype == KVS_BF16 && lph == 8) KVS_DEC_CASE(KVS_BF16, 8);
