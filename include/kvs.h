@@ -330,6 +330,8 @@ KVS_API kvs_status kvs_first_order_impact(const kvs_shape *shape, int64_t n_toke
  * order in which the device's atomics arrive.  Six launches, no host synchronisation.  Cost grows
  * with the matched tokens, except for degenerate inputs (one token repeated throughout both
  * sequences makes every pair of windows a candidate: n_target x n_candidate steps).
+ * Several earlier requests are matched in one call by concatenating them into one candidate with a token id
+ * that occurs nowhere else between them (no window then spans two requests); partners index the concatenation.
  * The scheduler of Sec. 4.3 Alg. 2 needs no call of its own: the batch it sends on is
  * kvs_select_topk over the requests' hit rates (ties to the request that arrived first).
  */

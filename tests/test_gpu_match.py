@@ -117,6 +117,23 @@ def test_match_periodic_text():
     check(c, t, 8)
 
 
+def test_match_against_several_earlier_requests_in_one_call():
+    """two earlier requests concatenated with a separator id that occurs nowhere else: stretches are found in both,
+    none spans the separator, and the result equals the oracle's on the same concatenation"""
+    say("match: two candidates in one call")
+    rng = np.random.default_rng(21)
+    c1, c2 = rng.integers(0, 5000, size=900), rng.integers(0, 5000, size=1100)
+    sep = 2 ** 30
+    t = np.concatenate([c2[100:400], rng.integers(5000, 9000, size=50), c1[600:900], c2[:40]])   # ends of c1 / start of c2: adjacent in the concatenation
+    cat = np.concatenate([c1, [sep], c2])
+    k = check(t, cat, 16)
+    partner, _, _, _, _ = gpu_match(t, cat, 16, BASE, MOD)
+    assert k >= 300 + 300 + 40
+    assert np.array_equal(partner[:300], 901 + np.arange(100, 400))           # from the second request
+    assert np.array_equal(partner[350:650], np.arange(600, 900))              # from the first
+    assert np.array_equal(partner[650:690], 901 + np.arange(40))              # the second again, although it follows c1's end in t
+
+
 def test_schedule_batch_is_topk_of_hit_rates():
     """Sec. 4.3 Alg. 2: the N requests of highest hit rate (earlier arrival among equals) as kvs_select_topk finds them"""
     say("schedule: top-N by hit rate")
