@@ -149,3 +149,84 @@ def test_attn_colsum_argument_errors(lib):
     n_long = 1 << 17
     assert call(shape=f32, n=n_long, ws_bytes=B.kvs_workspace_size("attn_colsum", f32, 1, n_long)) == B.EUNSUPPORTED
     assert b"vector path" in lib.kvs_last_error()
+
+
+def test_deviation_topk_argument_errors(lib):
+    sh = _shape()
+
+    def call(n=1000, k=10, idx=FAKE, ws=None, ws_bytes=0, v=FAKE):
+        return lib.kvs_deviation_topk(ctypes.byref(sh), n, None, v, None, FAKE, None, None, 0, None, FAKE, FAKE,
+                                      k, idx, ws, ws_bytes, None)
+    assert call(n=-1) == B.EINVAL
+    assert call(k=-1) == B.EINVAL
+    assert call(k=1001) == B.EINVAL and b"outside" in lib.kvs_last_error()
+    assert call(idx=None) == B.EINVAL
+    assert call(ws=FAKE * 16 + 64, ws_bytes=1 << 20) == B.EINVAL          # workspace alignment
+    assert call(v=None) == B.EINVAL                                        # the scoring call's own checks still apply
+    assert call(n=0, k=0, idx=None, v=None) == B.OK                        # empty: no-op
+
+
+def test_first_order_impact_argument_errors(lib):
+    sh = _shape()
+    need = B.kvs_workspace_size("first_order_impact", sh, 1, 500)
+    assert need >= 3 * 4 * 8 * 500
+
+    def call(n=500, q=FAKE, lse=FAKE, scale=1.0, ws=FAKE * 16, ws_bytes=need):
+        return lib.kvs_first_order_impact(ctypes.byref(sh), n, q, FAKE, FAKE, FAKE, FAKE, FAKE, lse, None, scale,
+                                          FAKE, FAKE, FAKE, ws, ws_bytes, None)
+    assert call(n=-1) == B.EINVAL
+    assert call(n=0) == B.OK                                               # empty: no-op
+    assert call(n=(1 << 20) + 1, ws_bytes=1 << 40) == B.EUNSUPPORTED
+    assert call(q=None) == B.EINVAL
+    assert call(lse=None) == B.EINVAL
+    assert call(scale=float("inf")) == B.EINVAL
+    assert call(ws=None) == B.EWORKSPACE
+    assert call(ws_bytes=need - 1) == B.EWORKSPACE
+    assert call(ws=FAKE * 16 + 64) == B.EINVAL
+
+
+def test_match_tokens_argument_errors(lib):
+    need = B.kvs_workspace_size("match_tokens", None, 1, 4000, 3000)
+    assert need > 0
+
+    def call(nt=4000, nc=3000, w=16, m=4294967291, targ=FAKE, cand=FAKE, partner=FAKE, n_out=FAKE, ws=FAKE * 16, ws_bytes=need):
+        return lib.kvs_match_tokens(targ, nt, cand, nc, w, 1000003, m, partner, None, None, n_out, ws, ws_bytes, None)
+    assert call(nt=-1) == B.EINVAL
+    assert call(nc=-1) == B.EINVAL
+    assert call(w=0) == B.EINVAL
+    assert call(m=0) == B.EINVAL and b"modulus" in lib.kvs_last_error()
+    assert call(nt=(1 << 26) + 1) == B.EUNSUPPORTED
+    assert call(n_out=None) == B.EINVAL
+    assert call(targ=None) == B.EINVAL
+    assert call(partner=None) == B.EINVAL
+    assert call(cand=None) == B.EINVAL
+    assert call(ws=None) == B.EINVAL
+    assert call(ws=FAKE * 16 + 64) == B.EINVAL
+    assert call(ws_bytes=need - 1) == B.EWORKSPACE
+    # the workspace grows with both sequences
+    assert B.kvs_workspace_size("match_tokens", None, 1, 8000, 3000) > need
+    assert B.kvs_workspace_size("match_tokens", None, 1, 4000, 6000) > need
+
+
+def test_project_qkv_argument_errors(lib):
+    sh = _shape()
+
+    def call(shape=sh, hidden=4096, x=FAKE, n_tok=1000, rows=None, pos=FAKE, n_sel=100, wq=FAKE, rope=FAKE, rope_n=2048,
+             q=FAKE, k=FAKE, v=FAKE):
+        return lib.kvs_project_qkv(ctypes.byref(shape), hidden, x, n_tok, rows, pos, n_sel, wq, rope, rope_n, q, k, v, None)
+    assert call(n_tok=-1) == B.EINVAL
+    assert call(n_sel=-1) == B.EINVAL
+    assert call(shape=_shape(dt=B.F32, d=64, hq=4, hk=4)) == B.EUNSUPPORTED
+    assert call(shape=_shape(hq=3, hk=1)) == B.EUNSUPPORTED               # 5 heads in all: odd
+    assert call(hidden=4096 + 32) == B.EUNSUPPORTED
+    assert call(hidden=0) == B.EUNSUPPORTED
+    assert call(n_sel=0, x=None, wq=None, q=None, k=None, v=None) == B.OK  # nothing selected: no-op
+    assert call(n_tok=0) == B.EINVAL
+    assert call(n_sel=1001) == B.EINVAL                                    # without a row list the first n_sel rows of x are meant
+    assert call(x=None) == B.EINVAL
+    assert call(v=None) == B.EINVAL
+    assert call(pos=None) == B.EINVAL and b"rotary" in lib.kvs_last_error()
+    assert call(rope_n=0) == B.EINVAL
+    assert call(wq=FAKE + 8) == B.EINVAL
+    assert call(n_tok=1 << 20) == B.EUNSUPPORTED and b"4 GiB" in lib.kvs_last_error()
+    assert call(rope_n=1 << 23) == B.EUNSUPPORTED and b"rotary" in lib.kvs_last_error()
