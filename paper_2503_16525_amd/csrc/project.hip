@@ -24,8 +24,11 @@
 // the same lane (feature blocks fb and fb + 2 of the wave's head).  The rotary table rows come in and
 // the results go out through LDS, as whole rows.
 //
-// Launch order.  Workgroup b runs on XCD b % 8; tiles are numbered feature-tile-major and XCD x takes
-// a contiguous eighth of them, so the workgroups that share an L2 share weight tiles.
+// Launch order.  Workgroup b runs on XCD b % 8.  The grid of tiles (feature tiles x token tiles) is cut
+// into eight blocks, fx along the features and 8 / fx along the tokens, one block per XCD: what an XCD
+// pulls through its L2 is then its block's rows of weights plus its block's hidden rows, and the cut is
+// chosen for the smallest block first (the launch is as long as the fullest XCD) and the smallest sum of
+// the two after that.
 #include "kvs_internal.h"
 
 #include <type_traits>
@@ -68,15 +71,16 @@ __global__ __launch_bounds__(PNT, 1) void project_qkv_kernel(
     const int32_t *__restrict__ x_rows, const int32_t *__restrict__ sel_pos, int n_sel,
     const uint16_t *__restrict__ w, const float *__restrict__ rope, int rope_positions,
     uint16_t *__restrict__ q_out, uint16_t *__restrict__ k_out, uint16_t *__restrict__ v_out,
-    int tiles_m, int total_tiles, int tiles_per_xcd)
+    int tiles_m, int tiles_n, int xcd_fx, int block_n, int block_m)
 {
     extern __shared__ __attribute__((aligned(16))) char plds[];
     const int tid = threadIdx.x, lane = tid & 63, ln = lane & 31, hf = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wf = wave & 1, wt = wave >> 1;      // which 128 features / 128 tokens of the tile
-    const int tile = (int)(blockIdx.x % PXCDS) * tiles_per_xcd + (int)(blockIdx.x / PXCDS);
-    if (tile >= total_tiles) return;              // uniform: the padding of the last XCD's range
-    const int tile_n = tile / tiles_m, tile_m = tile - tile_n * tiles_m;
+    // the XCD's block of the tile grid, walked with the feature tile running fastest
+    const int xcd = (int)(blockIdx.x % PXCDS), in_block = (int)(blockIdx.x / PXCDS);
+    const int tile_n = (xcd % xcd_fx) * block_n + in_block % block_n, tile_m = (xcd / xcd_fx) * block_m + in_block / block_n;
+    if (tile_n >= tiles_n || tile_m >= tiles_m) return;      // uniform: blocks at the edges of the grid are not full
     const int m0 = tile_m * PBM, n0 = tile_n * PBN;
     const int nk = hidden / PBK;
 
@@ -329,12 +333,20 @@ extern "C" kvs_status kvs_project_qkv(const kvs_shape *shape, int32_t hidden, co
         return e == hipSuccess ? KVS_OK : fail(KVS_EHIP, "kvs_project_qkv: hipFuncSetAttribute: %s", hipGetErrorString(e));
     });
     if (st != KVS_OK) return st;
-    const int64_t tiles_m = (n_sel + PBM - 1) / PBM, tiles_n = features / PBN, total = tiles_m * tiles_n;
-    const int64_t per_xcd = (total + PXCDS - 1) / PXCDS;
+    const int64_t tiles_m = (n_sel + PBM - 1) / PBM, tiles_n = features / PBN;
+    int fx = PXCDS;
+    int64_t block_n = 0, block_m = 0;
+    for (int f = PXCDS; f >= 1; f >>= 1) {
+        const int64_t bn = (tiles_n + f - 1) / f, bm = (tiles_m + PXCDS / f - 1) / (PXCDS / f);
+        if (block_n == 0 || bn * bm < block_n * block_m || (bn * bm == block_n * block_m && bn + bm < block_n + block_m)) {
+            fx = f; block_n = bn; block_m = bm;
+        }
+    }
+    const int64_t per_xcd = block_n * block_m;
     if (per_xcd * PXCDS > 0x7fffffff) return fail(KVS_EUNSUPPORTED, "kvs_project_qkv: too many tiles");
     hipLaunchKernelGGL(project_qkv_kernel, dim3((unsigned)(per_xcd * PXCDS)), dim3(PNT), PLDS_BYTES, (hipStream_t)stream,
                        shape->n_q_heads, shape->n_kv_heads, (int)hidden, (const uint16_t *)x, n_tokens, x_rows, sel_pos, (int)n_sel,
                        (const uint16_t *)w_qkv, rope, (int)rope_positions, (uint16_t *)q_out, (uint16_t *)k_out, (uint16_t *)v_out,
-                       (int)tiles_m, (int)total, (int)per_xcd);
+                       (int)tiles_m, (int)tiles_n, fx, (int)block_n, (int)block_m);
     return check_launch("kvs_project_qkv");
 }
